@@ -1,0 +1,184 @@
+/*
+ * asgd.h — C ABI of the MI355X (gfx950) ASGD mini-batch K-Means library.
+ *
+ * The library runs W independent SGD workers on one GPU.  Every worker streams its
+ * own shard of fp32 samples through mini-batch K-Means steps (nearest prototype,
+ * per-centroid gradient, update) and every E steps sends its state to one other
+ * worker, whose next step merges it under the paper's Parzen-window rule.
+ *
+ * Conventions
+ *   - every function returns ASGD_OK (0) or a negative ASGD_E* code; nothing throws
+ *     or aborts across this boundary; asgd_strerror() names a code;
+ *   - "device pointer" = HIP device memory of the current device, "host pointer" =
+ *     ordinary host memory; the library never frees caller memory;
+ *   - a context belongs to the device that was current in asgd_create(); calls on
+ *     one context must not overlap in time (one context per host thread);
+ *   - there is no CPU fallback: without a usable HIP device the calls fail.
+ *
+ * Notation: k centroids, d dimensions, W workers, b mini-batch size, eps step size,
+ * E exchange interval, H = floor(N / W) shard length, S = floor(H / b) steps per
+ * epoch, t = step counter (the same for all workers, it continues across epochs and
+ * across calls), round r = floor(t / E).
+ */
+#ifndef ASGD_H
+#define ASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct asgd_ctx asgd_ctx; /* opaque: worker states, exchange buffers, counters */
+
+enum {
+    ASGD_OK = 0,
+    ASGD_EINVAL = -1,   /* bad argument (null pointer, size out of range, unknown option) */
+    ASGD_ENOMEM = -2,   /* device or host allocation failed */
+    ASGD_ESTATE = -3,   /* call out of order (e.g. run before load_shards) */
+    ASGD_EHIP = -4,     /* a HIP runtime call failed; asgd_last_hip_error() has its code */
+    ASGD_ESYNC = -5     /* a bounded wait inside a kernel expired (persistent kernels) */
+};
+
+/* Keys of asgd_set_option().  Values are passed as double and rounded to integers
+   where an integer is meant. */
+enum {
+    ASGD_OPT_EXCHANGE_EVERY = 1, /* E >= 0; 0 = never send: silent mode = SimuParallelSGD with
+                                    mini-batches (Sec. 4, first paragraph; Sec. 5.4 "silent");
+                                    E = 1 is Alg. 5 as printed.  Default 0. */
+    ASGD_OPT_SEED = 2,           /* seed of the peer schedule (integer < 2^53).  Default 1. */
+    ASGD_OPT_MODE = 3,           /* ASGD_MODE_*.  Default deterministic. */
+    ASGD_OPT_PARZEN = 4,         /* 1 = gate merges with Eq. 4 (default), 0 = delta = 1 (Eq. 2) */
+    ASGD_OPT_LR_MODE = 5,        /* ASGD_LR_*.  Default constant. */
+    ASGD_OPT_DROP_RATE = 6,      /* test hook: probability in [0,1] that a message is lost on
+                                    the way (Sec. 4.4: a lost message is harmless).  Default 0. */
+    ASGD_OPT_KERNEL = 7,         /* ASGD_KERNEL_*: which implementation runs the steps.
+                                    Default auto.  All give the same results to rounding. */
+    ASGD_OPT_TUNE = 8            /* launch-shape variant of the chosen kernel (0 = default); for
+                                    performance experiments, never changes what is computed */
+};
+enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
+enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };
+enum { ASGD_KERNEL_AUTO = 0, ASGD_KERNEL_GENERIC = 1, ASGD_KERNEL_SMALL = 2, ASGD_KERNEL_MFMA = 3 };
+
+typedef struct asgd_stats {
+    int64_t steps;            /* value of the step counter t */
+    int64_t samples;          /* samples processed so far = t * W * b */
+    int64_t sent;             /* messages written, summed over workers (Alg. 5 line 9) */
+    int64_t received;         /* messages found in a buffer and tested with Eq. 4 */
+    int64_t accepted;         /* of those, messages with delta = 1 ("good" messages, Sec. 5.4) */
+    int64_t parzen_near_ties; /* tested messages with |lhs - rhs| / rhs < 1e-6 in Eq. 4 */
+    int64_t exact_rechecks;   /* samples whose two best fp32 scores were too close to call and
+                                 whose assignment was therefore recomputed in fp64 */
+    double last_run_ms;       /* device time of the last asgd_run_* call (HIP events) */
+    int32_t kernel;           /* ASGD_KERNEL_* that the last run used */
+    int32_t launches;         /* kernel launches of the last run */
+} asgd_stats;
+
+/*
+ * Create a context for the problem of Sec. 5.1 (k prototypes for points in R^d) run by
+ * Alg. 5 with W workers ("nodes"), mini-batch size b and step size eps = lr.
+ * Requires k, d, W, b >= 1 and lr > 0 (Alg. 5 "Require"; W = 1 is allowed and equals
+ * Alg. 4).  Allocates W*k*d floats of state and the exchange buffers on the current
+ * device.  *out is set only on success and must be released with asgd_destroy().
+ */
+int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr);
+
+/* Set one option (see the key list).  Allowed at any time between runs. */
+int asgd_set_option(asgd_ctx *ctx, int key, double value);
+
+/*
+ * Hand the samples to the workers (Sec. 4 "Initialization": the data is split into
+ * packages, one per worker; Alg. 5 lines 1-2).
+ *   x_dev       device pointer, N x d fp32 row-major, at least 8-byte aligned.  BORROWED:
+ *               the caller keeps it alive and unchanged until asgd_destroy() or the
+ *               next asgd_load_shards().
+ *   N           number of rows; worker i owns rows [i*H, (i+1)*H), the last N mod W rows
+ *               are not used by the optimisation.  Requires H >= max(k, b).
+ *   hip_stream  a hipStream_t (0 = default stream) on which this and all later calls of
+ *               the context enqueue their work.
+ * Effects: every worker's state is set to the first k rows of its own shard, exchange
+ * buffers, counters and the step counter are cleared.  Synchronises the stream.
+ */
+int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_stream);
+
+/*
+ * Overwrite worker states from host memory: w_host holds k*d floats (worker >= 0 sets
+ * that worker, worker = -1 gives the same w0 to all workers, Sec. 4 "Initialization") or
+ * W*k*d floats (worker = -2 sets each worker from its own block).  Needed to continue an
+ * earlier run (Sec. 4: w0 may be the result of a run that was stopped early).
+ */
+int asgd_set_state(asgd_ctx *ctx, int worker, const float *w_host);
+
+/* Set the step counter t (>= 0) when continuing an earlier run.  Exchange buffers are
+   emptied; a run resumed at a multiple of E therefore equals the uninterrupted run only
+   if the last message of the earlier run is not needed (E = 0) or t is not a merge point. */
+int asgd_set_step(asgd_ctx *ctx, int64_t t);
+
+/*
+ * Run `epochs` passes over every shard: epochs * S steps of Alg. 5 lines 6-10 per
+ * worker, mini-batch s of an epoch being rows [s*b, (s+1)*b) of the shard (the tail
+ * H mod b is skipped).  A step = assignment s_i(w) (Sec. 5.1), gradient (Eq. 9 with
+ * m' = b), merge of a buffered external state when t > 0 and t mod E == 0 (Eq. 4,
+ * Eq. 7), update w <- w - eps * step (Alg. 5 line 8) and, when (t+1) mod E == 0, the
+ * send of the new state to one other worker (Alg. 5 line 9).  Returns after the work
+ * has finished on the device.
+ */
+int asgd_run_epochs(asgd_ctx *ctx, int epochs);
+
+/* Same, for an arbitrary number of steps (continues inside an epoch). */
+int asgd_run_steps(asgd_ctx *ctx, int64_t steps);
+
+/*
+ * Test aid: record the assignment s_i of every sample processed by later runs.
+ *   assign_dev  device pointer to capacity int32 values, BORROWED, or NULL to stop.
+ * A run of n steps writes n*W*b values, step-major, then worker, then position in the
+ * mini-batch, and fails with ASGD_EINVAL if that exceeds `capacity`.
+ */
+int asgd_set_assign_dump(asgd_ctx *ctx, int32_t *assign_dev, size_t capacity);
+
+/*
+ * Copy states to host memory.  worker >= 0: that worker's k*d floats (worker 0 is the
+ * result Alg. 5 line 11 returns); worker = -1: all W states, W*k*d floats.
+ * out_bytes must be at least the size copied.
+ */
+int asgd_get_state(asgd_ctx *ctx, int worker, float *out_host, size_t out_bytes);
+
+/*
+ * The mean of the W worker states (the alternative final aggregation of Sec. 4.3),
+ * k*d floats, computed on the device in worker order.
+ */
+int asgd_get_mean_state(asgd_ctx *ctx, float *out_host, size_t out_bytes);
+
+/*
+ * Quantization error of Eq. 8, E(w) = sum_i 1/2 * min_k |x_i - w_k|^2, over all N loaded
+ * rows for the state of `worker` (>= 0) or the mean state (worker = -1).  Distances in
+ * fp32 (direct form), summed in fp64.  *out is host memory.
+ */
+int asgd_quant_error(asgd_ctx *ctx, int worker, double *out);
+
+/* Totals since asgd_load_shards(). */
+int asgd_get_stats(asgd_ctx *ctx, asgd_stats *out);
+
+/* Per-worker message counters (Sec. 5.4, "messages sent or received by a single CPU"):
+   each array receives W values; any pointer may be NULL. */
+int asgd_get_worker_counters(asgd_ctx *ctx, int64_t *sent, int64_t *received, int64_t *accepted);
+
+/* Recipient of worker i's message of round r under the deterministic schedule
+   (host-side copy of what the kernels compute; W >= 2). */
+int64_t asgd_schedule_peer(uint64_t seed, int64_t r, int64_t i, int64_t W);
+
+/* hipError_t of the last failed HIP call of this context (0 if none). */
+int asgd_last_hip_error(asgd_ctx *ctx);
+
+/* Release the context and everything it allocated (not the samples, not the dump). */
+void asgd_destroy(asgd_ctx *ctx);
+
+/* Static description of a return code. */
+const char *asgd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASGD_H */

@@ -1,0 +1,421 @@
+// Host side of the C ABI declared in asgd.h: argument checks, device memory of a context,
+// splitting of a run into launches, timing, copies to and from the host.
+#include <math.h>
+#include <new>
+#include <string.h>
+#include <vector>
+
+#include "asgd_internal.h"
+
+using namespace asgd;
+
+struct asgd_ctx {
+    int k = 0, d = 0, W = 0, b = 0;
+    float lr = 0.f;
+    int E = 0;
+    uint64_t seed = 1;
+    int mode = ASGD_MODE_DETERMINISTIC;
+    int parzen = 1;
+    int lr_mode = ASGD_LR_CONST;
+    double drop_rate = 0.0;
+    int kernel_opt = ASGD_KERNEL_AUTO;
+    int tune = 0;
+
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool loaded = false;
+    const float *x = nullptr;
+    long long N = 0, H = 0, S = 0;
+    long long t = 0;
+
+    float *w = nullptr, *slot = nullptr, *acc = nullptr, *xabsmax = nullptr, *mean = nullptr;
+    int *stamp = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
+    long long *ncum = nullptr, *counters = nullptr;
+    double *qpart = nullptr, *qout = nullptr;
+    int32_t *dump = nullptr;
+    size_t dump_cap = 0;
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    double last_ms = 0.0;
+    int last_kernel = 0, last_launches = 0;
+    int hip_err = 0;
+};
+
+namespace {
+
+#define HIP_TRY(ctx, call)                              \
+    do {                                                \
+        hipError_t e__ = (call);                        \
+        if (e__ != hipSuccess) {                        \
+            (ctx)->hip_err = (int)e__;                  \
+            return e__ == hipErrorOutOfMemory ? ASGD_ENOMEM : ASGD_EHIP; \
+        }                                               \
+    } while (0)
+
+size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
+
+void free_all(asgd_ctx *c)
+{
+    void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->cnt, c->assign_tmp,
+                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout};
+    for (void *q : ptrs)
+        if (q) (void)hipFree(q);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
+}
+
+StepParams make_params(const asgd_ctx *c)
+{
+    StepParams p;
+    memset(&p, 0, sizeof(p));
+    p.x = c->x; p.w = c->w; p.slot = c->slot; p.stamp = c->stamp; p.ncum = c->ncum;
+    p.counters = c->counters; p.acc = c->acc; p.cnt = c->cnt; p.assign_tmp = c->assign_tmp;
+    p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->error_flag;
+    p.H = c->H; p.S = c->S; p.t_dump0 = c->t; p.seed = c->seed;
+    p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr;
+    p.parzen = c->parzen; p.lr_mode = c->lr_mode; p.mode = c->mode;
+    p.drop_thr = (uint32_t)llround(c->drop_rate * (double)(1u << 24));
+    p.tune = c->tune;
+    return p;
+}
+
+int clear_exchange(asgd_ctx *c)
+{
+    HIP_TRY(c, hipMemsetAsync(c->slot, 0, 2 * (size_t)c->W * kd_of(c) * sizeof(float), c->stream));
+    HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->W * sizeof(int), c->stream));   // -1
+    return ASGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *asgd_strerror(int code)
+{
+    switch (code) {
+        case ASGD_OK: return "success";
+        case ASGD_EINVAL: return "invalid argument";
+        case ASGD_ENOMEM: return "out of memory";
+        case ASGD_ESTATE: return "call out of order";
+        case ASGD_EHIP: return "HIP runtime error";
+        case ASGD_ESYNC: return "bounded wait inside a kernel expired";
+        default: return "unknown error code";
+    }
+}
+
+int64_t asgd_schedule_peer(uint64_t seed, int64_t r, int64_t i, int64_t W)
+{
+    if (W < 2 || i < 0 || i >= W || r < 0) return -1;
+    return peer_deterministic(seed, r, (int)i, (int)W);
+}
+
+int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
+{
+    if (!out || k < 1 || d < 1 || W < 1 || b < 1 || !(lr > 0.0f) || !isfinite(lr)) return ASGD_EINVAL;
+    if ((double)k * d > (double)(1 << 28) || (double)W * k * d > 4e10) return ASGD_EINVAL;
+    asgd_ctx *c = new (std::nothrow) asgd_ctx();
+    if (!c) return ASGD_ENOMEM;
+    c->k = k; c->d = d; c->W = W; c->b = b; c->lr = lr;
+    int rc = ASGD_OK;
+    auto fail = [&](hipError_t e) {
+        c->hip_err = (int)e;
+        rc = (e == hipErrorOutOfMemory) ? ASGD_ENOMEM : ASGD_EHIP;
+    };
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { delete c; return ASGD_EHIP; }
+    const size_t kd = kd_of(c), Wz = (size_t)W;
+    struct { void **p; size_t bytes; } allocs[] = {
+        {(void **)&c->w, Wz * kd * sizeof(float)},
+        {(void **)&c->slot, 2 * Wz * kd * sizeof(float)},
+        {(void **)&c->acc, Wz * kd * sizeof(float)},
+        {(void **)&c->xabsmax, (size_t)d * sizeof(float)},
+        {(void **)&c->mean, kd * sizeof(float)},
+        {(void **)&c->stamp, 2 * Wz * sizeof(int)},
+        {(void **)&c->cnt, Wz * k * sizeof(int)},
+        {(void **)&c->assign_tmp, Wz * (size_t)b * sizeof(int)},
+        {(void **)&c->error_flag, sizeof(int)},
+        {(void **)&c->ncum, Wz * k * sizeof(long long)},
+        {(void **)&c->counters, Wz * CNT_STRIDE * sizeof(long long)},
+        {(void **)&c->qpart, (size_t)quant_partials_count() * sizeof(double)},
+        {(void **)&c->qout, sizeof(double)},
+    };
+    for (auto &a : allocs) {
+        e = hipMalloc(a.p, a.bytes);
+        if (e != hipSuccess) { fail(e); break; }
+    }
+    if (rc == ASGD_OK && (e = hipEventCreate(&c->ev0)) != hipSuccess) fail(e);
+    if (rc == ASGD_OK && (e = hipEventCreate(&c->ev1)) != hipSuccess) fail(e);
+    if (rc != ASGD_OK) {
+        free_all(c);
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return ASGD_OK;
+}
+
+void asgd_destroy(asgd_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->stream || ctx->loaded) (void)hipStreamSynchronize(ctx->stream);
+    free_all(ctx);
+    delete ctx;
+}
+
+int asgd_last_hip_error(asgd_ctx *ctx) { return ctx ? ctx->hip_err : 0; }
+
+int asgd_set_option(asgd_ctx *ctx, int key, double value)
+{
+    if (!ctx || !isfinite(value)) return ASGD_EINVAL;
+    switch (key) {
+        case ASGD_OPT_EXCHANGE_EVERY:
+            if (value < 0 || value > 2e9 || value != floor(value)) return ASGD_EINVAL;
+            ctx->E = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_SEED:
+            if (value < 0 || value > 9007199254740992.0 || value != floor(value)) return ASGD_EINVAL;
+            ctx->seed = (uint64_t)value;
+            return ASGD_OK;
+        case ASGD_OPT_MODE:
+            if (value != ASGD_MODE_DETERMINISTIC && value != ASGD_MODE_FREE_RUNNING) return ASGD_EINVAL;
+            ctx->mode = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_PARZEN:
+            if (value != 0 && value != 1) return ASGD_EINVAL;
+            ctx->parzen = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_LR_MODE:
+            if (value != ASGD_LR_CONST && value != ASGD_LR_INV_COUNT) return ASGD_EINVAL;
+            ctx->lr_mode = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_DROP_RATE:
+            if (value < 0.0 || value > 1.0) return ASGD_EINVAL;
+            ctx->drop_rate = value;
+            return ASGD_OK;
+        case ASGD_OPT_KERNEL:
+            if (value != ASGD_KERNEL_AUTO && value != ASGD_KERNEL_GENERIC && value != ASGD_KERNEL_SMALL &&
+                value != ASGD_KERNEL_MFMA)
+                return ASGD_EINVAL;
+            ctx->kernel_opt = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_TUNE:
+            if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
+            ctx->tune = (int)value;
+            return ASGD_OK;
+        default:
+            return ASGD_EINVAL;
+    }
+}
+
+int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_stream)
+{
+    if (!ctx || !x_dev || N < 1) return ASGD_EINVAL;
+    if (((uintptr_t)x_dev & 7u) != 0 || ctx->d > 65536) return ASGD_EINVAL;
+    const long long H = N / ctx->W;
+    if (H < ctx->k || H < ctx->b) return ASGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    ctx->x = x_dev; ctx->N = N; ctx->H = H; ctx->S = H / ctx->b;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->t = 0;
+    ctx->loaded = false;
+    StepParams p = make_params(ctx);
+    HIP_TRY(ctx, launch_init_first_k(p, ctx->stream));
+    int rc = clear_exchange(ctx);
+    if (rc != ASGD_OK) return rc;
+    HIP_TRY(ctx, hipMemsetAsync(ctx->ncum, 0, (size_t)ctx->W * ctx->k * sizeof(long long), ctx->stream));
+    HIP_TRY(ctx, hipMemsetAsync(ctx->counters, 0, (size_t)ctx->W * CNT_STRIDE * sizeof(long long), ctx->stream));
+    HIP_TRY(ctx, hipMemsetAsync(ctx->error_flag, 0, sizeof(int), ctx->stream));
+    // per-dimension max |x| over the rows the workers own: input of the rounding-error bound
+    // that decides when an assignment is recomputed exactly
+    HIP_TRY(ctx, launch_absmax(x_dev, H * ctx->W, ctx->d, ctx->xabsmax, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->loaded = true;
+    return ASGD_OK;
+}
+
+int asgd_set_state(asgd_ctx *ctx, int worker, const float *w_host)
+{
+    if (!ctx || !w_host || worker < -2 || worker >= ctx->W) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const size_t kdb = kd_of(ctx) * sizeof(float);
+    if (worker >= 0) {
+        HIP_TRY(ctx, hipMemcpy(ctx->w + (size_t)worker * kd_of(ctx), w_host, kdb, hipMemcpyHostToDevice));
+    } else if (worker == -1) {
+        for (int i = 0; i < ctx->W; ++i)
+            HIP_TRY(ctx, hipMemcpy(ctx->w + (size_t)i * kd_of(ctx), w_host, kdb, hipMemcpyHostToDevice));
+    } else {
+        HIP_TRY(ctx, hipMemcpy(ctx->w, w_host, kdb * ctx->W, hipMemcpyHostToDevice));
+    }
+    return ASGD_OK;
+}
+
+int asgd_set_step(asgd_ctx *ctx, int64_t t)
+{
+    if (!ctx || t < 0) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    ctx->t = t;
+    int rc = clear_exchange(ctx);
+    if (rc != ASGD_OK) return rc;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return ASGD_OK;
+}
+
+int asgd_set_assign_dump(asgd_ctx *ctx, int32_t *assign_dev, size_t capacity)
+{
+    if (!ctx) return ASGD_EINVAL;
+    ctx->dump = assign_dev;
+    ctx->dump_cap = assign_dev ? capacity : 0;
+    return ASGD_OK;
+}
+
+int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
+{
+    if (!ctx || steps < 0) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    if (ctx->lr_mode == ASGD_LR_INV_COUNT && ctx->E != 0) return ASGD_EINVAL;
+    if (ctx->dump && (double)steps * ctx->W * ctx->b > (double)ctx->dump_cap) return ASGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+
+    int kernel = ctx->kernel_opt;
+    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST;
+    if (kernel == ASGD_KERNEL_AUTO) kernel = small_ok ? ASGD_KERNEL_SMALL : ASGD_KERNEL_GENERIC;
+    if (kernel == ASGD_KERNEL_SMALL && !small_ok) return ASGD_EINVAL;
+    if (kernel == ASGD_KERNEL_MFMA) return ASGD_EINVAL;
+
+    StepParams p = make_params(ctx);
+    const long long t_end = ctx->t + steps;
+    // Deterministic mode: a launch never crosses a multiple of E, so the message a worker reads
+    // at the first step of a round was written by an earlier launch on the same stream.
+    const bool split = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
+    int launches = 0;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
+    for (long long ta = ctx->t; ta < t_end;) {
+        long long tb = t_end;
+        if (split) {
+            const long long next = (ta / ctx->E + 1) * (long long)ctx->E;
+            if (next < tb) tb = next;
+        }
+        hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream)
+                                                     : launch_generic_steps(p, ta, tb, ctx->stream);
+        HIP_TRY(ctx, e);
+        ++launches;
+        ta = tb;
+    }
+    HIP_TRY(ctx, hipEventRecord(ctx->ev1, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev0, ctx->ev1));
+    ctx->last_ms = ms;
+    ctx->last_kernel = kernel;
+    ctx->last_launches = launches;
+    ctx->t = t_end;
+    int flag = 0;
+    HIP_TRY(ctx, hipMemcpy(&flag, ctx->error_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag) return ASGD_ESYNC;
+    return ASGD_OK;
+}
+
+int asgd_run_epochs(asgd_ctx *ctx, int epochs)
+{
+    if (!ctx || epochs < 0) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    return asgd_run_steps(ctx, (int64_t)epochs * ctx->S);
+}
+
+int asgd_get_state(asgd_ctx *ctx, int worker, float *out_host, size_t out_bytes)
+{
+    if (!ctx || !out_host || worker < -1 || worker >= ctx->W) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    const size_t kdb = kd_of(ctx) * sizeof(float);
+    const size_t need = worker >= 0 ? kdb : kdb * ctx->W;
+    if (out_bytes < need) return ASGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const float *src = worker >= 0 ? ctx->w + (size_t)worker * kd_of(ctx) : ctx->w;
+    HIP_TRY(ctx, hipMemcpy(out_host, src, need, hipMemcpyDeviceToHost));
+    return ASGD_OK;
+}
+
+int asgd_get_mean_state(asgd_ctx *ctx, float *out_host, size_t out_bytes)
+{
+    if (!ctx || !out_host) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    const size_t kdb = kd_of(ctx) * sizeof(float);
+    if (out_bytes < kdb) return ASGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, launch_mean_state(ctx->w, ctx->W, (int)kd_of(ctx), ctx->mean, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, hipMemcpy(out_host, ctx->mean, kdb, hipMemcpyDeviceToHost));
+    return ASGD_OK;
+}
+
+int asgd_quant_error(asgd_ctx *ctx, int worker, double *out)
+{
+    if (!ctx || !out || worker < -1 || worker >= ctx->W) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    const float *w = ctx->w + (size_t)(worker >= 0 ? worker : 0) * kd_of(ctx);
+    if (worker == -1) {
+        HIP_TRY(ctx, launch_mean_state(ctx->w, ctx->W, (int)kd_of(ctx), ctx->mean, ctx->stream));
+        w = ctx->mean;
+    }
+    HIP_TRY(ctx, launch_quant_error(ctx->x, ctx->N, ctx->d, ctx->k, w, ctx->qpart, ctx->qout, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, hipMemcpy(out, ctx->qout, sizeof(double), hipMemcpyDeviceToHost));
+    return ASGD_OK;
+}
+
+int asgd_get_worker_counters(asgd_ctx *ctx, int64_t *sent, int64_t *received, int64_t *accepted)
+{
+    if (!ctx) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    std::vector<long long> h;
+    try {
+        h.resize((size_t)ctx->W * CNT_STRIDE);
+    } catch (...) {
+        return ASGD_ENOMEM;
+    }
+    HIP_TRY(ctx, hipMemcpy(h.data(), ctx->counters, h.size() * sizeof(long long), hipMemcpyDeviceToHost));
+    for (int i = 0; i < ctx->W; ++i) {
+        if (sent) sent[i] = h[(size_t)i * CNT_STRIDE + CNT_SENT];
+        if (received) received[i] = h[(size_t)i * CNT_STRIDE + CNT_RECEIVED];
+        if (accepted) accepted[i] = h[(size_t)i * CNT_STRIDE + CNT_ACCEPTED];
+    }
+    return ASGD_OK;
+}
+
+int asgd_get_stats(asgd_ctx *ctx, asgd_stats *out)
+{
+    if (!ctx || !out) return ASGD_EINVAL;
+    if (!ctx->loaded) return ASGD_ESTATE;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    std::vector<long long> h;
+    try {
+        h.resize((size_t)ctx->W * CNT_STRIDE);
+    } catch (...) {
+        return ASGD_ENOMEM;
+    }
+    HIP_TRY(ctx, hipMemcpy(h.data(), ctx->counters, h.size() * sizeof(long long), hipMemcpyDeviceToHost));
+    memset(out, 0, sizeof(*out));
+    for (int i = 0; i < ctx->W; ++i) {
+        out->sent += h[(size_t)i * CNT_STRIDE + CNT_SENT];
+        out->received += h[(size_t)i * CNT_STRIDE + CNT_RECEIVED];
+        out->accepted += h[(size_t)i * CNT_STRIDE + CNT_ACCEPTED];
+        out->parzen_near_ties += h[(size_t)i * CNT_STRIDE + CNT_PARZEN_NEAR];
+        out->exact_rechecks += h[(size_t)i * CNT_STRIDE + CNT_RECHECK];
+    }
+    out->steps = ctx->t;
+    out->samples = ctx->t * (long long)ctx->W * ctx->b;
+    out->last_run_ms = ctx->last_ms;
+    out->kernel = ctx->last_kernel;
+    out->launches = ctx->last_launches;
+    return ASGD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of the HIP library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "asgd.h"
+
+namespace asgd {
+
+// ---- counter-based integer generator (published splitmix64 finaliser) --------------------
+// Used for the peer schedule and the message-loss test hook.  Integer only, so host and
+// device agree bit for bit.
+__host__ __device__ inline uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+__host__ __device__ inline uint64_t round_hash(uint64_t seed, int64_t r)
+{
+    return mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(r + 1));
+}
+// Deterministic schedule: one cyclic shift per round, shared by all senders, so that every
+// worker receives exactly one message per round (Alg. 5 line 9 asks only for "a random node
+// other than i").
+__host__ __device__ inline int peer_deterministic(uint64_t seed, int64_t r, int i, int W)
+{
+    uint64_t shift = 1 + round_hash(seed, r) % (uint64_t)(W - 1);
+    return (int)(((uint64_t)i + shift) % (uint64_t)W);
+}
+// Free-running schedule: every sender draws its own recipient; collisions are the data race
+// of Fig. 2 (III) and are allowed.
+__host__ __device__ inline int peer_free(uint64_t seed, int64_t r, int i, int W)
+{
+    uint64_t h = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(i + 1) + 0x5851F42D4C957F2DULL);
+    return (int)(((uint64_t)i + 1 + h % (uint64_t)(W - 1)) % (uint64_t)W);
+}
+__host__ __device__ inline bool message_dropped(uint64_t seed, int64_t r, int sender, uint32_t thr)
+{
+    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1)) >> 40;
+    return u < (uint64_t)thr;
+}
+
+// Per-worker counters kept in device memory.
+enum { CNT_SENT = 0, CNT_RECEIVED = 1, CNT_ACCEPTED = 2, CNT_PARZEN_NEAR = 3, CNT_RECHECK = 4, CNT_STRIDE = 8 };
+
+// Everything a step kernel needs; passed by value.
+struct StepParams {
+    const float *x;        // N x d samples
+    float *w;              // W x k x d states
+    float *slot;           // 2 x W x k x d exchange buffers (parity, worker)
+    int *stamp;            // 2 x W round number of the buffered message, -1 = empty
+    long long *ncum;       // W x k cumulative counts (1/count step size only)
+    long long *counters;   // W x CNT_STRIDE
+    float *acc;            // W x k x d gradient-sum scratch (generic/large kernels)
+    int *cnt;              // W x k count scratch
+    int *assign_tmp;       // W x b assignment scratch
+    int32_t *dump;         // optional assignment dump (step-major), or nullptr
+    const float *xabsmax;  // d per-dimension max |x| over the loaded samples
+    int *error_flag;       // set non-zero by a kernel whose bounded wait expired
+    long long H, S;        // shard length, steps per epoch
+    long long t_dump0;     // step counter value at which the dump buffer starts
+    uint64_t seed;
+    int k, d, W, b, E;
+    float eps;
+    int parzen, lr_mode, mode;
+    uint32_t drop_thr;
+    int tune;              // variant selector for experiments (0 = default)
+};
+
+// Launchers (each returns the hipError_t of its launch).
+hipError_t launch_init_first_k(const StepParams &p, hipStream_t s);
+hipError_t launch_absmax(const float *x, long long rows, int d, float *out, hipStream_t s);
+hipError_t launch_generic_steps(const StepParams &p, long long t0, long long t1, hipStream_t s);
+bool small_kernel_supports(int k, int d, int b);
+hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s);
+hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s);
+// Eq. 8 over rows [0, N): partials is scratch of quant_partials_count() doubles.
+int quant_partials_count();
+hipError_t launch_quant_error(const float *x, long long N, int d, int k, const float *w, double *partials,
+                              double *out, hipStream_t s);
+
+}  // namespace asgd

@@ -1,0 +1,71 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/asgd.h declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1505_04956_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "asgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(asgd_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_functions() == sorted(binding.SYMBOLS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.lib()
+    assert os.path.exists(build.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_no_torch_or_cxx_types_in_signatures():
+    text = open(os.path.join(ROOT, "include", "asgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    assert "torch" not in text and "std::" not in text and "hipStream_t" not in text
+
+
+def test_host_only_entry_points():
+    assert binding.strerror(0) == "success"
+    assert "order" in binding.strerror(binding.ESTATE)
+    assert binding.strerror(-99) == "unknown error code"
+    # schedule: a cyclic shift per round, never to oneself
+    for W in (2, 3, 1024):
+        p = [binding.asgd_schedule_peer(5, 3, i, W) for i in range(W)]
+        assert sorted(p) == list(range(W)) and all(p[i] != i for i in range(W))
+    assert binding.asgd_schedule_peer(5, 3, 0, 1) == -1
+
+
+def test_schedule_agrees_with_oracle(oracle):
+    for W in (2, 7, 4096):
+        for seed in (0, 1, 2**40 + 17):
+            for r in (0, 1, 77):
+                for i in (0, W // 2, W - 1):
+                    assert binding.asgd_schedule_peer(seed, r, i, W) == oracle.peer(seed, r, i, W)
+
+
+def test_argument_checks_need_no_gpu():
+    lib = binding.lib()
+    h = ctypes.c_void_p()
+    assert lib.asgd_create(ctypes.byref(h), 0, 10, 4, 500, 0.05) == binding.EINVAL
+    assert lib.asgd_create(ctypes.byref(h), 10, 10, 4, 500, 0.0) == binding.EINVAL
+    assert lib.asgd_create(None, 10, 10, 4, 500, 0.05) == binding.EINVAL
+    assert lib.asgd_run_steps(None, 1) == binding.EINVAL
+    assert lib.asgd_set_option(None, 1, 1.0) == binding.EINVAL
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1505_04956_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|asgd_oracle|#include\s+\"[^\"]*oracle", text, flags=re.M), f

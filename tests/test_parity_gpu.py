@@ -1,0 +1,203 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bars (deterministic mode):
+  - assignments identical except where the oracle's relative gap (d2-d1)/d1 is < 1e-6
+    (near-ties; counted and printed);
+  - every worker state within 1e-4 relative (Frobenius), quantization error within 1e-4
+    relative; message counters identical unless the oracle flags a Parzen near-tie.
+"""
+import numpy as np
+import pytest
+
+from paper_1505_04956_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+NEAR_TIE = 1e-6
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a HIP device; there is no CPU fallback")
+    from paper_1505_04956_amd import binding
+    binding.lib()
+    return binding
+
+
+def to_dev(X):
+    import torch
+    return torch.from_numpy(X).to("cuda:0")
+
+
+def rel_fro(a, b):
+    a = a.astype(np.float64).reshape(a.shape[0], -1)
+    b = b.astype(np.float64).reshape(b.shape[0], -1)
+    return np.linalg.norm(a - b, axis=1) / np.linalg.norm(b, axis=1)
+
+
+def make_data(N, d, k, seed=3, centres="uniform10", weights="equal", sigma=1.0):
+    wl = workloads.Workload("t", N, d, k, 1, 1, 0.1, 0, 1, sigma, centres, weights, data_seed=seed)
+    return workloads.generate_host(wl)
+
+
+def run_both(B, oracle, X, k, W, b, lr, E, steps, seed=1, parzen=True, drop_rate=0.0, lr_mode=0,
+             kernel=0, tune=0, dump=True, w0=None, check_qe=True):
+    """Run `steps` steps on the GPU and in the oracle; assert the bars; return both."""
+    N, d = X.shape
+    g = B.ASGD(k, d, W, b, lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate, lr_mode=lr_mode,
+               kernel=kernel, tune=tune)
+    g.load_shards(to_dev(X))
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate,
+                          lr_mode=lr_mode, w0=w0)
+    if w0 is not None:
+        g.set_state(-1, np.asarray(w0, dtype=np.float32))
+    if dump:
+        g.enable_assign_dump(steps)
+    g.run_steps(steps)
+    od = o.run_steps(steps, dump=dump)
+    wg = g.get_state()
+    st = g.stats()
+    mism = near = 0
+    if dump:
+        ag = g.assign_dump(steps)
+        ao, gap = od
+        diff = ag != ao
+        mism = int(diff.sum())
+        near = int((gap < NEAR_TIE).sum())
+        bad = diff & ~(gap < NEAR_TIE)
+        assert not bad.any(), "%d assignments differ outside near-ties (min gap %.3g)" % (bad.sum(), gap[bad].min())
+    err = rel_fro(wg, o.w)
+    print("\n[parity] k=%d d=%d W=%d b=%d E=%d steps=%d kernel=%d: max state err %.3g, assign mismatches %d "
+          "(oracle near-ties %d, Parzen near-ties %d), rechecks %d, msgs sent/recv/good gpu %d/%d/%d oracle %d/%d/%d"
+          % (k, d, W, b, E, steps, st.kernel, err.max(), mism, near, o.near[1], st.exact_rechecks,
+             st.sent, st.received, st.accepted, *o.counters.sum(0)))
+    assert np.all(np.isfinite(wg))
+    assert err.max() <= TOL
+    if o.near[1] == 0:
+        assert np.array_equal(g.worker_counters(), o.counters)
+    if check_qe:
+        for wk in sorted({0, W - 1}):
+            qg, qo = g.quant_error(wk), o.quant_error(wk)
+            assert abs(qg - qo) <= TOL * qo, (qg, qo)
+    assert st.steps == steps
+    return g, o
+
+
+# ----------------------------------------------------------------------------------- config 0
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_config0_full(B, oracle, kernel):
+    wl = workloads.CONFIGS[0]
+    X = workloads.generate_host(wl)
+    g, o = run_both(B, oracle, X, wl.k, wl.W, wl.b, wl.lr, wl.E, wl.epochs * wl.S, seed=wl.schedule_seed,
+                    kernel=kernel)
+    assert g.stats().kernel == (2 if kernel == 0 else 1)      # small kernel is the default for k=d=10
+    assert o.counters[:, 2].sum() > 0                          # merges really happened
+
+
+@pytest.mark.parametrize("tune", [1, 2, 3, 4])
+def test_small_kernel_variants(B, oracle, tune):
+    X = make_data(40_000, 10, 10, seed=5)
+    run_both(B, oracle, X, 10, 8, 333, 0.05, 2, 31, kernel=2, tune=tune)
+
+
+# ------------------------------------------------------------------- shapes, tails, edge cases
+@pytest.mark.parametrize("k,d,W,b,E,N", [
+    (5, 7, 3, 130, 2, 3 * 1000 + 2),      # odd d, N not divisible by W, b not a multiple of 64
+    (1, 4, 2, 64, 1, 2 * 640),            # k = 1, exchange after every step (Alg. 5 as printed)
+    (3, 1, 5, 17, 3, 5 * 200 + 4),        # d = 1
+    (16, 16, 4, 256, 4, 4 * 2048),
+    (10, 10, 1, 500, 4, 5000),            # W = 1: nothing to exchange (Alg. 4)
+    (70, 3, 2, 100, 2, 2 * 700),          # k > 64
+])
+def test_generic_shapes(B, oracle, k, d, W, b, E, N):
+    X = make_data(N, d, k, seed=11)
+    H = N // W
+    run_both(B, oracle, X, k, W, b, 0.1, E, 2 * (H // b) + 3, kernel=1)
+
+
+def test_small_kernel_ragged(B, oracle):
+    # b below one group of 64, b = 64 exactly, and a tail of one sample
+    for b in (37, 64, 65, 1000):
+        X = make_data(4 * 3000 + 3, 10, 10, seed=b)
+        run_both(B, oracle, X, 10, 4, b, 0.05, 3, 11, kernel=2)
+
+
+def test_options(B, oracle):
+    X = make_data(24_000, 10, 10, seed=2)
+    for kernel in (1, 2):
+        run_both(B, oracle, X, 10, 6, 200, 0.1, 2, 25, parzen=False, kernel=kernel)
+        run_both(B, oracle, X, 10, 6, 200, 0.1, 2, 25, drop_rate=0.5, kernel=kernel)
+        run_both(B, oracle, X, 10, 6, 200, 0.1, 0, 25, kernel=kernel)
+    run_both(B, oracle, X, 10, 6, 200, 0.1, 0, 25, lr_mode=1, kernel=1)     # 1/count step size
+    w0 = np.random.default_rng(0).uniform(0, 10, size=(10, 10))
+    run_both(B, oracle, X, 10, 6, 200, 0.1, 2, 25, w0=w0.astype(np.float32).astype(np.float64))
+
+
+def test_lost_messages_equal_silent_mode_bitwise(B):
+    X = to_dev(make_data(24_000, 10, 10, seed=2))
+    for kernel in (1, 2):
+        a = B.ASGD(10, 10, 6, 200, 0.1, E=2, drop_rate=1.0, kernel=kernel); a.load_shards(X); a.run_steps(25)
+        s = B.ASGD(10, 10, 6, 200, 0.1, E=0, kernel=kernel); s.load_shards(X); s.run_steps(25)
+        assert np.array_equal(a.get_state(), s.get_state())
+        assert a.stats().sent == 6 * 12 and a.stats().received == 0
+
+
+def test_reproducible_and_resumable(B):
+    X = to_dev(make_data(24_000, 10, 10, seed=4))
+    for kernel in (1, 2):
+        kw = dict(E=3, seed=8, kernel=kernel)
+        full = B.ASGD(10, 10, 6, 200, 0.1, **kw); full.load_shards(X); full.run_steps(40)
+        again = B.ASGD(10, 10, 6, 200, 0.1, **kw); again.load_shards(X); again.run_steps(40)
+        assert np.array_equal(full.get_state(), again.get_state())          # bit for bit
+        a = B.ASGD(10, 10, 6, 200, 0.1, **kw); a.load_shards(X); a.run_steps(10); a.run_steps(7)
+        c = B.ASGD(10, 10, 6, 200, 0.1, **kw); c.load_shards(X)
+        c.set_state(-2, a.get_state()); c.set_step(17)                      # 17 is not a merge point
+        c.run_steps(23)
+        assert np.array_equal(full.get_state(), c.get_state())
+
+
+def test_wider_shapes_generic(B, oracle):
+    # scaled-down relatives of the k=d=100 and the k=1024, d=128 workloads
+    X = make_data(4 * 2000 * 3, 100, 100, seed=6, weights="zipf1.1")
+    run_both(B, oracle, X, 100, 4, 2000, 0.02, 2, 7, kernel=1)
+    X = make_data(2 * 4096 * 2, 128, 1024, seed=7, centres="sphere10")
+    run_both(B, oracle, X, 1024, 2, 4096, 0.01, 2, 4, kernel=1)
+
+
+def test_error_paths(B):
+    import torch
+    with pytest.raises(B.AsgdError):
+        B.asgd_create(0, 10, 4, 500, 0.05)
+    with pytest.raises(B.AsgdError):
+        B.asgd_create(10, 10, 4, 500, -1.0)
+    g = B.ASGD(10, 10, 4, 500, 0.05)
+    with pytest.raises(B.AsgdError) as e:
+        g.run_steps(1)                                   # before load_shards
+    assert e.value.code == B.ESTATE
+    x = torch.zeros((100, 10), device="cuda:0")
+    with pytest.raises(B.AsgdError):
+        g.load_shards(x)                                 # shard shorter than b
+    with pytest.raises(B.AsgdError):
+        g.set_option(B.OPT_MODE, 7)
+    g2 = B.ASGD(10, 10, 2, 10, 0.05, E=2, lr_mode=1)
+    g2.load_shards(torch.rand((100, 10), device="cuda:0"))
+    with pytest.raises(B.AsgdError):
+        g2.run_steps(1)                                  # 1/count step size needs silent mode
+
+
+def test_schedule_matches_oracle(B, oracle):
+    for W in (2, 5, 1024):
+        for r in range(5):
+            for i in (0, 1, W - 1):
+                assert B.asgd_schedule_peer(9, r, i, W) == oracle.peer(9, r, i, W)
+
+
+def test_mean_state(B, oracle):
+    X = make_data(24_000, 10, 10, seed=2)
+    g, o = run_both(B, oracle, X, 10, 6, 200, 0.1, 2, 10)
+    assert np.allclose(g.get_mean_state(), o.w.mean(0), rtol=1e-4, atol=1e-5)
+    qg = g.quant_error(-1)
+    qo = oracle.quant_error(X, o.w.mean(0))
+    assert abs(qg - qo) <= TOL * qo
