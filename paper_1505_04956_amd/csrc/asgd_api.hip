@@ -29,7 +29,7 @@ struct asgd_ctx {
     long long t = 0;
 
     float *w = nullptr, *slot = nullptr, *acc = nullptr, *xabsmax = nullptr, *mean = nullptr;
-    int *stamp = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
+    int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
     long long *ncum = nullptr, *counters = nullptr;
     double *qpart = nullptr, *qout = nullptr;
     int32_t *dump = nullptr;
@@ -56,7 +56,7 @@ size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
 
 void free_all(asgd_ctx *c)
 {
-    void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->cnt, c->assign_tmp,
+    void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->consumed, c->cnt, c->assign_tmp,
                     c->error_flag, c->ncum, c->counters, c->qpart, c->qout};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
@@ -68,7 +68,7 @@ StepParams make_params(const asgd_ctx *c)
 {
     StepParams p;
     memset(&p, 0, sizeof(p));
-    p.x = c->x; p.w = c->w; p.slot = c->slot; p.stamp = c->stamp; p.ncum = c->ncum;
+    p.x = c->x; p.w = c->w; p.slot = c->slot; p.stamp = c->stamp; p.consumed = c->consumed; p.ncum = c->ncum;
     p.counters = c->counters; p.acc = c->acc; p.cnt = c->cnt; p.assign_tmp = c->assign_tmp;
     p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->error_flag;
     p.H = c->H; p.S = c->S; p.t_dump0 = c->t; p.seed = c->seed;
@@ -131,6 +131,7 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
         {(void **)&c->xabsmax, (size_t)d * sizeof(float)},
         {(void **)&c->mean, kd * sizeof(float)},
         {(void **)&c->stamp, 2 * Wz * sizeof(int)},
+        {(void **)&c->consumed, Wz * sizeof(int)},
         {(void **)&c->cnt, Wz * k * sizeof(int)},
         {(void **)&c->assign_tmp, Wz * (size_t)b * sizeof(int)},
         {(void **)&c->error_flag, sizeof(int)},
@@ -287,18 +288,36 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 
     StepParams p = make_params(ctx);
     const long long t_end = ctx->t + steps;
-    // Deterministic mode: a launch never crosses a multiple of E, so the message a worker reads
-    // at the first step of a round was written by an earlier launch on the same stream.
-    const bool split = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
+    // Deterministic mode: a worker may only read the message of round r-1 once its sender has
+    // finished that round.  Either the whole run is one launch of co-resident workgroups that wait
+    // for each other's stamps (small-state kernel), or a launch never crosses a multiple of E, so
+    // that the message was written by an earlier launch on the same stream.
+    const bool rounds = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
     int launches = 0;
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
-    for (long long ta = ctx->t; ta < t_end;) {
+    bool done = false;
+    if (rounds && kernel == ASGD_KERNEL_SMALL && ctx->tune != 3 && steps > 0) {
+        // every worker has passed the merge points before the first step of this run
+        const long long r0 = ctx->t / ctx->E;
+        const int passed = (int)((ctx->t % ctx->E) != 0 ? r0 : (r0 > 0 ? r0 - 1 : 0));
+        HIP_TRY(ctx, hipMemsetD32Async((hipDeviceptr_t)ctx->consumed, passed, (size_t)ctx->W, ctx->stream));
+        hipError_t e = launch_small_steps(p, ctx->t, t_end, ctx->stream, true);
+        if (e == hipSuccess) {
+            done = true;
+            launches = 1;
+        } else if (e == hipErrorCooperativeLaunchTooLarge || e == hipErrorNotSupported) {
+            (void)hipGetLastError();     // fall back to one launch per round
+        } else {
+            HIP_TRY(ctx, e);
+        }
+    }
+    for (long long ta = ctx->t; !done && ta < t_end;) {
         long long tb = t_end;
-        if (split) {
+        if (rounds) {
             const long long next = (ta / ctx->E + 1) * (long long)ctx->E;
             if (next < tb) tb = next;
         }
-        hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream)
+        hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream, false)
                                                      : launch_generic_steps(p, ta, tb, ctx->stream);
         HIP_TRY(ctx, e);
         ++launches;

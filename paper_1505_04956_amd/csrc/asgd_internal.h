@@ -51,6 +51,7 @@ struct StepParams {
     float *w;              // W x k x d states
     float *slot;           // 2 x W x k x d exchange buffers (parity, worker)
     int *stamp;            // 2 x W round number of the buffered message, -1 = empty
+    int *consumed;         // W: last round whose merge point the worker has passed
     long long *ncum;       // W x k cumulative counts (1/count step size only)
     long long *counters;   // W x CNT_STRIDE
     float *acc;            // W x k x d gradient-sum scratch (generic/large kernels)
@@ -74,7 +75,8 @@ hipError_t launch_init_first_k(const StepParams &p, hipStream_t s);
 hipError_t launch_absmax(const float *x, long long rows, int d, float *out, hipStream_t s);
 hipError_t launch_generic_steps(const StepParams &p, long long t0, long long t1, hipStream_t s);
 bool small_kernel_supports(int k, int d, int b);
-hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s);
+// persistent = true: the whole range in one cooperative launch with in-kernel waits between rounds
+hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent);
 hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s);
 // Eq. 8 over rows [0, N): partials is scratch of quant_partials_count() doubles.
 int quant_partials_count();

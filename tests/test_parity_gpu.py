@@ -96,10 +96,10 @@ def test_config0_full(B, oracle, kernel):
     assert o.counters[:, 2].sum() > 0                          # merges really happened
 
 
-@pytest.mark.parametrize("tune", [1, 2, 3, 4])
+@pytest.mark.parametrize("tune", [1, 2])
 def test_small_kernel_variants(B, oracle, tune):
-    X = make_data(40_000, 10, 10, seed=5)
-    run_both(B, oracle, X, 10, 8, 333, 0.05, 2, 31, kernel=2, tune=tune)
+    X = make_data(8 * 4000, 10, 10, seed=5)
+    run_both(B, oracle, X, 10, 8, 1000, 0.05, 2, 9, kernel=2, tune=tune)
 
 
 # ------------------------------------------------------------------- shapes, tails, edge cases
@@ -119,9 +119,29 @@ def test_generic_shapes(B, oracle, k, d, W, b, E, N):
 
 def test_small_kernel_ragged(B, oracle):
     # b below one group of 64, b = 64 exactly, and a tail of one sample
-    for b in (37, 64, 65, 1000):
+    for b in (37, 64, 65, 200, 500, 1000):
         X = make_data(4 * 3000 + 3, 10, 10, seed=b)
         run_both(B, oracle, X, 10, 4, b, 0.05, 3, 11, kernel=2)
+
+
+def test_more_workers_than_resident_workgroups(B, oracle):
+    # a workgroup of the single-launch path then takes several workers through every round
+    X = make_data(2500 * 200 + 7, 10, 10, seed=9)
+    g, o = run_both(B, oracle, X, 10, 2500, 64, 0.05, 2, 7, kernel=2, drop_rate=0.25)
+    assert g.stats().launches == 1
+
+
+def test_single_launch_equals_one_launch_per_round(B):
+    X = to_dev(make_data(16 * 4000, 10, 10, seed=12))
+    res = []
+    for tune in (0, 3):      # 3 = end every launch at a multiple of E instead of waiting inside the kernel
+        g = B.ASGD(10, 10, 16, 1000, 0.05, E=2, seed=3, kernel=2, tune=tune)
+        g.load_shards(X)
+        g.run_steps(5)
+        g.run_steps(6)
+        res.append((g.get_state(), g.worker_counters(), g.stats().launches))
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+    assert res[0][2] == 1 and res[1][2] > 1
 
 
 def test_options(B, oracle):
