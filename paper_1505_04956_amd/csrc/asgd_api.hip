@@ -296,7 +296,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     int launches = 0;
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
     bool done = false;
-    if (rounds && kernel == ASGD_KERNEL_SMALL && ctx->tune != 3 && steps > 0) {
+    if (rounds && kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3 && steps > 0) {
         // every worker has passed the merge points before the first step of this run
         const long long r0 = ctx->t / ctx->E;
         const int passed = (int)((ctx->t % ctx->E) != 0 ? r0 : (r0 > 0 ? r0 - 1 : 0));

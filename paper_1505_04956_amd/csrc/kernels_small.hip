@@ -81,6 +81,12 @@ __device__ __forceinline__ bool wait_flag(const int *flag, int want, bool at_lea
 }
 
 // Steps [t0, t1) of the workers blockIdx.x, blockIdx.x + gridDim.x, ...
+//   NW   wavefronts per worker: wave v takes the groups v, v+NW, ... of every mini-batch.
+//        NW = 1: a lane owns one accumulator row per centroid and its read-modify-write is
+//                software-pipelined (the row is read one group before it is added to);
+//        NW = 2: lanes l and l+32 share a row and update it one after the other, which halves
+//                the LDS per wave so that two waves per SIMD are resident and hide each other's
+//                latencies.
 //   sync = 0: the launch contains nothing a worker has to wait for (silent or free-running mode,
 //             or the host ends every launch at a multiple of E); one workgroup per worker.
 //   sync = 1: the whole run is one launch of co-resident workgroups.  A workgroup takes its workers
@@ -89,43 +95,44 @@ __device__ __forceinline__ bool wait_flag(const int *flag, int want, bool at_lea
 //             of the previous round), and a sender waits until the recipient has consumed the older
 //             message that sits in the same buffer.  Every wait is on an earlier round, so the
 //             waits cannot form a cycle.
-template <int K, int D, int PF>
-__global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
+template <int K, int D, int PF, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW))) void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 {
     constexpr int KD = K * D;
-    constexpr int ROWF = (D + 1 + 3) / 4 * 4;       // floats per accumulator row: d sums, count, padding
-    constexpr int NQ = ROWF / 4;                    // float4 per row
+    constexpr int NQ = (D + 1 + 3) / 4;             // float4 per accumulator row: d sums, count, padding
     constexpr int NT = K * NQ;                      // reduction tasks: one float4 column each
-    constexpr int NPART = 64 / NT;                  // lanes sharing a task split the 64 rows
+    constexpr int NPART = 64 / NT;                  // lanes sharing a task split the rows
     constexpr int NSLOT = (KD + 63) / 64;           // state elements a lane owns (element e = slot*64 + lane)
+    constexpr int RL = 64 / NW;                     // accumulator rows per centroid and wave
+    constexpr int RPP = RL / NPART;                 // rows one lane sums in the reduction
+    static_assert(NW == 1 || NW == 2, "one or two waves per worker");
     static_assert(PF >= 2, "the ring needs the previous group's buffer");
-    static_assert(NT <= 64 && NPART >= 1 && 64 % NPART == 0, "state too large for this kernel");
-    static_assert(ROWF % 4 == 0 && ((ROWF / 4) % 2) == 1, "row stride must be an odd number of 16-byte units");
+    static_assert(NT <= 64 && NPART >= 1 && RL % NPART == 0 && RPP % 2 == 0, "state too large for this kernel");
 
-    __shared__ __attribute__((aligned(16))) float acc[(K + 1) * 64 * ROWF];   // row K: scratch for masked lanes
-    __shared__ __attribute__((aligned(16))) float wbc[KD];                    // state, wave-uniform reads
-    __shared__ __attribute__((aligned(16))) float sq[KD];
-    __shared__ __attribute__((aligned(16))) float part[NPART][NT][4];
+    // acc[wave][row][q][r]: float4 number q of the row that lane r (NW = 2: lanes r and r+32) keeps for
+    // centroid `row`; row K is scratch for masked lanes.  Consecutive lanes are 16 bytes apart.
+    __shared__ float4 acc[NW][K + 1][NQ][RL];
+    __shared__ __attribute__((aligned(16))) float wbc[NW][KD];   // state, wave-uniform reads, one copy per wave
+    __shared__ __attribute__((aligned(16))) float sq[NW][KD];
+    __shared__ float4 part[2][NW][NPART][NT];                    // per-wave totals, double-buffered by step parity
 
-    const int lane = threadIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int b = p.b;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
     const bool rounds = (p.E > 0 && p.W > 1 && det);   // work is cut at multiples of E
     const float inv_b = 1.0f / (float)b;
-    // groups of 64 samples per mini-batch, rounded up to a multiple of the ring depth (the extra
-    // groups are fully masked)
-    const int ngroups = ((b + 63) / 64 + PF - 1) / PF * PF;
+    // groups of 64 samples per mini-batch and wave, rounded up to a multiple of the ring depth (the
+    // extra groups are fully masked); group m of wave v covers samples [(v + m*NW)*64, +64)
+    const int ngw = (((b + 63) / 64 + NW - 1) / NW + PF - 1) / PF * PF;
 
     float sum_xmax = 0.0f;
 #pragma unroll
     for (int j = 0; j < D; ++j) sum_xmax += p.xabsmax[j];
-    {
-        float4 *a4 = reinterpret_cast<float4 *>(acc);
-        for (int q = lane; q < (K + 1) * 64 * NQ; q += 64) a4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int q = lane; q < (K + 1) * NQ * RL; q += 64) (&acc[wave][0][0][0])[q] = make_float4(0.f, 0.f, 0.f, 0.f);
 
     long long rechecks = 0;
     int wait_failed = 0;
+    int parity = 0;
 
     // first work item: worker i, steps [ta, tb)
     int i = blockIdx.x;
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
     long long tb = rounds ? min(t1, (ta / p.E + 1) * (long long)p.E) : t1;
     long long s_seg = ta % p.S;                     // position of step ta inside the epoch
 
-    // ring of sample buffers: buffer u holds group g with g % PF == u
+    // ring of sample buffers: buffer u holds this wave's group m with m % PF == u
     float xr[PF][D];
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
@@ -143,8 +150,8 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
     {
         const float *x0 = p.x + ((size_t)i * p.H + (size_t)s_seg * b) * D;
 #pragma unroll
-        for (int u = 0; u + 1 < PF; ++u) {
-            const int n = u * 64 + lane;
+        for (int u = 0; u < (NW == 1 ? PF - 1 : PF); ++u) {
+            const int n = (wave + u * NW) * 64 + lane;
             load_row<D>(xr[u], x0 + (size_t)(n < b ? n : b - 1) * D);
         }
     }
@@ -183,19 +190,19 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
             for (int q = 0; q < NSLOT; ++q) {
                 const int e = q * 64 + lane;
                 if (e < KD) {
-                    wbc[e] = wl[q];
-                    sq[e] = wl[q] * wl[q];
+                    wbc[wave][e] = wl[q];
+                    sq[wave][e] = wl[q] * wl[q];
                 }
                 wabs = fmaxf(wabs, fabsf(wl[q]));
             }
             __syncthreads();
             float wv[KD];
 #pragma unroll
-            for (int e = 0; e < KD; ++e) wv[e] = wbc[e];
+            for (int e = 0; e < KD; ++e) wv[e] = wbc[wave][e];
             float hl = 0.0f;
             if (lane < K) {
 #pragma unroll
-                for (int j = 0; j < D; ++j) hl += sq[lane * D + j];
+                for (int j = 0; j < D; ++j) hl += sq[wave][lane * D + j];
             }
             hl *= -0.5f;
             float hn[K];
@@ -216,18 +223,20 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
             const float *xb = xs + (size_t)s_epoch * b * D;                       // this mini-batch
             const float *xbn = (t + 1 < tb) ? xs + (size_t)s_next * b * D : x_after;   // the one after it
 
-            // pending read-modify-write: row pointer and row content of the group before the current one
-            float4 *prow = reinterpret_cast<float4 *>(&acc[(K * 64 + lane) * ROWF]);
+            // NW = 1: pending read-modify-write (row pointer and content) of the group before the current one
+            float4 *prow = &acc[wave][K][0][lane % RL];
             float4 pr[NQ];
+            if constexpr (NW == 1) {
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) pr[q] = prow[q];
+                for (int q = 0; q < NQ; ++q) pr[q] = prow[q * RL];
+            }
 
-            for (int g0 = 0; g0 < ngroups; g0 += PF) {
+            for (int m0 = 0; m0 < ngw; m0 += PF) {
 #pragma unroll
                 for (int u = 0; u < PF; ++u) {
                     const int up = (u + PF - 1) % PF;           // buffer of the previous group
-                    const int g = g0 + u;
-                    const int n = g * 64 + lane;
+                    const int m = m0 + u;
+                    const int n = (wave + m * NW) * 64 + lane;
                     const float(&xc)[D] = xr[u];
 
                     float best = -INFINITY, second = -INFINITY;
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
                             double sd = 0.0;
 #pragma unroll
                             for (int j = 0; j < D; ++j) {
-                                double diff = (double)xe[j] - (double)wbc[c * D + j];
+                                double diff = (double)xe[j] - (double)wbc[wave][c * D + j];
                                 sd += diff * diff;
                             }
                             if (sd < dbest) { dbest = sd; darg = c; }
@@ -266,62 +275,79 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
                     }
                     if (p.dump && valid) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
 
-                    // finish the previous group's row: add its sample (still in buffer `up`), write back
-                    {
-                        float *rf = reinterpret_cast<float *>(pr);
+                    if constexpr (NW == 1) {
+                        // finish the previous group's row: add its sample (still in buffer `up`), write back
+                        {
+                            float *rf = reinterpret_cast<float *>(pr);
 #pragma unroll
-                        for (int j = 0; j < D; ++j) rf[j] += xr[up][j];
-                        rf[D] += 1.0f;
+                            for (int j = 0; j < D; ++j) rf[j] += xr[up][j];
+                            rf[D] += 1.0f;
 #pragma unroll
-                        for (int q = 0; q < NQ; ++q) prow[q] = pr[q];
+                            for (int q = 0; q < NQ; ++q) prow[q * RL] = pr[q];
+                        }
+                        // start this group's row
+                        prow = &acc[wave][valid ? arg : K][0][lane];
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q) pr[q] = prow[q * RL];
+                    } else {
+                        // lanes l and l+32 share a row: lower half first, then upper half
+                        float4 *row = &acc[wave][valid ? arg : K][0][lane % RL];
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            if ((lane >> 5) == h) {
+                                float4 rr[NQ];
+#pragma unroll
+                                for (int q = 0; q < NQ; ++q) rr[q] = row[q * RL];
+                                float *rf = reinterpret_cast<float *>(rr);
+#pragma unroll
+                                for (int j = 0; j < D; ++j) rf[j] += xc[j];
+                                rf[D] += 1.0f;
+#pragma unroll
+                                for (int q = 0; q < NQ; ++q) row[q * RL] = rr[q];
+                            }
+                        }
                     }
-                    // buffer `up` is free now: refill it with the group PF-1 turns ahead
+                    // refill a free buffer with the group PF-1 (NW = 1) or PF (NW = 2) turns ahead
                     {
-                        const int gg = g + PF - 1;
-                        const bool same = gg < ngroups;
+                        constexpr int ahead = (NW == 1) ? PF - 1 : PF;
+                        const int mm = m + ahead;
+                        const bool same = mm < ngw;
                         const float *src = same ? xb : xbn;
-                        const int nn = (same ? gg : gg - ngroups) * 64 + lane;
-                        load_row<D>(xr[up], src + (size_t)(nn < b ? nn : b - 1) * D);
+                        const int nn = (wave + (same ? mm : mm - ngw) * NW) * 64 + lane;
+                        load_row<D>(xr[NW == 1 ? up : u], src + (size_t)(nn < b ? nn : b - 1) * D);
                     }
-                    // start this group's row
-                    prow = reinterpret_cast<float4 *>(&acc[((valid ? arg : K) * 64 + lane) * ROWF]);
-#pragma unroll
-                    for (int q = 0; q < NQ; ++q) pr[q] = prow[q];
                 }
             }
-            // finish the last group of the mini-batch (buffer PF-1)
-            {
+            if constexpr (NW == 1) {
+                // finish the last group of the mini-batch (buffer PF-1)
                 float *rf = reinterpret_cast<float *>(pr);
 #pragma unroll
                 for (int j = 0; j < D; ++j) rf[j] += xr[PF - 1][j];
                 rf[D] += 1.0f;
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) prow[q] = pr[q];
+                for (int q = 0; q < NQ; ++q) prow[q * RL] = pr[q];
             }
             __syncthreads();
 
-            // ---- sum the 64 rows of every centroid in a fixed order, clear them ----
+            // ---- sum the rows of every centroid in a fixed order, clear them ----
             // lane = (part, task): task = one float4 column (centroid c, quarter q4); part = its share of the rows
             {
                 const int task = lane % NT, prt = lane / NT;
                 if (prt < NPART) {
-                    constexpr int ROWS = 64 / NPART;
                     const int c = task / NQ, q4 = task % NQ;
+                    float4 *col = &acc[wave][c][q4][prt * RPP];
                     float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
 #pragma unroll
-                    for (int r = 0; r < ROWS; r += 2) {
-                        float4 *a0 = reinterpret_cast<float4 *>(&acc[((c * 64) + prt * ROWS + r) * ROWF]) + q4;
-                        float4 *a1 = reinterpret_cast<float4 *>(&acc[((c * 64) + prt * ROWS + r + 1) * ROWF]) + q4;
-                        const float4 v0 = *a0, v1 = *a1;
-                        *a0 = make_float4(0.f, 0.f, 0.f, 0.f);
-                        *a1 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int r = 0; r < RPP; r += 2) {
+                        // start at a task-dependent row so that the lanes of one access hit different banks
+                        const int r0 = (r + task) % RPP, r1 = (r + 1 + task) % RPP;
+                        const float4 v0 = col[r0], v1 = col[r1];
+                        col[r0] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        col[r1] = make_float4(0.f, 0.f, 0.f, 0.f);
                         s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
                         s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
                     }
-                    part[prt][task][0] = s0.x + s1.x;
-                    part[prt][task][1] = s0.y + s1.y;
-                    part[prt][task][2] = s0.z + s1.z;
-                    part[prt][task][3] = s0.w + s1.w;
+                    part[parity][wave][prt][task] = make_float4(s0.x + s1.x, s0.y + s1.y, s0.z + s1.z, s0.w + s1.w);
                 }
             }
             __syncthreads();
@@ -332,15 +358,17 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
                 float sv = 0.0f, cv = 0.0f;
                 if (e < KD) {
                     const int c = e / D, j = e % D;
+                    const float *pf = reinterpret_cast<const float *>(&part[parity][0][0][0]);
 #pragma unroll
-                    for (int v = 0; v < NPART; ++v) {
-                        sv += part[v][c * NQ + j / 4][j % 4];
-                        cv += part[v][c * NQ + D / 4][D % 4];
+                    for (int v = 0; v < NW * NPART; ++v) {      // waves, then parts: one fixed order
+                        sv += pf[(v * NT + c * NQ + j / 4) * 4 + j % 4];
+                        cv += pf[(v * NT + c * NQ + D / 4) * 4 + D % 4];
                     }
                 }
                 S[q] = sv;
                 cntv[q] = cv;
             }
+            parity ^= 1;
 
             // ---- merge point? (a buffer is looked at once, at the first step of a round) ----
             const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && te == 0);
@@ -377,11 +405,11 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
                 }
             }
             int delta = 0;
-            if (has_ext) {           // uniform over the wave
+            if (has_ext) {           // uniform over the workgroup
                 lhs = wave_sum(lhs); rhs = wave_sum(rhs); nrm = wave_sum(nrm);
                 if (nrm > 0.0) {     // lambda of Eq. 3: an all-zero buffer is empty
                     delta = p.parzen ? (lhs < rhs) : 1;       // Eq. 4
-                    if (lane == 0) {
+                    if (threadIdx.x == 0) {
                         long long *cn = p.counters + (size_t)i * CNT_STRIDE;
                         cn[CNT_RECEIVED] += 1;
                         cn[CNT_ACCEPTED] += delta;
@@ -397,16 +425,17 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
                 wl[q] = wl[q] - p.eps * step;
             }
             if (merge_point) {
-                // the buffer has been read: empty it and tell senders of later rounds so
+                // every wave has read the buffer: empty it and tell senders of later rounds so
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                if (lane == 0) {
+                if constexpr (NW > 1) __syncthreads();
+                if (threadIdx.x == 0) {
                     __hip_atomic_store(p.stamp + (size_t)rpar * p.W + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     __hip_atomic_store(p.consumed + i, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
 
-            // ---- send (Alg. 5 line 9) ----
-            if (p.E > 0 && p.W > 1 && te + 1 == p.E) {
+            // ---- send (Alg. 5 line 9): the first wave writes ----
+            if (p.E > 0 && p.W > 1 && te + 1 == p.E && wave == 0) {
                 if (!message_dropped(p.seed, round, i, p.drop_thr)) {
                     const int peer = det ? peer_deterministic(p.seed, round, i, p.W) : peer_free(p.seed, round, i, p.W);
                     const int spar = det ? (int)(round & 1) : 0;
@@ -434,12 +463,15 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
             if (p.E > 0 && ++te == p.E) { te = 0; ++round; }
         }
 
+        if (wave == 0) {
 #pragma unroll
-        for (int q = 0; q < NSLOT; ++q) {
-            const int e = q * 64 + lane;
-            if (e < KD) p.w[(size_t)i * KD + e] = wl[q];
+            for (int q = 0; q < NSLOT; ++q) {
+                const int e = q * 64 + lane;
+                if (e < KD) p.w[(size_t)i * KD + e] = wl[q];
+            }
         }
         if (!has_next) break;
+        if constexpr (NW > 1) __syncthreads();      // the other wave reloads the state written above
         i = next_i;
         if (next_ta != ta) {
             ta = next_ta;
@@ -455,12 +487,12 @@ __global__ __launch_bounds__(64) void small_steps_kernel(StepParams p, long long
     if (lane == 0 && wait_failed) atomicOr(p.error_flag, 1);
 }
 
-template <int K, int D, int PF>
+template <int K, int D, int PF, int NW>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
-    auto kern = small_steps_kernel<K, D, PF>;
+    auto kern = small_steps_kernel<K, D, PF, NW>;
     if (!persistent) {
-        hipLaunchKernelGGL(kern, dim3(p.W), dim3(64), 0, s, p, t0, t1, 0);
+        hipLaunchKernelGGL(kern, dim3(p.W), dim3(64 * NW), 0, s, p, t0, t1, 0);
         return hipGetLastError();
     }
     // one launch for the whole run: every workgroup must be resident at the same time
@@ -468,7 +500,7 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipSt
     hipDeviceProp_t prop;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NW, 0);
     if (e != hipSuccess) return e;
     const long long capacity = (long long)per_cu * prop.multiProcessorCount;
     if (capacity < 1) return hipErrorCooperativeLaunchTooLarge;
@@ -477,7 +509,7 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipSt
     long long a0 = t0, a1 = t1;
     int sync = 1;
     void *args[] = {&pp, &a0, &a1, &sync};
-    return hipLaunchCooperativeKernel((const void *)kern, dim3(grid), dim3(64), args, 0, s);
+    return hipLaunchCooperativeKernel((const void *)kern, dim3(grid), dim3(64 * NW), args, 0, s);
 }
 
 }  // namespace
@@ -491,16 +523,26 @@ bool small_kernel_supports(int k, int d, int b)
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
     if (!(p.k == 10 && p.d == 10)) return hipErrorInvalidValue;
-    const int ngroups = (p.b + 63) / 64;
-    // ring depth: the largest of 8, 4 that divides the number of groups per mini-batch, else 2
-    // (the kernel then pads an odd group count with one masked group)
-    int pf = (ngroups % 8 == 0) ? 8 : (ngroups % 4 == 0) ? 4 : 2;
-    if (p.tune == 1 && pf > 4) pf = 4;
-    if (p.tune == 2 && pf > 2) pf = 2;
+    // tune: bit 2 (value 4) = one wave per worker; bits 0-1 limit the ring depth (1: 4, 2: 2); 3 is
+    // handled by the caller (one launch per round)
+    const int nw = (p.tune & 4) ? 1 : 2;
+    const int ngw = ((p.b + 63) / 64 + nw - 1) / nw;
+    // ring depth: the largest of 8, 4 that divides the number of groups per mini-batch and wave, else 2
+    // (the kernel then pads the group count with masked groups)
+    int pf = (ngw % 8 == 0) ? 8 : (ngw % 4 == 0) ? 4 : 2;
+    if (nw == 2 && pf > 4) pf = 4;                 // two waves per SIMD: 256 registers each
+    if ((p.tune & 3) == 1 && pf > 4) pf = 4;
+    if ((p.tune & 3) == 2 && pf > 2) pf = 2;
+    if (nw == 1) {
+        switch (pf) {
+            case 8: return launch_variant<10, 10, 8, 1>(p, t0, t1, s, persistent);
+            case 4: return launch_variant<10, 10, 4, 1>(p, t0, t1, s, persistent);
+            default: return launch_variant<10, 10, 2, 1>(p, t0, t1, s, persistent);
+        }
+    }
     switch (pf) {
-        case 8: return launch_variant<10, 10, 8>(p, t0, t1, s, persistent);
-        case 4: return launch_variant<10, 10, 4>(p, t0, t1, s, persistent);
-        default: return launch_variant<10, 10, 2>(p, t0, t1, s, persistent);
+        case 4: return launch_variant<10, 10, 4, 2>(p, t0, t1, s, persistent);
+        default: return launch_variant<10, 10, 2, 2>(p, t0, t1, s, persistent);
     }
 }
 

@@ -96,7 +96,7 @@ def test_config0_full(B, oracle, kernel):
     assert o.counters[:, 2].sum() > 0                          # merges really happened
 
 
-@pytest.mark.parametrize("tune", [1, 2])
+@pytest.mark.parametrize("tune", [1, 2, 4, 5, 6])   # ring depths, one or two waves per worker
 def test_small_kernel_variants(B, oracle, tune):
     X = make_data(8 * 4000, 10, 10, seed=5)
     run_both(B, oracle, X, 10, 8, 1000, 0.05, 2, 9, kernel=2, tune=tune)
@@ -134,14 +134,16 @@ def test_more_workers_than_resident_workgroups(B, oracle):
 def test_single_launch_equals_one_launch_per_round(B):
     X = to_dev(make_data(16 * 4000, 10, 10, seed=12))
     res = []
-    for tune in (0, 3):      # 3 = end every launch at a multiple of E instead of waiting inside the kernel
+    for tune in (0, 3, 4, 7):   # +3 = end every launch at a multiple of E instead of waiting inside the kernel
         g = B.ASGD(10, 10, 16, 1000, 0.05, E=2, seed=3, kernel=2, tune=tune)
         g.load_shards(X)
         g.run_steps(5)
         g.run_steps(6)
         res.append((g.get_state(), g.worker_counters(), g.stats().launches))
-    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
-    assert res[0][2] == 1 and res[1][2] > 1
+    for a, c in ((0, 1), (2, 3)):
+        assert np.array_equal(res[a][0], res[c][0]) and np.array_equal(res[a][1], res[c][1])
+        assert res[a][2] == 1 and res[c][2] > 1
+    assert np.allclose(res[0][0], res[2][0], rtol=1e-5)      # one or two waves per worker: other summation order
 
 
 def test_options(B, oracle):
