@@ -55,8 +55,13 @@ enum {
                                     the way (Sec. 4.4: a lost message is harmless).  Default 0. */
     ASGD_OPT_KERNEL = 7,         /* ASGD_KERNEL_*: which implementation runs the steps.
                                     Default auto.  All give the same results to rounding. */
-    ASGD_OPT_TUNE = 8            /* launch-shape variant of the chosen kernel (0 = default); for
+    ASGD_OPT_TUNE = 8,           /* launch-shape variant of the chosen kernel (0 = default); for
                                     performance experiments, never changes what is computed */
+    ASGD_OPT_COOPERATIVE = 9     /* 1 (default): a run that needs all its workgroups resident at the
+                                    same time is started with a cooperative launch, which refuses
+                                    grids that cannot be; 0: plain launch of the same grid (for tools
+                                    that cannot follow cooperative launches).  The in-kernel waits are
+                                    bounded either way. */
 };
 enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
 enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };
@@ -157,6 +162,10 @@ int asgd_get_mean_state(asgd_ctx *ctx, float *out_host, size_t out_bytes);
  * fp32 (direct form), summed in fp64.  *out is host memory.
  */
 int asgd_quant_error(asgd_ctx *ctx, int worker, double *out);
+
+/* Device time in milliseconds of the last asgd_run_* call, measured with HIP events recorded on
+   the context's stream around its kernel launches.  No device access. */
+int asgd_last_run_ms(asgd_ctx *ctx, double *out);
 
 /* Totals since asgd_load_shards(). */
 int asgd_get_stats(asgd_ctx *ctx, asgd_stats *out);

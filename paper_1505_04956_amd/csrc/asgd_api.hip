@@ -20,6 +20,7 @@ struct asgd_ctx {
     double drop_rate = 0.0;
     int kernel_opt = ASGD_KERNEL_AUTO;
     int tune = 0;
+    int cooperative = 1;
 
     int device = 0;
     hipStream_t stream = nullptr;
@@ -76,6 +77,7 @@ StepParams make_params(const asgd_ctx *c)
     p.parzen = c->parzen; p.lr_mode = c->lr_mode; p.mode = c->mode;
     p.drop_thr = (uint32_t)llround(c->drop_rate * (double)(1u << 24));
     p.tune = c->tune;
+    p.cooperative = c->cooperative;
     return p;
 }
 
@@ -198,6 +200,10 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
                 value != ASGD_KERNEL_MFMA)
                 return ASGD_EINVAL;
             ctx->kernel_opt = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_COOPERATIVE:
+            if (value != 0 && value != 1) return ASGD_EINVAL;
+            ctx->cooperative = (int)value;
             return ASGD_OK;
         case ASGD_OPT_TUNE:
             if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
@@ -405,6 +411,13 @@ int asgd_get_worker_counters(asgd_ctx *ctx, int64_t *sent, int64_t *received, in
         if (received) received[i] = h[(size_t)i * CNT_STRIDE + CNT_RECEIVED];
         if (accepted) accepted[i] = h[(size_t)i * CNT_STRIDE + CNT_ACCEPTED];
     }
+    return ASGD_OK;
+}
+
+int asgd_last_run_ms(asgd_ctx *ctx, double *out)
+{
+    if (!ctx || !out) return ASGD_EINVAL;
+    *out = ctx->last_ms;
     return ASGD_OK;
 }
 

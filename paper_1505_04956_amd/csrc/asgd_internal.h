@@ -68,6 +68,7 @@ struct StepParams {
     int parzen, lr_mode, mode;
     uint32_t drop_thr;
     int tune;              // variant selector for experiments (0 = default)
+    int cooperative;       // use the cooperative launch API for single-launch runs
 };
 
 // Launchers (each returns the hipError_t of its launch).

@@ -496,20 +496,29 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipSt
         return hipGetLastError();
     }
     // one launch for the whole run: every workgroup must be resident at the same time
-    int dev = 0, per_cu = 0;
-    hipDeviceProp_t prop;
+    // resident workgroups of this kernel on the current device (queried once per device and variant)
+    static long long cached_capacity[64] = {0};
+    int dev = 0;
     hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NW, 0);
     if (e != hipSuccess) return e;
-    const long long capacity = (long long)per_cu * prop.multiProcessorCount;
+    long long capacity = (dev >= 0 && dev < 64) ? cached_capacity[dev] : 0;
+    if (capacity == 0) {
+        int per_cu = 0, cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NW, 0);
+        if (e != hipSuccess) return e;
+        capacity = (long long)per_cu * cus;
+        if (dev >= 0 && dev < 64) cached_capacity[dev] = capacity;
+    }
     if (capacity < 1) return hipErrorCooperativeLaunchTooLarge;
     const int grid = (int)(p.W < capacity ? p.W : capacity);
     StepParams pp = p;
     long long a0 = t0, a1 = t1;
     int sync = 1;
     void *args[] = {&pp, &a0, &a1, &sync};
-    return hipLaunchCooperativeKernel((const void *)kern, dim3(grid), dim3(64 * NW), args, 0, s);
+    if (p.cooperative) return hipLaunchCooperativeKernel((const void *)kern, dim3(grid), dim3(64 * NW), args, 0, s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), 0, s, pp, a0, a1, sync);
+    return hipGetLastError();
 }
 
 }  // namespace
