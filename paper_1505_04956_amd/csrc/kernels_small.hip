@@ -1,21 +1,28 @@
-// Step kernel for small states (k*d of the order of 100): the streaming workloads.
+// Step kernel for small states (k <= 16, k*d of the order of 100): the streaming workloads.
 //
-// One wavefront per worker.  A lane takes one sample at a time:
-//   - the sample's d floats come straight from HBM into registers through a ring of PF
-//     register buffers, so that PF-1 groups of 64 samples are in flight per wave; the ring
-//     runs across mini-batch boundaries (the addresses of the next mini-batch do not depend on
+// One workgroup of NW wavefronts per worker; a lane takes one sample at a time:
+//   - the sample's d floats come straight from HBM into registers through a ring of PF register
+//     buffers, so that PF-1 groups of 64 samples are in flight per wave; the ring runs across
+//     mini-batch, round and worker boundaries (the addresses of later mini-batches do not depend on
 //     the state), so the update between two mini-batches overlaps with loads;
-//   - the k scores x.w_k - |w_k|^2/2 (largest score = nearest centroid, the |x|^2 term is
-//     common to all k) are fused multiply-add chains against a wave-uniform copy of the state
-//     held in registers;
-//   - the two best scores are tracked; when they are closer than a rigorous bound on the fp32
-//     rounding error of the scores, the lane recomputes its assignment exactly (fp64, direct
-//     form), so the assignment is the exact-arithmetic nearest centroid of the fp32 state;
-//   - the gradient sums of Eq. 9 are kept per lane in LDS: row (centroid, lane) holds the d
-//     sums and the count; a lane reads its row, adds its sample and writes the row back (plain
-//     128-bit LDS accesses; the 48-byte lane stride keeps them free of bank conflicts).  The
-//     read is issued one group ahead of the add.  Lanes past the end of a mini-batch use a
-//     scratch row.  A fixed-order reduction over the 64 lanes follows once per step.
+//   - scores relative to centroid 0, t_k = x.(w_k - w_0) + (h_k - h_0) + 1 with h_k = -|w_k|^2/2
+//     (largest t_k = nearest centroid; the |x|^2 term is common to all k), are chains of fused
+//     multiply-adds against a wave-uniform copy of w_k - w_0 held in registers;
+//   - the centroid index rides in the low 4 mantissa bits of t_k, and the two largest t_k come out
+//     of a network of three-input max/median instructions; when they are closer than a rigorous
+//     bound on the fp32 rounding error (packing included), the lane decides exactly in fp64, so the
+//     assignment is the exact-arithmetic nearest centroid of the fp32 state;
+//   - the gradient sums of Eq. 9 are kept per lane in LDS: a row holds the d sums and the count of
+//     one centroid, as NQ float4, for one lane (RS = 1) or for the lane pair l, l+32 (RS = 2).  A
+//     sample is added to its row in NQ phases of one 128-bit read, four adds and one 128-bit write;
+//     in phase p the lower lanes work on float4 number p and the upper lanes on number p+1 (mod NQ),
+//     so a shared row is never touched twice in one phase and every LDS instruction serves all 64
+//     lanes.  The phases of a group are interleaved with the score computation of the next group,
+//     which hides their LDS latency.  Lanes past the end of a mini-batch use a scratch row.  A
+//     fixed-order reduction follows once per step.
+// The LDS pipeline is the scarce resource of this kernel (it was measured ~85 % busy with twice as
+// many, half-filled accesses), hence the care for few, full LDS instructions and for DPP instead of
+// LDS-backed shuffles in the per-step part.
 // Every sum is formed in one fixed order, so a run is reproducible bit for bit.
 #include "asgd_internal.h"
 
@@ -46,11 +53,74 @@ __device__ __forceinline__ double wave_sum(double v)
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
-__device__ __forceinline__ float wave_max(float v)
+
+// max over the wave of a non-negative value, without LDS: butterfly inside rows of 16 lanes with DPP
+// (lane ^ 1, lane ^ 2, mirror inside 8, mirror inside 16), then the four rows through scalar reads.
+__device__ __forceinline__ float wave_max_nonneg(float v)
 {
+    int x = __float_as_int(v);      // non-negative floats order like their bit patterns
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xF, 0xF, true));   // row_mirror
+    const int a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
+    const int c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
+    return __int_as_float(max(max(a, b), max(c, d)));
+}
+
+// min and max of floats through the integer instructions on their bit patterns.  For non-negative
+// values the integer order is the float order and every negative value is below every non-negative
+// one; negative values compare in reverse among themselves.  That is enough for top2() below, whose
+// callers guarantee that the largest value is at least 1 and only look at the second largest when
+// it is within a small distance of the largest.  (Integer instructions need no NaN quieting.)
+__device__ __forceinline__ float fmin2(float a, float b) { return __int_as_float(min(__float_as_int(a), __float_as_int(b))); }
+__device__ __forceinline__ float fmax2(float a, float b) { return __int_as_float(max(__float_as_int(a), __float_as_int(b))); }
+__device__ __forceinline__ float fmax3(float a, float b, float c)
+{
+    return __int_as_float(max(max(__float_as_int(a), __float_as_int(b)), __float_as_int(c)));
+}
+
+// Largest and second largest of t[0..N) with three-input max/median instructions: triples are reduced
+// to (max, median) and merged pairwise.  Exact when the second largest is non-negative (see above).
+template <int N>
+__device__ __forceinline__ void top2(const float (&t)[N], float &best, float &second)
+{
+    static_assert(N >= 2, "need two values");
+    float H, M;
+    int i;
+    if constexpr (N >= 3) {
+        H = fmax3(t[0], t[1], t[2]);
+        M = __builtin_amdgcn_fmed3f(t[0], t[1], t[2]);
+        i = 3;
+    } else {
+        H = fmax2(t[0], t[1]);
+        M = fmin2(t[0], t[1]);
+        i = 2;
+    }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    for (; i + 2 < N; i += 3) {
+        const float h = fmax3(t[i], t[i + 1], t[i + 2]);
+        const float m = __builtin_amdgcn_fmed3f(t[i], t[i + 1], t[i + 2]);
+        const float lo = fmin2(H, h);
+        H = fmax2(H, h);
+        M = fmax3(lo, M, m);
+    }
+#pragma unroll
+    for (; i < N; ++i) {
+        M = __builtin_amdgcn_fmed3f(H, M, t[i]);
+        H = fmax2(H, t[i]);
+    }
+    best = H;
+    second = M;
+}
+
+// Lanes l and l+32 hand parts of an accumulator row to each other through LDS.  The hardware executes
+// the LDS accesses of a wave in program order; this keeps the compiler from moving the read of one
+// phase above the write of the previous one (to a single lane the two look unrelated).
+__device__ __forceinline__ void phase_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 // Exchange buffers are written and read with relaxed device-scope atomic accesses: these go through
@@ -82,11 +152,9 @@ __device__ __forceinline__ bool wait_flag(const int *flag, int want, bool at_lea
 
 // Steps [t0, t1) of the workers blockIdx.x, blockIdx.x + gridDim.x, ...
 //   NW   wavefronts per worker: wave v takes the groups v, v+NW, ... of every mini-batch.
-//        NW = 1: a lane owns one accumulator row per centroid and its read-modify-write is
-//                software-pipelined (the row is read one group before it is added to);
-//        NW = 2: lanes l and l+32 share a row and update it one after the other, which halves
-//                the LDS per wave so that two waves per SIMD are resident and hide each other's
-//                latencies.
+//   RS   lanes sharing an accumulator row: 1 = every lane has its own rows (64 per centroid and
+//        wave); 2 = lanes l and l+32 share a row, which halves the LDS per wave so that twice as many
+//        waves are resident.
 //   sync = 0: the launch contains nothing a worker has to wait for (silent or free-running mode,
 //             or the host ends every launch at a multiple of E); one workgroup per worker.
 //   sync = 1: the whole run is one launch of co-resident workgroups.  A workgroup takes its workers
@@ -95,28 +163,39 @@ __device__ __forceinline__ bool wait_flag(const int *flag, int want, bool at_lea
 //             of the previous round), and a sender waits until the recipient has consumed the older
 //             message that sits in the same buffer.  Every wait is on an earlier round, so the
 //             waits cannot form a cycle.
-template <int K, int D, int PF, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW))) void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
+//
+// State layout in registers ("task layout"): lane l < NT = K*NQ holds the four elements
+// (c, 4q .. 4q+3) of the state with c = l / NQ, q = l % NQ (elements past d do not exist and stay 0);
+// the same lane sums float4 column (c, q) of the accumulator rows once per step.
+template <int K, int D, int PF, int NW, int RS>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(RS, RS)))
+void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 {
     constexpr int KD = K * D;
     constexpr int NQ = (D + 1 + 3) / 4;             // float4 per accumulator row: d sums, count, padding
-    constexpr int NT = K * NQ;                      // reduction tasks: one float4 column each
-    constexpr int NPART = 64 / NT;                  // lanes sharing a task split the rows
-    constexpr int NSLOT = (KD + 63) / 64;           // state elements a lane owns (element e = slot*64 + lane)
-    constexpr int RL = 64 / NW;                     // accumulator rows per centroid and wave
+    constexpr int NT = K * NQ;                      // tasks: one float4 column each
+    constexpr int NPART = 64 / NT;                  // lanes sharing a task split the rows in the reduction
+    constexpr int RL = 64 / RS;                     // accumulator rows per centroid and wave
     constexpr int RPP = RL / NPART;                 // rows one lane sums in the reduction
+    constexpr int CPC = (K - 1 + NQ - 1) / NQ;      // score chains between two row phases
+    constexpr int CQ = D / 4, CI = D % 4;           // float4 and component that hold the count
     static_assert(NW == 1 || NW == 2, "one or two waves per worker");
+    static_assert(RS == 1 || (RS == 2 && NQ >= 2), "two lanes share a row only if it has two float4 or more");
+    static_assert(K >= 2 && K <= 16, "index packing uses 4 bits");
     static_assert(PF >= 2, "the ring needs the previous group's buffer");
     static_assert(NT <= 64 && NPART >= 1 && RL % NPART == 0 && RPP % 2 == 0, "state too large for this kernel");
 
-    // acc[wave][row][q][r]: float4 number q of the row that lane r (NW = 2: lanes r and r+32) keeps for
+    // acc[wave][row][q][r]: float4 number q of the row that lane r (RS = 2: lanes r and r+32) keeps for
     // centroid `row`; row K is scratch for masked lanes.  Consecutive lanes are 16 bytes apart.
     __shared__ float4 acc[NW][K + 1][NQ][RL];
-    __shared__ __attribute__((aligned(16))) float wbc[NW][KD];   // state, wave-uniform reads, one copy per wave
-    __shared__ __attribute__((aligned(16))) float sq[NW][KD];
-    __shared__ float4 part[2][NW][NPART][NT];                    // per-wave totals, double-buffered by step parity
+    __shared__ __attribute__((aligned(16))) float wbc[NW][KD];         // state, one copy per wave
+    __shared__ __attribute__((aligned(16))) float wdc[NW][KD - D + 4]; // w_k - w_0 for k >= 1
+    __shared__ float hq[NW][64];                                       // per-task sums of squares
+    __shared__ float hnc[NW][16];                                      // (h_k - h_0) + 1
+    __shared__ float4 part[2][NW][NPART][NT];                          // per-wave totals, double-buffered by step parity
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool lower = RS == 1 || lane < 32;        // the half of the wave that starts with float4 number 0
     const int b = p.b;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
     const bool rounds = (p.E > 0 && p.W > 1 && det);   // work is cut at multiples of E
@@ -124,6 +203,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
     // groups of 64 samples per mini-batch and wave, rounded up to a multiple of the ring depth (the
     // extra groups are fully masked); group m of wave v covers samples [(v + m*NW)*64, +64)
     const int ngw = (((b + 63) / 64 + NW - 1) / NW + PF - 1) / PF * PF;
+
+    // this lane's task
+    const bool has_task = lane < NT;
+    const int tc = has_task ? lane / NQ : 0, tq = has_task ? lane % NQ : 0;
+    bool tv[4];                                     // which of the four elements exist
+    int te_[4];                                     // their index in the state
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) {
+        tv[c4] = has_task && (4 * tq + c4 < D);
+        te_[c4] = tc * D + 4 * tq + c4;
+    }
+    // float4 number this lane works on in phase ph of a row update, as an offset in float4 units
+    int qoff[NQ];
+#pragma unroll
+    for (int ph = 0; ph < NQ; ++ph) qoff[ph] = (lower ? ph : (ph + 1) % NQ) * RL;
 
     float sum_xmax = 0.0f;
 #pragma unroll
@@ -150,11 +244,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
     {
         const float *x0 = p.x + ((size_t)i * p.H + (size_t)s_seg * b) * D;
 #pragma unroll
-        for (int u = 0; u < (NW == 1 ? PF - 1 : PF); ++u) {
+        for (int u = 0; u + 1 < PF; ++u) {
             const int n = (wave + u * NW) * 64 + lane;
             load_row<D>(xr[u], x0 + (size_t)(n < b ? n : b - 1) * D);
         }
     }
+
+    // part of sample x that goes to float4 number q of a row, component c4: the d values, then the count
+    auto row_part = [](const float(&x)[D], int q, int c4) -> float {
+        const int j = 4 * q + c4;
+        return j < D ? x[j] : (j == D ? 1.0f : 0.0f);
+    };
 
     for (;;) {
         // ---- what this workgroup does after the current item ----
@@ -173,63 +273,78 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
         const float *xs = p.x + (size_t)i * p.H * D;            // this worker's shard
         const float *x_after = has_next ? p.x + ((size_t)next_i * p.H + (size_t)next_s * b) * D : xs + (size_t)s_seg * b * D;
 
-        float wl[NSLOT];                                        // element e = slot*64 + lane of the state
+        float w4[4];                                            // this lane's four elements of the state
 #pragma unroll
-        for (int q = 0; q < NSLOT; ++q) {
-            const int e = q * 64 + lane;
-            wl[q] = e < KD ? p.w[(size_t)i * KD + e] : 0.0f;
-        }
+        for (int c4 = 0; c4 < 4; ++c4) w4[c4] = tv[c4] ? p.w[(size_t)i * KD + te_[c4]] : 0.0f;
         long long s_epoch = s_seg;
         long long round = p.E > 0 ? ta / p.E : 0;
         int te = p.E > 0 ? (int)(ta % p.E) : 0;
 
         for (long long t = ta; t < tb; ++t) {
-            // ---- wave-uniform copy of the state, -|w_k|^2/2, and the rounding-error bound ----
-            float wabs = 0.0f;
+            // ---- wave-uniform copies: state (for exact re-evaluation), differences to centroid 0, offsets ----
+            // centroid 0 lives in the lanes 0 .. NQ-1
+            float w0[4 * NQ];
 #pragma unroll
-            for (int q = 0; q < NSLOT; ++q) {
-                const int e = q * 64 + lane;
-                if (e < KD) {
-                    wbc[wave][e] = wl[q];
-                    sq[wave][e] = wl[q] * wl[q];
-                }
-                wabs = fmaxf(wabs, fabsf(wl[q]));
+            for (int q = 0; q < NQ; ++q) {
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4)
+                    w0[4 * q + c4] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w4[c4]), q));
             }
-            __syncthreads();
-            float wv[KD];
+            float dabs = 0.0f, hsq = 0.0f;
 #pragma unroll
-            for (int e = 0; e < KD; ++e) wv[e] = wbc[wave][e];
+            for (int c4 = 0; c4 < 4; ++c4) {
+                float w0q = w0[c4];
+#pragma unroll
+                for (int q = 1; q < NQ; ++q) w0q = (tq == q) ? w0[4 * q + c4] : w0q;
+                const float wd = tv[c4] ? w4[c4] - w0q : 0.0f;
+                if (tv[c4]) {
+                    wbc[wave][te_[c4]] = w4[c4];
+                    if (tc >= 1) wdc[wave][te_[c4] - D] = wd;
+                }
+                dabs = fmaxf(dabs, fabsf(wd));
+                hsq = fmaf(w4[c4], w4[c4], hsq);
+            }
+            hq[wave][lane] = hsq;
+            __syncthreads();
+            float wv[KD - D];                                    // w_k - w_0 for k >= 1
+#pragma unroll
+            for (int e = 0; e < KD - D; ++e) wv[e] = wdc[wave][e];
             float hl = 0.0f;
             if (lane < K) {
 #pragma unroll
-                for (int j = 0; j < D; ++j) hl += sq[wave][lane * D + j];
+                for (int q = 0; q < NQ; ++q) hl += hq[wave][lane * NQ + q];
             }
             hl *= -0.5f;
-            float hn[K];
-            float hmax = 0.0f;
+            const float h0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(hl), 0));
+            const float hdl = hl - h0;
+            const float hol = hdl + 1.0f;
+            if (lane < K) hnc[wave][lane] = hol;
+            float hn[K];                                         // hn[k] = (h_k - h_0) + 1
 #pragma unroll
-            for (int c = 0; c < K; ++c) {
-                hn[c] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(hl), c));
-                hmax = fmaxf(hmax, -hn[c]);
-            }
-            const float wmax = wave_max(wabs);
-            // Each score is a chain of D fused multiply-adds started from hn (itself a sum of D squares),
-            // so its rounding error is below (2D+1) * 2^-24 * (max|w| * sum_j max|x_j| + max_k |hn_k|).
-            // Two scores that differ by more than twice that (here with a factor 1.5 to spare) are
-            // ordered correctly by the fp32 comparison.
-            const float thr = 3.0f * (float)(2 * D + 1) * 5.9604645e-8f * (wmax * sum_xmax + hmax);
+            for (int c = 0; c < K; ++c) hn[c] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(hol), c));
+            // max_k |h_k| bounds max_k |h_k - h_0| up to a factor 2; one wave-wide max serves both
+            const float hmax = wave_max_nonneg(lane < K ? fabsf(hl) : 0.0f);
+            const float hdmax = 2.0f * hmax;
+            // Rounding-error bound of one t_k, with u = 2^-24, A = max|w_k - w_0| * sum_j max|x_j| (a bound of
+            // sum_j |x_j||w_kj - w_0j|) and Hd = max_k |h_k - h_0|:
+            //   differences w_k - w_0 ................. u A
+            //   D fused multiply-adds ................. D u (A + Hd + 1)
+            //   h_k (D squares and adds, one product) . (D+1) u max|h| each, two of them in h_k - h_0
+            //   the subtraction and the +1 ............ 2 u (Hd + 1)
+            //   index in the low 4 mantissa bits ...... 32 u (A + Hd + 1)
+            // Two values that differ by more than twice the sum (times 1.5 to spare) are ordered correctly.
+            const float Abound = wave_max_nonneg(dabs) * sum_xmax;
+            const float thr = 3.0f * 5.9604645e-8f *
+                              ((float)(D + 33) * Abound + (float)(D + 34) * (hdmax + 1.0f) + (float)(2 * D + 2) * hmax);
 
             const long long s_next = (s_epoch + 1 == p.S) ? 0 : s_epoch + 1;
             const float *xb = xs + (size_t)s_epoch * b * D;                       // this mini-batch
             const float *xbn = (t + 1 < tb) ? xs + (size_t)s_next * b * D : x_after;   // the one after it
 
-            // NW = 1: pending read-modify-write (row pointer and content) of the group before the current one
+            // pending row update of the group before the current one: row pointer (float4 number 0 of the
+            // row) and the float4 read for the coming phase.  At the start of a step: the scratch row.
             float4 *prow = &acc[wave][K][0][lane % RL];
-            float4 pr[NQ];
-            if constexpr (NW == 1) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) pr[q] = prow[q * RL];
-            }
+            float4 pr = prow[qoff[0]];
 
             for (int m0 = 0; m0 < ngw; m0 += PF) {
 #pragma unroll
@@ -238,104 +353,141 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
                     const int m = m0 + u;
                     const int n = (wave + m * NW) * 64 + lane;
                     const float(&xc)[D] = xr[u];
+                    const float(&xp)[D] = xr[up];
 
-                    float best = -INFINITY, second = -INFINITY;
-                    int arg = 0;
+                    // t_k with the centroid index in the low 4 mantissa bits (15 - k, so that the lower index
+                    // wins exact ties of positive values); between the chains, the row phases of the
+                    // previous group: add, write, (fence,) read for the next phase
+                    float tk[K];
+                    const float tk0 = __uint_as_float(0x3F800000u | 15u);
+                    tk[0] = tk0;
 #pragma unroll
-                    for (int c = 0; c < K; ++c) {
-                        float sc = hn[c];
+                    for (int ph = 0; ph < NQ; ++ph) {
 #pragma unroll
-                        for (int j = 0; j < D; ++j) sc = fmaf(xc[j], wv[c * D + j], sc);
-                        second = __builtin_amdgcn_fmed3f(best, second, sc);   // second largest so far
-                        arg = sc > best ? c : arg;
-                        best = fmaxf(best, sc);
+                        for (int c = 1 + ph * CPC; c < 1 + (ph + 1) * CPC && c < K; ++c) {
+                            float sc = hn[c];
+#pragma unroll
+                            for (int j = 0; j < D; ++j) sc = fmaf(xc[j], wv[(c - 1) * D + j], sc);
+                            tk[c] = __uint_as_float((__float_as_uint(sc) & 0xFFFFFFF0u) | (unsigned)(15 - c));
+                        }
+                        float add[4];
+#pragma unroll
+                        for (int c4 = 0; c4 < 4; ++c4) {
+                            const float lo = row_part(xp, ph, c4);
+                            if constexpr (RS == 1) {
+                                add[c4] = lo;
+                            } else {
+                                const float hi = row_part(xp, (ph + 1) % NQ, c4);
+                                add[c4] = lower ? lo : hi;
+                            }
+                        }
+                        pr.x += add[0]; pr.y += add[1]; pr.z += add[2]; pr.w += add[3];
+                        prow[qoff[ph]] = pr;
+                        if (ph + 1 < NQ) {
+                            if constexpr (RS == 2) phase_fence();
+                            pr = prow[qoff[ph + 1]];
+                        }
                     }
+                    // buffer `up` is free now: refill it with the group PF-1 turns ahead
+                    {
+                        const int mm = m + PF - 1;
+                        const bool same = mm < ngw;
+                        const float *src = same ? xb : xbn;
+                        const int nn = (wave + (same ? mm : mm - ngw) * NW) * 64 + lane;
+                        load_row<D>(xr[up], src + (size_t)(nn < b ? nn : b - 1) * D);
+                    }
+
+                    float best, second;
+                    top2<K>(tk, best, second);
+                    int arg = 15 - (int)(__float_as_uint(best) & 15u);
                     const bool valid = n < b;
                     if (valid && !(best - second > thr)) {
-                        // too close to call in fp32: exact assignment, fp64 direct form, lowest index on ties
+                        // Too close to call in fp32.  Candidates are the centroids within thr of the best; with
+                        // two of them their distances are compared exactly (fp64), with more all k distances
+                        // are recomputed in fp64, direct form; the lowest index wins exact ties.
                         float xe[D];
 #pragma unroll
                         for (int j = 0; j < D; ++j) {
                             xe[j] = xc[j];
                             asm volatile("" : "+v"(xe[j]));     // keep the conversions below inside this branch
                         }
-                        double dbest = INFINITY;
-                        int darg = 0;
-                        for (int c = 0; c < K; ++c) {
-                            double sd = 0.0;
+                        // count the candidates by forming every t_k again (same operations, same values)
+                        int ncand = (tk0 >= best - thr) ? 1 : 0;
+#pragma unroll 1
+                        for (int c = 1; c < K; ++c) {
+                            float sc = hnc[wave][c];
+#pragma unroll
+                            for (int j = 0; j < D; ++j) sc = fmaf(xe[j], wdc[wave][(c - 1) * D + j], sc);
+                            const float tc2 = __uint_as_float((__float_as_uint(sc) & 0xFFFFFFF0u) | (unsigned)(15 - c));
+                            ncand += (tc2 >= best - thr) ? 1 : 0;
+                        }
+                        if (ncand <= 2) {
+                            const int ca = arg, cb = 15 - (int)(__float_as_uint(second) & 15u);
+                            // |x - w_a|^2 - |x - w_b|^2 = sum_j (w_aj - w_bj) (w_aj + w_bj - 2 x_j)
+                            double dd = 0.0;
 #pragma unroll
                             for (int j = 0; j < D; ++j) {
-                                double diff = (double)xe[j] - (double)wbc[wave][c * D + j];
-                                sd += diff * diff;
+                                const double wa = (double)wbc[wave][ca * D + j], wb = (double)wbc[wave][cb * D + j];
+                                dd += (wa - wb) * ((wa + wb) - 2.0 * (double)xe[j]);
                             }
-                            if (sd < dbest) { dbest = sd; darg = c; }
+                            arg = (dd < 0.0 || (dd == 0.0 && ca < cb)) ? ca : cb;
+                        } else {
+                            double dbest = INFINITY;
+                            int darg = 0;
+#pragma unroll 1
+                            for (int c = 0; c < K; ++c) {
+                                double sd = 0.0;
+#pragma unroll
+                                for (int j = 0; j < D; ++j) {
+                                    double diff = (double)xe[j] - (double)wbc[wave][c * D + j];
+                                    sd += diff * diff;
+                                }
+                                if (sd < dbest) { dbest = sd; darg = c; }
+                            }
+                            arg = darg;
                         }
-                        arg = darg;
                         rechecks += 1;
                     }
                     if (p.dump && valid) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
 
-                    if constexpr (NW == 1) {
-                        // finish the previous group's row: add its sample (still in buffer `up`), write back
-                        {
-                            float *rf = reinterpret_cast<float *>(pr);
-#pragma unroll
-                            for (int j = 0; j < D; ++j) rf[j] += xr[up][j];
-                            rf[D] += 1.0f;
-#pragma unroll
-                            for (int q = 0; q < NQ; ++q) prow[q * RL] = pr[q];
-                        }
-                        // start this group's row
-                        prow = &acc[wave][valid ? arg : K][0][lane];
-#pragma unroll
-                        for (int q = 0; q < NQ; ++q) pr[q] = prow[q * RL];
-                    } else {
-                        // lanes l and l+32 share a row: lower half first, then upper half
-                        float4 *row = &acc[wave][valid ? arg : K][0][lane % RL];
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            if ((lane >> 5) == h) {
-                                float4 rr[NQ];
-#pragma unroll
-                                for (int q = 0; q < NQ; ++q) rr[q] = row[q * RL];
-                                float *rf = reinterpret_cast<float *>(rr);
-#pragma unroll
-                                for (int j = 0; j < D; ++j) rf[j] += xc[j];
-                                rf[D] += 1.0f;
-#pragma unroll
-                                for (int q = 0; q < NQ; ++q) row[q * RL] = rr[q];
-                            }
-                        }
-                    }
-                    // refill a free buffer with the group PF-1 (NW = 1) or PF (NW = 2) turns ahead
-                    {
-                        constexpr int ahead = (NW == 1) ? PF - 1 : PF;
-                        const int mm = m + ahead;
-                        const bool same = mm < ngw;
-                        const float *src = same ? xb : xbn;
-                        const int nn = (wave + (same ? mm : mm - ngw) * NW) * 64 + lane;
-                        load_row<D>(xr[NW == 1 ? up : u], src + (size_t)(nn < b ? nn : b - 1) * D);
-                    }
+                    // start this group's row update: read for phase 0
+                    if constexpr (RS == 2) phase_fence();
+                    prow = &acc[wave][valid ? arg : K][0][lane % RL];
+                    pr = prow[qoff[0]];
                 }
             }
-            if constexpr (NW == 1) {
-                // finish the last group of the mini-batch (buffer PF-1)
-                float *rf = reinterpret_cast<float *>(pr);
+            // finish the last group of the mini-batch (buffer PF-1)
+            {
+                const float(&xp)[D] = xr[PF - 1];
 #pragma unroll
-                for (int j = 0; j < D; ++j) rf[j] += xr[PF - 1][j];
-                rf[D] += 1.0f;
+                for (int ph = 0; ph < NQ; ++ph) {
+                    float add[4];
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) prow[q * RL] = pr[q];
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        const float lo = row_part(xp, ph, c4);
+                        if constexpr (RS == 1) {
+                            add[c4] = lo;
+                        } else {
+                            const float hi = row_part(xp, (ph + 1) % NQ, c4);
+                            add[c4] = lower ? lo : hi;
+                        }
+                    }
+                    pr.x += add[0]; pr.y += add[1]; pr.z += add[2]; pr.w += add[3];
+                    prow[qoff[ph]] = pr;
+                    if (ph + 1 < NQ) {
+                        if constexpr (RS == 2) phase_fence();
+                        pr = prow[qoff[ph + 1]];
+                    }
+                }
             }
             __syncthreads();
 
             // ---- sum the rows of every centroid in a fixed order, clear them ----
-            // lane = (part, task): task = one float4 column (centroid c, quarter q4); part = its share of the rows
+            // lane = (part, task): task = one float4 column (centroid, float4 number); part = its share of the rows
             {
                 const int task = lane % NT, prt = lane / NT;
                 if (prt < NPART) {
-                    const int c = task / NQ, q4 = task % NQ;
-                    float4 *col = &acc[wave][c][q4][prt * RPP];
+                    float4 *col = &acc[wave][task / NQ][task % NQ][prt * RPP];
                     float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
 #pragma unroll
                     for (int r = 0; r < RPP; r += 2) {
@@ -351,22 +503,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
                 }
             }
             __syncthreads();
-            float S[NSLOT], cntv[NSLOT];
+            // totals of this lane's float4 column and the count of its centroid: waves, then parts, one fixed order
+            float S4[4] = {0.f, 0.f, 0.f, 0.f};
+            float cnt = 0.0f;
+            if (has_task) {
 #pragma unroll
-            for (int q = 0; q < NSLOT; ++q) {
-                const int e = q * 64 + lane;
-                float sv = 0.0f, cv = 0.0f;
-                if (e < KD) {
-                    const int c = e / D, j = e % D;
-                    const float *pf = reinterpret_cast<const float *>(&part[parity][0][0][0]);
-#pragma unroll
-                    for (int v = 0; v < NW * NPART; ++v) {      // waves, then parts: one fixed order
-                        sv += pf[(v * NT + c * NQ + j / 4) * 4 + j % 4];
-                        cv += pf[(v * NT + c * NQ + D / 4) * 4 + D % 4];
-                    }
+                for (int v = 0; v < NW * NPART; ++v) {
+                    const float4 sv = (&part[parity][0][0][0])[v * NT + lane];
+                    const float4 cv = (&part[parity][0][0][0])[v * NT + tc * NQ + CQ];
+                    S4[0] += sv.x; S4[1] += sv.y; S4[2] += sv.z; S4[3] += sv.w;
+                    cnt += CI == 0 ? cv.x : (CI == 1 ? cv.y : (CI == 2 ? cv.z : cv.w));
                 }
-                S[q] = sv;
-                cntv[q] = cv;
             }
             parity ^= 1;
 
@@ -389,18 +536,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
                 has_ext = det ? (st == (int)(round - 1)) : (st >= 0);
             }
             const float *ext = p.slot + ((size_t)rpar * p.W + i) * KD;
-            float G[NSLOT], we[NSLOT];
+            float G[4], we[4];
             double lhs = 0.0, rhs = 0.0, nrm = 0.0;
 #pragma unroll
-            for (int q = 0; q < NSLOT; ++q) {
-                const int e = q * 64 + lane;
-                G[q] = (cntv[q] * wl[q] - S[q]) * inv_b;      // descent gradient of Eq. 9
-                we[q] = 0.0f;
-                if (has_ext && e < KD) {
-                    we[q] = load_shared(ext + e);
-                    const double wed = (double)we[q];
-                    const double a = ((double)wl[q] - (double)p.eps * (double)G[q]) - wed;
-                    const double c2 = (double)wl[q] - wed;
+            for (int c4 = 0; c4 < 4; ++c4) {
+                G[c4] = tv[c4] ? (cnt * w4[c4] - S4[c4]) * inv_b : 0.0f;      // descent gradient of Eq. 9
+                we[c4] = 0.0f;
+                if (has_ext && tv[c4]) {
+                    we[c4] = load_shared(ext + te_[c4]);
+                    const double wed = (double)we[c4];
+                    const double a = ((double)w4[c4] - (double)p.eps * (double)G[c4]) - wed;
+                    const double c2 = (double)w4[c4] - wed;
                     lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
                 }
             }
@@ -419,10 +565,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
             }
             // Eq. 7 and Alg. 5 line 8
 #pragma unroll
-            for (int q = 0; q < NSLOT; ++q) {
-                float step = G[q];
-                if (delta) step += wl[q] - 0.5f * (wl[q] + we[q]);
-                wl[q] = wl[q] - p.eps * step;
+            for (int c4 = 0; c4 < 4; ++c4) {
+                float step = G[c4];
+                if (delta) step += w4[c4] - 0.5f * (w4[c4] + we[c4]);
+                w4[c4] = w4[c4] - p.eps * step;
             }
             if (merge_point) {
                 // every wave has read the buffer: empty it and tell senders of later rounds so
@@ -446,9 +592,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
                     }
                     float *dst = p.slot + ((size_t)spar * p.W + peer) * KD;
 #pragma unroll
-                    for (int q = 0; q < NSLOT; ++q) {
-                        const int e = q * 64 + lane;
-                        if (e < KD) store_shared(dst + e, wl[q]);
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        if (tv[c4]) store_shared(dst + te_[c4], w4[c4]);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                     if (lane == 0)
@@ -465,9 +610,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
 
         if (wave == 0) {
 #pragma unroll
-            for (int q = 0; q < NSLOT; ++q) {
-                const int e = q * 64 + lane;
-                if (e < KD) p.w[(size_t)i * KD + e] = wl[q];
+            for (int c4 = 0; c4 < 4; ++c4) {
+                if (tv[c4]) p.w[(size_t)i * KD + te_[c4]] = w4[c4];
             }
         }
         if (!has_next) break;
@@ -487,16 +631,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW, NW)
     if (lane == 0 && wait_failed) atomicOr(p.error_flag, 1);
 }
 
-template <int K, int D, int PF, int NW>
+template <int K, int D, int PF, int NW, int RS>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
-    auto kern = small_steps_kernel<K, D, PF, NW>;
+    auto kern = small_steps_kernel<K, D, PF, NW, RS>;
     if (!persistent) {
         hipLaunchKernelGGL(kern, dim3(p.W), dim3(64 * NW), 0, s, p, t0, t1, 0);
         return hipGetLastError();
     }
     // one launch for the whole run: every workgroup must be resident at the same time
-    // resident workgroups of this kernel on the current device (queried once per device and variant)
+    // (resident workgroups of this kernel on the current device: queried once per device and variant)
     static long long cached_capacity[64] = {0};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -521,6 +665,17 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipSt
     return hipGetLastError();
 }
 
+template <int NW, int RS>
+hipError_t launch_shape(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent, int pf)
+{
+    // RS = 2 leaves 256 registers per wave: ring depth at most 4
+    if constexpr (RS == 1) {
+        if (pf >= 8) return launch_variant<10, 10, 8, NW, RS>(p, t0, t1, s, persistent);
+    }
+    if (pf >= 4) return launch_variant<10, 10, 4, NW, RS>(p, t0, t1, s, persistent);
+    return launch_variant<10, 10, 2, NW, RS>(p, t0, t1, s, persistent);
+}
+
 }  // namespace
 
 bool small_kernel_supports(int k, int d, int b)
@@ -532,26 +687,23 @@ bool small_kernel_supports(int k, int d, int b)
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
     if (!(p.k == 10 && p.d == 10)) return hipErrorInvalidValue;
-    // tune: bit 2 (value 4) = one wave per worker; bits 0-1 limit the ring depth (1: 4, 2: 2); 3 is
-    // handled by the caller (one launch per round)
-    const int nw = (p.tune & 4) ? 1 : 2;
+    // Shape of a worker: two waves sharing accumulator rows pairwise (default: 8 waves per CU with one
+    // worker per 4 SIMD slots), one wave with shared rows (many workers: twice as many resident), or
+    // one wave with private rows.  tune: bits 2-3 pick the shape, bits 0-1 limit the ring depth
+    // (1: 4, 2: 2); the value 3 in bits 0-1 is handled by the caller (one launch per round).
+    int shape = (p.tune >> 2) & 3;          // 0 = by number of workers, 1 = 1 wave private rows, 2 = 1 wave shared rows, 3 = 2 waves
+    if (shape == 0) shape = p.W > 1024 ? 2 : 3;
+    const int nw = shape == 3 ? 2 : 1;
     const int ngw = ((p.b + 63) / 64 + nw - 1) / nw;
     // ring depth: the largest of 8, 4 that divides the number of groups per mini-batch and wave, else 2
     // (the kernel then pads the group count with masked groups)
     int pf = (ngw % 8 == 0) ? 8 : (ngw % 4 == 0) ? 4 : 2;
-    if (nw == 2 && pf > 4) pf = 4;                 // two waves per SIMD: 256 registers each
     if ((p.tune & 3) == 1 && pf > 4) pf = 4;
     if ((p.tune & 3) == 2 && pf > 2) pf = 2;
-    if (nw == 1) {
-        switch (pf) {
-            case 8: return launch_variant<10, 10, 8, 1>(p, t0, t1, s, persistent);
-            case 4: return launch_variant<10, 10, 4, 1>(p, t0, t1, s, persistent);
-            default: return launch_variant<10, 10, 2, 1>(p, t0, t1, s, persistent);
-        }
-    }
-    switch (pf) {
-        case 4: return launch_variant<10, 10, 4, 2>(p, t0, t1, s, persistent);
-        default: return launch_variant<10, 10, 2, 2>(p, t0, t1, s, persistent);
+    switch (shape) {
+        case 1: return launch_shape<1, 1>(p, t0, t1, s, persistent, pf);
+        case 2: return launch_shape<1, 2>(p, t0, t1, s, persistent, pf);
+        default: return launch_shape<2, 2>(p, t0, t1, s, persistent, pf);
     }
 }
 

@@ -96,7 +96,7 @@ def test_config0_full(B, oracle, kernel):
     assert o.counters[:, 2].sum() > 0                          # merges really happened
 
 
-@pytest.mark.parametrize("tune", [1, 2, 4, 5, 6])   # ring depths, one or two waves per worker
+@pytest.mark.parametrize("tune", [1, 2, 4, 5, 6, 8, 9, 12])   # ring depths x worker shapes (waves, row sharing)
 def test_small_kernel_variants(B, oracle, tune):
     X = make_data(8 * 4000, 10, 10, seed=5)
     run_both(B, oracle, X, 10, 8, 1000, 0.05, 2, 9, kernel=2, tune=tune)
