@@ -30,6 +30,8 @@ struct asgd_ctx {
     long long t = 0;
 
     float *w = nullptr, *slot = nullptr, *acc = nullptr, *xabsmax = nullptr, *mean = nullptr;
+    float *waug = nullptr, *xnorm2max = nullptr;    // matrix-core kernel only, allocated on first use
+    bool xnorm2max_valid = false;
     int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
     long long *ncum = nullptr, *counters = nullptr;
     double *qpart = nullptr, *qout = nullptr;
@@ -58,7 +60,7 @@ size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
 void free_all(asgd_ctx *c)
 {
     void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->consumed, c->cnt, c->assign_tmp,
-                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout};
+                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->waug, c->xnorm2max};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
@@ -225,6 +227,7 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->stream = (hipStream_t)hip_stream;
     ctx->t = 0;
     ctx->loaded = false;
+    ctx->xnorm2max_valid = false;
     StepParams p = make_params(ctx);
     HIP_TRY(ctx, launch_init_first_k(p, ctx->stream));
     int rc = clear_exchange(ctx);
@@ -288,9 +291,23 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 
     int kernel = ctx->kernel_opt;
     const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST;
-    if (kernel == ASGD_KERNEL_AUTO) kernel = small_ok ? ASGD_KERNEL_SMALL : ASGD_KERNEL_GENERIC;
+    const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
+    if (kernel == ASGD_KERNEL_AUTO) {
+        // the matrix-core kernel pays off once the k x d contraction dominates a step
+        kernel = small_ok ? ASGD_KERNEL_SMALL
+                          : (mfma_ok && ctx->k >= 32 && ctx->d >= 16 ? ASGD_KERNEL_MFMA : ASGD_KERNEL_GENERIC);
+    }
     if (kernel == ASGD_KERNEL_SMALL && !small_ok) return ASGD_EINVAL;
-    if (kernel == ASGD_KERNEL_MFMA) return ASGD_EINVAL;
+    if (kernel == ASGD_KERNEL_MFMA) {
+        if (!mfma_ok) return ASGD_EINVAL;
+        if (!ctx->waug)
+            HIP_TRY(ctx, hipMalloc((void **)&ctx->waug, mfma_waug_floats(ctx->k, ctx->d, ctx->W) * sizeof(float)));
+        if (!ctx->xnorm2max) HIP_TRY(ctx, hipMalloc((void **)&ctx->xnorm2max, sizeof(float)));
+        if (!ctx->xnorm2max_valid) {
+            HIP_TRY(ctx, launch_rownorm2max(ctx->x, ctx->H * ctx->W, ctx->d, ctx->xnorm2max, ctx->stream));
+            ctx->xnorm2max_valid = true;
+        }
+    }
 
     StepParams p = make_params(ctx);
     const long long t_end = ctx->t + steps;
@@ -324,7 +341,9 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
             if (next < tb) tb = next;
         }
         hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream, false)
-                                                     : launch_generic_steps(p, ta, tb, ctx->stream);
+                       : (kernel == ASGD_KERNEL_MFMA)
+                           ? launch_mfma_steps(p, ta, tb, ctx->waug, ctx->xnorm2max, ctx->stream)
+                           : launch_generic_steps(p, ta, tb, ctx->stream);
         HIP_TRY(ctx, e);
         ++launches;
         ta = tb;

@@ -188,6 +188,46 @@ def test_wider_shapes_generic(B, oracle):
     run_both(B, oracle, X, 1024, 2, 4096, 0.01, 2, 4, kernel=1)
 
 
+@pytest.mark.parametrize("k,d,W,b,E,steps,N,centres,weights", [
+    (100, 100, 4, 2000, 2, 7, 4 * 2000 * 3, "uniform10", "zipf1.1"),     # relative of the k = d = 100 workload
+    (1024, 128, 2, 4096, 2, 4, 2 * 4096 * 2, "sphere10", "equal"),      # relative of the k = 1024, d = 128 workload
+    (70, 8, 3, 100, 2, 9, 3 * 450 + 2, "uniform10", "equal"),           # b below one tile, k not a multiple of 32
+    (33, 36, 5, 300, 3, 8, 5 * 1000 + 3, "uniform10", "equal"),         # ragged last tile, odd row length of W'
+    (2, 4, 2, 129, 1, 6, 2 * 400, "uniform10", "equal"),                # smallest k and d
+    (128, 64, 2, 256, 1, 5, 2 * 1024, "uniform10", "equal"),            # exact multiples of all tile sizes
+])
+def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights):
+    X = make_data(N, d, k, seed=21, centres=centres, weights=weights)
+    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3)
+    assert g.stats().kernel == 3
+
+
+def test_matrix_core_kernel_options(B, oracle):
+    X = make_data(6 * 1200, 20, 40, seed=22)
+    run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11, parzen=False, kernel=3)
+    run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11, drop_rate=0.5, kernel=3)
+    run_both(B, oracle, X, 40, 6, 200, 0.05, 0, 11, kernel=3)
+    g, o = run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11)            # chosen automatically for this shape
+    assert g.stats().kernel == 3
+    # duplicated samples give exact ties between centroids started from them: lowest index wins on both sides
+    Xd = X.copy()
+    Xd[1] = Xd[0]
+    Xd[1200 + 3] = Xd[1200]
+    run_both(B, oracle, Xd, 40, 6, 200, 0.05, 2, 6, kernel=3)
+    # same run twice: bit for bit; lost messages: same as silent
+    Xg = to_dev(X)
+    a = B.ASGD(40, 20, 6, 200, 0.05, E=2, kernel=3); a.load_shards(Xg); a.run_steps(11)
+    c = B.ASGD(40, 20, 6, 200, 0.05, E=2, kernel=3); c.load_shards(Xg); c.run_steps(4); c.run_steps(7)
+    assert np.array_equal(a.get_state(), c.get_state())
+    lost = B.ASGD(40, 20, 6, 200, 0.05, E=2, drop_rate=1.0, kernel=3); lost.load_shards(Xg); lost.run_steps(11)
+    sil = B.ASGD(40, 20, 6, 200, 0.05, E=0, kernel=3); sil.load_shards(Xg); sil.run_steps(11)
+    assert np.array_equal(lost.get_state(), sil.get_state())
+    with pytest.raises(B.AsgdError):
+        bad = B.ASGD(40, 18, 6, 200, 0.05, kernel=3)                   # d must be a multiple of 4
+        bad.load_shards(to_dev(make_data(6 * 1200, 18, 40)))
+        bad.run_steps(1)
+
+
 def test_error_paths(B):
     import torch
     with pytest.raises(B.AsgdError):
