@@ -30,7 +30,7 @@ struct asgd_ctx {
     long long t = 0;
 
     float *w = nullptr, *slot = nullptr, *acc = nullptr, *xabsmax = nullptr, *mean = nullptr;
-    float *waug = nullptr, *xnorm2max = nullptr;    // matrix-core kernel only, allocated on first use
+    float *xnorm2max = nullptr;    // matrix-core kernel only, allocated on first use
     bool xnorm2max_valid = false;
     int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
     long long *ncum = nullptr, *counters = nullptr;
@@ -60,7 +60,7 @@ size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
 void free_all(asgd_ctx *c)
 {
     void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->consumed, c->cnt, c->assign_tmp,
-                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->waug, c->xnorm2max};
+                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
@@ -300,8 +300,6 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     if (kernel == ASGD_KERNEL_SMALL && !small_ok) return ASGD_EINVAL;
     if (kernel == ASGD_KERNEL_MFMA) {
         if (!mfma_ok) return ASGD_EINVAL;
-        if (!ctx->waug)
-            HIP_TRY(ctx, hipMalloc((void **)&ctx->waug, mfma_waug_floats(ctx->k, ctx->d, ctx->W) * sizeof(float)));
         if (!ctx->xnorm2max) HIP_TRY(ctx, hipMalloc((void **)&ctx->xnorm2max, sizeof(float)));
         if (!ctx->xnorm2max_valid) {
             HIP_TRY(ctx, launch_rownorm2max(ctx->x, ctx->H * ctx->W, ctx->d, ctx->xnorm2max, ctx->stream));
@@ -342,7 +340,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         }
         hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream, false)
                        : (kernel == ASGD_KERNEL_MFMA)
-                           ? launch_mfma_steps(p, ta, tb, ctx->waug, ctx->xnorm2max, ctx->stream)
+                           ? launch_mfma_steps(p, ta, tb, ctx->xnorm2max, ctx->stream)
                            : launch_generic_steps(p, ta, tb, ctx->stream);
         HIP_TRY(ctx, e);
         ++launches;

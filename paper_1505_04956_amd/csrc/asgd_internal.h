@@ -80,10 +80,8 @@ bool small_kernel_supports(int k, int d, int b);
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent);
 // Matrix-core kernel: needs d % 4 == 0, d <= 128, 16-byte aligned samples and its LDS budget.
 bool mfma_kernel_supports(int k, int d, int b, const void *x);
-size_t mfma_waug_floats(int k, int d, int W);          // size of the augmented-state buffer
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s);   // max_n |x_n|^2
-hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, float *waug, const float *xnorm2max,
-                             hipStream_t s);
+hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s);
 hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s);
 // Eq. 8 over rows [0, N): partials is scratch of quant_partials_count() doubles.
 int quant_partials_count();

@@ -1,28 +1,33 @@
-// Step kernel for large states (k*d too large for registers/LDS): the contraction-bound workloads
+// Step kernel for large states (k*d too large for registers): the contraction-bound workloads
 // (k = 100, d = 100 and k = 1024, d = 128).
 //
-// One workgroup of 4 wavefronts per worker.  A step has two phases.
+// One workgroup of 8 wavefronts (two per SIMD, so that one wave's vector work overlaps the other's
+// matrix work) per worker.  A step has two phases.
 //
-// Phase 1, assignment: the scores x.w_c - |w_c|^2/2 of a tile of 128 samples against all centroids
+// Phase 1, assignment.  The scores x.w_c - |w_c|^2/2 of a tile of 256 samples against all centroids
 // are a dense contraction over d and run on the matrix cores in fp32 (v_mfma_f32_32x32x2_f32).
-//   - The state is kept a second time in "augmented" form W' (kpad x daug8, row c = [w_c, h_c, 0..],
-//     h_c = -|w_c|^2/2) and a sample row as [x, 1, 0..], so the offset is part of the contraction.
-//   - The sample tile sits in LDS for the whole pass over the centroids; blocks of 64 centroid rows
-//     of W' stream through a double-buffered LDS stage (W' itself stays in L2 / Infinity Cache).
-//   - Wave v owns 32 samples (matrix columns); rows are centroids.  A lane then holds, for ONE
-//     sample, 16 centroid scores per 32x32 tile, so the running arg-max is lane-local; the two
-//     half-waves (which see different centroid rows of the same sample) are merged once per tile.
-//   - Operands are fetched as float4 (4 consecutive dimensions) with the same (row, 4*half) pattern
-//     for both matrices; the matrix instruction number r of a group of four contracts dimensions
-//     r and r+4 of an 8-dimension chunk.  The order of the contraction over d is therefore a fixed
-//     permutation of 0..d-1; no transposition is needed.  LDS rows are padded to a stride that is an
-//     odd multiple of 4 floats, which keeps the 128-bit reads free of bank conflicts.
+//   - Matrix rows are centroids, columns are samples.  Wave v owns 32 samples of the tile and keeps
+//     their operand fragments in registers for the whole pass over the centroids (a lane holds, for
+//     its sample, 4 consecutive dimensions of every 8-dimension chunk: half-wave 0 dimensions 0-3,
+//     half-wave 1 dimensions 4-7); the fragments of the next tile are fetched into the same registers
+//     during the last centroid block of this one.  Samples never pass through LDS.
+//   - Blocks of 64 centroid rows stream from the state (L2 resident) through a double-buffered LDS
+//     stage, zero-padded to a multiple of 8 columns and of 64 rows; rows are padded to a stride that
+//     is an odd multiple of 4 floats, which keeps the 128-bit operand reads free of bank conflicts.
+//   - The accumulators start at h_c = -|w_c|^2/2 (kept in LDS), so the offset costs nothing.
+//     Matrix instruction q of a group of four contracts dimensions q and q+4 of a chunk: the order of
+//     the contraction is a fixed permutation of 0..d-1 and no transposition is needed.
+//   - In the 32x32 result a lane holds 16 centroid scores of ONE sample per tile, so the running
+//     arg-max is lane-local; the two half-waves (same sample, other rows) are merged once per tile.
 //   - The three largest scores and the indices of the two largest are tracked.  If the first two are
 //     closer than a bound on the fp32 rounding error, the sample is decided exactly in fp64 (pair
 //     comparison, or all k distances when the third is close too), lowest index on ties.
-// Phase 2, gradient and update: every centroid is owned by one wave (c mod 4), which scans the
-// assignments in sample order, adds the matching samples (lanes = dimensions) and updates the
-// centroid row: all sums have one fixed order, nothing is accumulated with atomics.
+// Phase 2, gradient and update.  The samples are sorted by centroid with a stable counting sort in
+// LDS (centroids ordered by owner wave c mod 8); each wave then streams the rows of its samples from
+// memory, 16 loads in flight, and adds them in sample order into per-centroid sums, which makes every
+// sum reproducible without atomics.  Gradient, Parzen sums (fp64), merge and update are row passes.
+#include <type_traits>
+
 #include "asgd_internal.h"
 
 namespace asgd {
@@ -31,11 +36,13 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int MF_THREADS = 256;
-constexpr int MF_WAVES = 4;
-constexpr int TM = 128;          // samples per tile (32 per wave)
-constexpr int WB = 64;           // centroid rows per W' block (2 matrix tiles of 32)
-constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows of W': never the nearest
+constexpr int MF_THREADS = 512;
+constexpr int MF_WAVES = 8;
+constexpr int TM = 256;          // samples per tile (32 per wave)
+constexpr int WB = 64;           // centroid rows per block (2 matrix tiles of 32)
+constexpr int RB = 4;            // rows per wave and iteration in the row passes (loads in flight)
+constexpr int GS = 16;           // sample rows in flight per wave in the gather
+constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the nearest
 
 struct Top3 {
     float v1, v2, v3;
@@ -64,22 +71,32 @@ __device__ __forceinline__ float wave_sum_f(float v)
     return v;
 }
 
-// Geometry shared by host and device.
+// LDS layout, shared by host and device
 struct MfmaGeom {
-    int daug8;     // d + 1 rounded up to a multiple of 8: row length of W'
-    int DP;        // LDS row stride in floats (daug8 + 4: an odd multiple of 4)
     int kpad;      // k rounded up to a multiple of WB
     int nblocks;   // kpad / WB
+    int kq;        // centroids per owner wave, rounded up
+    int ns;        // 8 * kq sort slots: slot(c) = (c % 8) * kq + c / 8
+    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, bytes;
 };
-__host__ __device__ inline MfmaGeom mfma_geom(int k, int d)
+__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident)
 {
     MfmaGeom g;
-    g.daug8 = (d + 1 + 7) / 8 * 8;
-    g.DP = g.daug8 + 4;
+    const int DP = nch * 8 + 4;
     g.kpad = (k + WB - 1) / WB * WB;
     g.nblocks = g.kpad / WB;
+    g.kq = (k + MF_WAVES - 1) / MF_WAVES;
+    g.ns = MF_WAVES * g.kq;
+    size_t o = (size_t)(resident ? g.kpad : 2 * WB) * DP * sizeof(float);
+    g.off_h = o;            o += (size_t)g.kpad * sizeof(float);
+    g.off_cstart = o;       o += ((size_t)g.ns + 4) / 4 * 4 * sizeof(int);
+    g.off_cursor = o;       o += ((size_t)g.ns + 3) / 4 * 4 * sizeof(int);
+    g.off_idx = o;          o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
+    g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
+    g.bytes = o;
     return g;
 }
+inline int mfma_chunks(int d) { return d <= 32 ? 4 : d <= 64 ? 8 : d <= 104 ? 13 : 16; }
 
 // max over rows of |x|^2 (one value), used by the rounding-error bound
 __global__ void rownorm2_partial_kernel(const float *__restrict__ x, long long rows, int d, float *partial)
@@ -109,12 +126,21 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
     }
 }
 
-// NJ = ceil(d / 64): dimensions per lane in the per-centroid passes (lane l owns l, l+64, ...)
-template <int NJ>
-__global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, long long t0, long long t1, float *waug_all,
+// NCH = number of 8-dimension chunks of the contraction (d <= 8 * NCH).
+// RES: the whole padded state fits in LDS.  It is then staged once per step and phase 1 needs no barriers.
+// Otherwise blocks of WB rows are streamed through a two-deep stage with one barrier per block.
+template <int NCH, bool RES>
+__global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
                                                                  const float *xnorm2max_ptr)
 {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
+    constexpr int DP8 = NCH * 8;                 // padded row length
+    constexpr int DP = DP8 + 4;                  // LDS row stride
+    constexpr int NJ = DP8 > 64 ? 2 : 1;         // dimensions per lane in the row passes (lane l owns l, l + 64)
+    constexpr int ROW4 = NCH * 2;                // float4 per padded row
+    constexpr int NVEC = WB * ROW4;              // float4 per staged block
+    constexpr int NST = (NVEC + MF_THREADS - 1) / MF_THREADS;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __shared__ double red_d[3][MF_WAVES];
     __shared__ float red_f[MF_WAVES];
     __shared__ int s_has_ext;
@@ -123,133 +149,177 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = lane >> 5, l32 = lane & 31;
     const int k = p.k, d = p.d, b = p.b;
-    const MfmaGeom g = mfma_geom(k, d);
+    const MfmaGeom g = mfma_geom(k, b, NCH, RES);
     const size_t kd = (size_t)k * d;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
 
-    float *Xs = smem;                                   // TM x DP
-    float *Ws = Xs + TM * g.DP;                         // 2 x WB x DP
-    unsigned short *idx = reinterpret_cast<unsigned short *>(Ws + 2 * WB * g.DP);   // b assignments
+    float *Ws = reinterpret_cast<float *>(smem_raw);                                  // (RES ? kpad : 2 x WB) x DP
+    float *hs = reinterpret_cast<float *>(smem_raw + g.off_h);                        // kpad offsets h_c
+    int *cstart = reinterpret_cast<int *>(smem_raw + g.off_cstart);                   // ns + 1 list starts
+    int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns counts, then cursors
+    unsigned short *idx = reinterpret_cast<unsigned short *>(smem_raw + g.off_idx);   // b assignments
+    unsigned short *perm = reinterpret_cast<unsigned short *>(smem_raw + g.off_perm); // b samples sorted by centroid
 
     float *wst = p.w + (size_t)i * kd;                  // state of this worker
-    float *waug = waug_all + (size_t)i * g.kpad * g.daug8;
-    float *gsc = p.acc + (size_t)i * kd;                // gradient scratch
+    float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
     const float xn2 = *xnorm2max_ptr;
 
-    // ---- augmented copy of the state, and max_c |w_c|^2 ----
+    // ---- h_c = -|w_c|^2/2 and max_c |w_c|^2 ----
     float wn2max = 0.0f;
-    for (int c = wave; c < g.kpad; c += MF_WAVES) {
-        float *row = waug + (size_t)c * g.daug8;
-        float s = 0.0f;
-        for (int j = lane; j < g.daug8; j += 64) {
-            float v = 0.0f;
-            if (c < k && j < d) {
-                v = wst[(size_t)c * d + j];
-                s = fmaf(v, v, s);
+    for (int c0 = wave * RB; c0 < g.kpad; c0 += MF_WAVES * RB) {
+        float s[RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const int c = c0 + q;
+            s[q] = 0.0f;
+#pragma unroll
+            for (int jq = 0; jq < NJ; ++jq) {
+                const int j = lane + 64 * jq;
+                const float v = wst[(size_t)(c < k ? c : 0) * d + (j < d ? j : 0)];
+                if (c < k && j < d) s[q] = fmaf(v, v, s[q]);
             }
-            if (j != d) row[j] = v;
         }
-        s = wave_sum_f(s);
-        if (lane == 0) row[d] = c < k ? -0.5f * s : PAD_SCORE;
-        wn2max = fmaxf(wn2max, s);
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const float sq = wave_sum_f(s[q]);
+            if (lane == 0) hs[c0 + q] = c0 + q < k ? -0.5f * sq : PAD_SCORE;      // kpad is a multiple of RB
+            wn2max = fmaxf(wn2max, sq);
+        }
     }
     if (lane == 0) red_f[wave] = wn2max;
     __syncthreads();
-    wn2max = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
+    wn2max = 0.0f;
+#pragma unroll
+    for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
     __syncthreads();
 
     long long rechecks = 0;
 
     for (long long t = t0; t < t1; ++t) {
+        // Fresh, opaque copies of the lane id per phase: everything derived from them (addresses, masks) is then
+        // recomputed per phase instead of being kept in registers across the whole step loop.
+        int lane_p1 = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane_p1));
+        const int lane = lane_p1, tid = wave * 64 + lane, half = lane >> 5, l32 = lane & 31;
         const long long s_ep = t % p.S;
         const float *xb = p.x + ((size_t)i * p.H + (size_t)s_ep * b) * d;
-        // Rounding-error bound of a score: daug8 products and sums on the matrix core plus the d roundings
-        // inside h_c, all relative to |x||w_c| + |h_c| <= sqrt(max|x|^2 max|w|^2) + max|w|^2/2.
+        // Bound on the rounding error of a score difference: DP8 products and sums on the matrix core plus the
+        // roundings inside h_c, each relative to |x||w_c| + |h_c| <= sqrt(max|x|^2 max|w|^2) + max|w|^2/2,
+        // doubled in case the matrix core truncates where a vector instruction would round to nearest.
         const float Bb = sqrtf(xn2) * sqrtf(wn2max) + 0.5f * wn2max;
-        const float thr = 3.0f * (float)(2 * g.daug8 + 4) * 5.9604645e-8f * Bb;
+        const float thr = 2.0f * (float)(2 * DP8 + 18) * 5.9604645e-8f * Bb;
 
         // ================= phase 1: assignment =================
-        for (int tile0 = 0; tile0 < b; tile0 += TM) {
-            __syncthreads();        // previous tile's readers of Xs are done
-            // sample tile -> LDS, as [x, 1, 0...]; rows past the mini-batch are zero
-            {
-                const int d4 = d >> 2;
-                for (int e = tid; e < TM * d4; e += MF_THREADS) {
-                    const int r = e / d4, c4 = e - r * d4;
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (tile0 + r < b) v = reinterpret_cast<const float4 *>(xb + (size_t)(tile0 + r) * d)[c4];
-                    *reinterpret_cast<float4 *>(&Xs[r * g.DP + 4 * c4]) = v;
-                }
-                for (int e = tid; e < TM * (g.daug8 - d); e += MF_THREADS) {
-                    const int r = e / (g.daug8 - d), c = d + e % (g.daug8 - d);
-                    Xs[r * g.DP + c] = (c == d && tile0 + r < b) ? 1.0f : 0.0f;
+        // Fragment ch of the sample in row `rowoff` (an offset in floats).  Columns past d are read from a clamped,
+        // valid address instead of being zeroed: they meet the zero padding of the state rows.  Likewise lanes past
+        // the mini-batch read row 0 and their scores are never used.
+        // half-wave 0 reads columns 8*ch + 0..3, half-wave 1 columns 8*ch + 4..7: the last start that is inside a row
+        const int col0 = (half && d >= 8) ? 4 : 0;
+        const int collim = half ? (d >= 8 ? (d - 8) / 8 * 8 + 4 : 0) : (d - 4) / 8 * 8;
+        auto frag = [&](unsigned rowoff, int ch) -> float4 {
+            const int col = ch * 8 + col0 < collim ? ch * 8 + col0 : collim;
+            return *reinterpret_cast<const float4 *>(xb + (rowoff + (unsigned)col));
+        };
+        auto rowoff_of = [&](int tile0) -> unsigned {
+            const int n = tile0 + wave * 32 + l32;
+            return (unsigned)(n < b ? n : 0) * (unsigned)d;
+        };
+        auto fetch_block = [&](float4(&st)[NST], int cb) {       // block cb of the state -> registers
+#pragma unroll
+            for (int q = 0; q < NST; ++q) {
+                const int e = tid + q * MF_THREADS;
+                const int r = (e < NVEC ? e : 0) / ROW4, c4 = (e < NVEC ? e : 0) - r * ROW4;
+                const int c = cb * WB + r, col = 4 * c4;
+                const bool ok = c < k && col < d;
+                float4 v = *reinterpret_cast<const float4 *>(wst + (size_t)(ok ? c : 0) * d + (ok ? col : 0));
+                if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+                st[q] = v;
+            }
+        };
+        auto store_block = [&](const float4(&st)[NST], float *dst) {
+#pragma unroll
+            for (int q = 0; q < NST; ++q) {
+                const int e = tid + q * MF_THREADS;
+                if (e < NVEC) {
+                    const int r = e / ROW4, c4 = e - r * ROW4;
+                    *reinterpret_cast<float4 *>(&dst[r * DP + 4 * c4]) = st[q];
                 }
             }
-            // first block of W' -> LDS buffer 0
-            {
-                const int row4 = g.daug8 >> 2;
-                for (int e = tid; e < WB * row4; e += MF_THREADS) {
-                    const int r = e / row4, c4 = e - r * row4;
-                    *reinterpret_cast<float4 *>(&Ws[r * g.DP + 4 * c4]) =
-                        reinterpret_cast<const float4 *>(waug + (size_t)r * g.daug8)[c4];
-                }
+        };
+        auto do_tile = [&](float4(&xf)[NCH], int tile0) {
+            const bool refill = tile0 + TM < b;
+            float4 st[NST];
+            if constexpr (!RES) {
+                __syncthreads();             // nobody still reads the stage
+                fetch_block(st, 0);
+                store_block(st, Ws);
             }
             Top3 top;
             top.v1 = top.v2 = top.v3 = -INFINITY;
             top.i1 = top.i2 = 0;
-
             for (int cb = 0; cb < g.nblocks; ++cb) {
-                __syncthreads();                        // Ws[cb & 1] (and Xs) complete; Ws[(cb+1) & 1] free
-                const float *Wc = Ws + (cb & 1) * WB * g.DP;
-                float *Wn = Ws + ((cb + 1) & 1) * WB * g.DP;
-                // next block: global -> registers now, -> LDS after the matrix work (at most 3 float4 per thread
-                // per pass of the loop below keeps the register need small)
-                const bool more = cb + 1 < g.nblocks;
-                const float *wsrc = waug + (size_t)(cb + 1) * WB * g.daug8;
-                const int row4 = g.daug8 >> 2, nvec = WB * row4;
-
+                if constexpr (!RES) __syncthreads();      // Ws[cb & 1] complete; Ws[(cb + 1) & 1] free
+                const float *Wc = Ws + (RES ? cb : (cb & 1)) * WB * DP;
+                const bool more = !RES && cb + 1 < g.nblocks;
+                const bool lastb = refill && cb + 1 == g.nblocks;
                 floatx16 acc0, acc1;
+                {
+                    const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { acc0[r] = 0.0f; acc1[r] = 0.0f; }
-                const float *xrow = Xs + (wave * 32 + l32) * g.DP + 4 * half;
-                const float *w0row = Wc + l32 * g.DP + 4 * half;
-                const float *w1row = Wc + (32 + l32) * g.DP + 4 * half;
-                int e_next = tid;
-                for (int ch = 0; ch < g.daug8; ch += 8) {
-                    const float4 xv = *reinterpret_cast<const float4 *>(xrow + ch);
-                    const float4 a0 = *reinterpret_cast<const float4 *>(w0row + ch);
-                    const float4 a1 = *reinterpret_cast<const float4 *>(w1row + ch);
-                    // one vector of the next block per chunk, spread over the matrix work
-                    float4 nv = make_float4(0.f, 0.f, 0.f, 0.f);
-                    const bool ld = more && e_next < nvec;
-                    int nr = 0, nc4 = 0;
-                    if (ld) {
-                        nr = e_next / row4; nc4 = e_next - nr * row4;
-                        nv = reinterpret_cast<const float4 *>(wsrc + (size_t)nr * g.daug8)[nc4];
-                    }
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
-                    if (ld) {
-                        *reinterpret_cast<float4 *>(&Wn[nr * g.DP + 4 * nc4]) = nv;
-                        e_next += MF_THREADS;
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 h0 = hp[2 * q], h1 = hp[8 + 2 * q];
+                        acc0[4 * q + 0] = h0.x; acc0[4 * q + 1] = h0.y; acc0[4 * q + 2] = h0.z; acc0[4 * q + 3] = h0.w;
+                        acc1[4 * q + 0] = h1.x; acc1[4 * q + 1] = h1.y; acc1[4 * q + 2] = h1.z; acc1[4 * q + 3] = h1.w;
                     }
                 }
-                // rest of the next block (when it has more vectors than there were chunks)
-                if (more) {
-                    for (; e_next < nvec; e_next += MF_THREADS) {
-                        const int nr = e_next / row4, nc4 = e_next - nr * row4;
-                        *reinterpret_cast<float4 *>(&Wn[nr * g.DP + 4 * nc4]) =
-                            reinterpret_cast<const float4 *>(wsrc + (size_t)nr * g.daug8)[nc4];
+                const float *w0row = Wc + l32 * DP + 4 * half;
+                const float *w1row = Wc + (32 + l32) * DP + 4 * half;
+                // MODE 0: plain; 1: fetch the next block of the state after the first chunk (not before it: the first
+                // chunk waits for all outstanding loads); 2: last block, refill the fragments.  No control flow
+                // inside, so that the operand reads of a chunk can be scheduled under the matrix work of the previous.
+                auto chunk_loop = [&](auto mode) {
+                    constexpr int MODE = decltype(mode)::value;
+                    unsigned nextoff = 0;
+                    if constexpr (MODE == 2) {
+                        nextoff = rowoff_of(tile0 + TM);
+                        asm volatile("" : "+v"(nextoff));          // keep the address arithmetic inside this block
                     }
-                }
-                // running arg-max of this lane's sample over the 32 centroid rows it sees in this block:
-                // row of register r in a 32x32 tile is 8*(r/4) + 4*half + r%4, visited in increasing order
+                    float4 a0 = *reinterpret_cast<const float4 *>(w0row);
+                    float4 a1 = *reinterpret_cast<const float4 *>(w1row);
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        // operands of the next chunk are read under the matrix work of this one; the scheduling
+                        // barrier keeps the compiler from hoisting the reads of ALL chunks to the top (registers)
+                        float4 n0 = a0, n1 = a1;
+                        if (ch + 1 < NCH) {
+                            n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
+                            n1 = *reinterpret_cast<const float4 *>(w1row + (ch + 1) * 8);
+                        }
+                        const float4 xv = xf[ch];
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
+                        if constexpr (MODE == 1) {
+                            if (ch == 0) fetch_block(st, cb + 1);
+                        }
+                        // the last block has used this fragment for the last time: fetch the next tile's into its
+                        // place, so that the fetch runs behind the matrix work and the epilogue of this tile
+                        if constexpr (MODE == 2) xf[ch] = frag(nextoff, ch);
+                        __builtin_amdgcn_sched_barrier(0);
+                        a0 = n0; a1 = n1;
+                    }
+                };
+                if (more) chunk_loop(std::integral_constant<int, 1>());
+                else if (lastb) chunk_loop(std::integral_constant<int, 2>());
+                else chunk_loop(std::integral_constant<int, 0>());
+                if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
+                // running arg-max of this lane's sample over the 32 rows it sees in this block: register r of a
+                // 32x32 tile is row 8*(r/4) + 4*half + r%4, visited in increasing order
                 const int cbase = cb * WB + 4 * half;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) top3_insert(top, acc0[r], cbase + 8 * (r >> 2) + (r & 3));
@@ -264,65 +334,130 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
                 top3_insert(top, pv2, pi2);
                 top.v3 = fmaxf(top.v3, pv3);
             }
-            const int n = tile0 + wave * 32 + l32;       // this lane pair's sample
+            const int nbase = tile0 + wave * 32;
+            const int n = nbase + l32;                    // this lane pair's sample
             const bool mine = half == 0 && n < b;
             int arg = top.i1;
             const bool close2 = mine && !(top.v1 - top.v2 > thr);
-            // exact decisions, one flagged sample at a time, the whole wave working on it
-            unsigned long long fm = __ballot(close2);
+            const bool close3 = close2 && !(top.v1 - top.v3 > thr);
+            // exact decision between two candidates, four flagged samples at a time:
+            // |x - w_a|^2 - |x - w_b|^2 = sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j), in fp64
+            unsigned long long pm = __ballot(close2 && !close3);
+            while (pm) {
+                int L[4], ca[4], cb2[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    L[q] = -1; ca[q] = 0; cb2[q] = 0;
+                    if (pm) {
+                        L[q] = __builtin_ctzll(pm);
+                        pm &= pm - 1;
+                        ca[q] = __builtin_amdgcn_readlane(top.i1, L[q]);
+                        cb2[q] = __builtin_amdgcn_readlane(top.i2, L[q]);
+                        rechecks += (lane == 0);
+                    }
+                }
+                double dd[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    dd[q] = 0.0;
+                    const float *xl = xb + (size_t)(nbase + (L[q] < 0 ? 0 : L[q])) * d;      // in bounds: that lane was valid
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq, jc = j < d ? j : 0;
+                        const double wa = (double)wst[(size_t)ca[q] * d + jc], wb = (double)wst[(size_t)cb2[q] * d + jc];
+                        const double xx = (double)xl[jc];
+                        if (j < d) dd[q] += (wa - wb) * ((wa + wb) - 2.0 * xx);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const double s = wave_sum_d(dd[q]);
+                    const int lo = ca[q] < cb2[q] ? ca[q] : cb2[q];
+                    const int res = s < 0.0 ? ca[q] : (s > 0.0 ? cb2[q] : lo);
+                    if (lane == L[q]) arg = res;
+                }
+            }
+            // all k distances in fp64, direct form; lane l takes centroids l, l + 64, ...
+            unsigned long long fm = __ballot(close3);
             while (fm) {
                 const int L = __builtin_ctzll(fm);
                 fm &= fm - 1;
-                const int ca = __builtin_amdgcn_readlane(top.i1, L), cb2 = __builtin_amdgcn_readlane(top.i2, L);
-                const float v1L = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(top.v1), L));
-                const float v3L = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(top.v3), L));
-                const float *xl = Xs + (wave * 32 + L) * g.DP;       // the sample (L < 32)
-                int res;
-                if (v1L - v3L > thr) {
-                    // two candidates: |x - w_a|^2 - |x - w_b|^2 = sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j), in fp64
-                    double dd = 0.0;
-                    for (int j = lane; j < d; j += 64) {
-                        const double wa = (double)wst[(size_t)ca * d + j], wb = (double)wst[(size_t)cb2 * d + j];
-                        dd += (wa - wb) * ((wa + wb) - 2.0 * (double)xl[j]);
+                const float *xl = xb + (size_t)(nbase + L) * d;
+                double best = INFINITY;
+                int barg = 0x7fffffff;
+                for (int c = lane; c < k; c += 64) {
+                    double sd = 0.0;
+                    for (int j = 0; j < d; ++j) {
+                        const double diff = (double)xl[j] - (double)wst[(size_t)c * d + j];
+                        sd += diff * diff;
                     }
-                    dd = wave_sum_d(dd);
-                    const int lo = ca < cb2 ? ca : cb2;
-                    res = dd < 0.0 ? ca : (dd > 0.0 ? cb2 : lo);
-                } else {
-                    // all k distances in fp64, direct form; lane l takes centroids l, l+64, ...
-                    double best = INFINITY;
-                    int barg = 0x7fffffff;
-                    for (int c = lane; c < k; c += 64) {
-                        double sd = 0.0;
-                        for (int j = 0; j < d; ++j) {
-                            const double diff = (double)xl[j] - (double)wst[(size_t)c * d + j];
-                            sd += diff * diff;
-                        }
-                        if (sd < best) { best = sd; barg = c; }
-                    }
-#pragma unroll
-                    for (int off = 32; off > 0; off >>= 1) {
-                        const double ob = __shfl_xor(best, off, 64);
-                        const int oa = __shfl_xor(barg, off, 64);
-                        if (ob < best || (ob == best && oa < barg)) { best = ob; barg = oa; }
-                    }
-                    res = barg;
+                    if (sd < best) { best = sd; barg = c; }
                 }
-                if (lane == L) arg = res;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const double ob = __shfl_xor(best, off, 64);
+                    const int oa = __shfl_xor(barg, off, 64);
+                    if (ob < best || (ob == best && oa < barg)) { best = ob; barg = oa; }
+                }
+                if (lane == L) arg = barg;
                 rechecks += (lane == 0);
             }
             if (mine) {
                 idx[n] = (unsigned short)arg;
                 if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
             }
+        };
+        if constexpr (RES) {
+            {
+                float4 st[NST];
+                for (int cb = 0; cb < g.nblocks; ++cb) {     // the whole state -> LDS (readers of the old one are done)
+                    fetch_block(st, cb);
+                    store_block(st, Ws + cb * WB * DP);
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
+        {
+            float4 xa[NCH];
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) xa[ch] = frag(rowoff_of(0), ch);
+            for (int tile0 = 0; tile0 < b; tile0 += TM) do_tile(xa, tile0);
+        }
 
         // ================= phase 2: gradient, merge, update =================
+        {
+        int lane_p2 = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane_p2));
+        const int lane = lane_p2, tid = wave * 64 + lane;
+        // ---- stable counting sort of the samples by centroid slot ----
+        for (int s = tid; s < g.ns; s += MF_THREADS) cursor[s] = 0;
+        __syncthreads();                                   // also: idx complete
+        for (int n = tid; n < b; n += MF_THREADS) {
+            const int c = idx[n];
+            atomicAdd(&cursor[(c & 7) * g.kq + (c >> 3)], 1);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            int running = 0;
+            for (int base = 0; base < g.ns; base += 64) {
+                const int s = base + lane;
+                const int v = s < g.ns ? cursor[s] : 0;
+                int incl = v;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int o = __shfl_up(incl, off, 64);
+                    if (lane >= off) incl += o;
+                }
+                const int excl = incl - v + running;
+                if (s < g.ns) { cstart[s] = excl; cursor[s] = excl; }
+                running += __shfl(incl, 63, 64);
+            }
+            if (lane == 0) cstart[g.ns] = running;
+        }
         const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && (t % p.E) == 0);
         const long long r_now = p.E > 0 ? t / p.E : 0;
         const int rpar = det ? (int)((r_now - 1) & 1) : 0;
-        if (tid == 0) {
+        if (tid == MF_THREADS - 1) {
             int has = 0;
             if (merge_point) {
                 const int st = p.stamp[(size_t)rpar * p.W + i];
@@ -332,67 +467,128 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
             s_has_ext = has;
         }
         __syncthreads();
-        const bool has_ext = s_has_ext != 0;
-        const float *ext = p.slot + ((size_t)rpar * p.W + i) * kd;
-
-        // pass A: per centroid, sums of the assigned samples in sample order -> gradient; Parzen sums
-        double lhs = 0.0, rhs = 0.0, nrm = 0.0;
-        for (int c = wave; c < k; c += MF_WAVES) {
+        // placement: every wave walks all samples in order and places those of its own centroids
+        for (int n0 = 0; n0 < b; n0 += 64) {
+            const int n = n0 + lane;
+            const int c = n < b ? (int)idx[n] : -1;
+            const bool own = n < b && (c & 7) == wave;
+            unsigned long long rem = __ballot(own);
+            int rank = 0;
+            bool last = false;
+            while (rem) {
+                const int L = __builtin_ctzll(rem);
+                const int cL = __builtin_amdgcn_readlane(c, L);
+                const unsigned long long same = __ballot(own && c == cL);
+                if (own && c == cL) {
+                    rank = __popcll(same & ((1ull << lane) - 1ull));
+                    last = (same >> lane) == 1ull;
+                }
+                rem &= ~same;
+            }
+            if (own) {
+                const int s = (c & 7) * g.kq + (c >> 3);
+                const int base = cursor[s];
+                perm[base + rank] = (unsigned short)n;
+                if (last) cursor[s] = base + rank + 1;
+            }
+        }
+        // gather: this wave's samples in (centroid, sample) order, GS rows in flight
+        {
+            const int pos0 = __builtin_amdgcn_readfirstlane(cstart[wave * g.kq]);
+            const int pos1 = __builtin_amdgcn_readfirstlane(cstart[(wave + 1) * g.kq]);
+            int cur = -1;
             float S[NJ];
 #pragma unroll
-            for (int q = 0; q < NJ; ++q) S[q] = 0.0f;
-            int cnt = 0;
-            for (int n0 = 0; n0 < b; n0 += 64) {
-                const int nn = n0 + lane;
-                unsigned long long m = __ballot(nn < b && (int)idx[nn < b ? nn : 0] == c);
-                while (m) {
-                    int ns[4];
+            for (int jq = 0; jq < NJ; ++jq) S[jq] = 0.0f;
+            for (int g0 = pos0; g0 < pos1; g0 += GS) {
+                const int myid = (lane < GS && g0 + lane < pos1) ? (int)perm[g0 + lane] : -1;
+                const int myc = myid >= 0 ? (int)idx[myid] : -1;
+                float v[GS][NJ];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (m) { ns[q] = n0 + __builtin_ctzll(m); m &= m - 1; ++cnt; }
-                        else ns[q] = -1;
+                for (int q = 0; q < GS; ++q) {
+                    const int id = __builtin_amdgcn_readlane(myid, q);
+                    const float *row = xb + (size_t)(id < 0 ? 0 : id) * d;
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        v[q][jq] = row[j < d ? j : 0];
                     }
-                    float v[4][NJ];
+                }
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < GS; ++q) {
+                    const int cq = __builtin_amdgcn_readlane(myc, q);
+                    if (cq >= 0) {
+                        if (cq != cur) {
+                            if (cur >= 0) {
 #pragma unroll
-                        for (int jq = 0; jq < NJ; ++jq) {
-                            const int j = lane + 64 * jq;
-                            v[q][jq] = (ns[q] >= 0 && j < d) ? xb[(size_t)ns[q] * d + j] : 0.0f;
+                                for (int jq = 0; jq < NJ; ++jq) {
+                                    const int j = lane + 64 * jq;
+                                    if (j < d) gsc[(size_t)cur * d + j] = S[jq];
+                                }
+                            }
+                            cur = cq;
+#pragma unroll
+                            for (int jq = 0; jq < NJ; ++jq) S[jq] = 0.0f;
                         }
-                    }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
 #pragma unroll
                         for (int jq = 0; jq < NJ; ++jq) S[jq] += v[q][jq];
                     }
                 }
             }
+            if (cur >= 0) {
 #pragma unroll
-            for (int jq = 0; jq < NJ; ++jq) {
-                const int j = lane + 64 * jq;
-                if (j < d) {
-                    const size_t e = (size_t)c * d + j;
-                    const float w = wst[e];
-                    const float gq = ((float)cnt * w - S[jq]) / (float)b;      // descent gradient of Eq. 9
-                    gsc[e] = gq;
-                    if (has_ext) {
-                        const double we = (double)ext[e];
-                        const double a = ((double)w - (double)p.eps * (double)gq) - we;
-                        const double c2 = (double)w - we;
-                        lhs += a * a; rhs += c2 * c2; nrm += we * we;
-                    }
+                for (int jq = 0; jq < NJ; ++jq) {
+                    const int j = lane + 64 * jq;
+                    if (j < d) gsc[(size_t)cur * d + j] = S[jq];
                 }
             }
         }
+        __threadfence_block();
+        __syncthreads();
+
+        const bool has_ext = s_has_ext != 0;
+        const float *ext = p.slot + ((size_t)rpar * p.W + i) * kd;
+        // ---- Parzen sums (Eq. 4) over the whole state, fp64 ----
         int delta = 0;
         if (has_ext) {       // uniform over the workgroup
+            double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+            for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
+                float w[RB][NJ], sm[RB][NJ], we[RB][NJ];
+                int cn[RB];
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    const int c = c0 + q < k ? c0 + q : k - 1;
+                    const int s = (c & 7) * g.kq + (c >> 3);
+                    cn[q] = cstart[s + 1] - cstart[s];
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        const size_t e = (size_t)c * d + (j < d ? j : 0);
+                        w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = ext[e];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        if (c0 + q < k && j < d) {
+                            const float sums = cn[q] > 0 ? sm[q][jq] : 0.0f;
+                            const float gq = ((float)cn[q] * w[q][jq] - sums) / (float)b;     // descent gradient of Eq. 9
+                            const double wed = (double)we[q][jq];
+                            const double a = ((double)w[q][jq] - (double)p.eps * (double)gq) - wed;
+                            const double c2 = (double)w[q][jq] - wed;
+                            lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
+                        }
+                    }
+                }
+            }
             lhs = wave_sum_d(lhs); rhs = wave_sum_d(rhs); nrm = wave_sum_d(nrm);
             if (lane == 0) { red_d[0][wave] = lhs; red_d[1][wave] = rhs; red_d[2][wave] = nrm; }
             __syncthreads();
-            lhs = ((red_d[0][0] + red_d[0][1]) + red_d[0][2]) + red_d[0][3];
-            rhs = ((red_d[1][0] + red_d[1][1]) + red_d[1][2]) + red_d[1][3];
-            nrm = ((red_d[2][0] + red_d[2][1]) + red_d[2][2]) + red_d[2][3];
+            lhs = rhs = nrm = 0.0;
+#pragma unroll
+            for (int v = 0; v < MF_WAVES; ++v) { lhs += red_d[0][v]; rhs += red_d[1][v]; nrm += red_d[2][v]; }
             if (nrm > 0.0) {                          // lambda of Eq. 3
                 delta = p.parzen ? (lhs < rhs) : 1;   // Eq. 4
                 if (tid == 0) {
@@ -403,32 +599,55 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
                 }
             }
         }
-        // pass B: Eq. 7, Alg. 5 line 8; refresh the augmented copy and max |w_c|^2
-        wn2max = 0.0f;
-        for (int c = wave; c < k; c += MF_WAVES) {
-            float s = 0.0f;
+        // ---- update: Eq. 7, Alg. 5 line 8; new offsets h_c and max |w_c|^2 ----
+        {
+            const float *extp = delta ? ext : wst;        // read something valid when there is nothing to merge
+            wn2max = 0.0f;
+            for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
+                float w[RB][NJ], sm[RB][NJ], we[RB][NJ], s2[RB];
+                int cn[RB];
 #pragma unroll
-            for (int jq = 0; jq < NJ; ++jq) {
-                const int j = lane + 64 * jq;
-                if (j < d) {
-                    const size_t e = (size_t)c * d + j;
-                    const float w = wst[e];
-                    float step = gsc[e];
-                    if (delta) step += w - 0.5f * (w + ext[e]);
-                    const float wn = w - p.eps * step;
-                    wst[e] = wn;
-                    waug[(size_t)c * g.daug8 + j] = wn;
-                    s = fmaf(wn, wn, s);
+                for (int q = 0; q < RB; ++q) {
+                    const int c = c0 + q < k ? c0 + q : k - 1;
+                    const int s = (c & 7) * g.kq + (c >> 3);
+                    cn[q] = cstart[s + 1] - cstart[s];
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        const size_t e = (size_t)c * d + (j < d ? j : 0);
+                        w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = extp[e];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    s2[q] = 0.0f;
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        if (c0 + q < k && j < d) {
+                            const float sums = cn[q] > 0 ? sm[q][jq] : 0.0f;
+                            float step = ((float)cn[q] * w[q][jq] - sums) / (float)b;
+                            if (delta) step += w[q][jq] - 0.5f * (w[q][jq] + we[q][jq]);
+                            const float wn = w[q][jq] - p.eps * step;
+                            wst[(size_t)(c0 + q) * d + j] = wn;
+                            s2[q] = fmaf(wn, wn, s2[q]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    const float sq = wave_sum_f(s2[q]);
+                    if (lane == 0 && c0 + q < k) hs[c0 + q] = -0.5f * sq;
+                    wn2max = fmaxf(wn2max, sq);
                 }
             }
-            s = wave_sum_f(s);
-            if (lane == 0) waug[(size_t)c * g.daug8 + d] = -0.5f * s;
-            wn2max = fmaxf(wn2max, s);
+            if (lane == 0) red_f[wave] = wn2max;
+            __threadfence_block();
+            __syncthreads();
+            wn2max = 0.0f;
+#pragma unroll
+            for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
         }
-        if (lane == 0) red_f[wave] = wn2max;
-        __threadfence_block();
-        __syncthreads();
-        wn2max = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
 
         // ---- send (Alg. 5 line 9) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
@@ -436,8 +655,9 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
             if (!message_dropped(p.seed, r, i, p.drop_thr)) {
                 const int peer = det ? peer_deterministic(p.seed, r, i, p.W) : peer_free(p.seed, r, i, p.W);
                 const int spar = det ? (int)(r & 1) : 0;
-                float *dst = p.slot + ((size_t)spar * p.W + peer) * kd;
-                for (size_t e = tid; e < kd; e += MF_THREADS) dst[e] = wst[e];
+                float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)spar * p.W + peer) * kd);
+                const float4 *src = reinterpret_cast<const float4 *>(wst);
+                for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
                 __threadfence();
                 __syncthreads();
                 if (tid == 0) p.stamp[(size_t)spar * p.W + peer] = (int)r;
@@ -445,6 +665,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }
         __syncthreads();
+        }
     }
 
     rechecks = (long long)wave_sum_d((double)rechecks);
@@ -452,24 +673,30 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
         atomicAdd((unsigned long long *)&p.counters[(size_t)i * CNT_STRIDE + CNT_RECHECK], (unsigned long long)rechecks);
 }
 
-size_t mfma_lds_bytes(int k, int d, int b)
+constexpr size_t MF_LDS_BUDGET = 150 * 1024;
+
+template <int NCH, bool RES>
+hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
 {
-    const MfmaGeom g = mfma_geom(k, d);
-    return ((size_t)TM * g.DP + 2 * (size_t)WB * g.DP) * sizeof(float) + ((size_t)b * sizeof(unsigned short) + 15) / 16 * 16;
+    const size_t lds = mfma_geom(p.k, p.b, NCH, RES).bytes;
+    hipError_t e = hipFuncSetAttribute((const void *)mfma_steps_kernel<NCH, RES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES>), dim3(p.W), dim3(MF_THREADS), lds, s, p, t0, t1, xnorm2max);
+    return hipGetLastError();
+}
+template <int NCH>
+hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
+{
+    if (mfma_geom(p.k, p.b, NCH, true).bytes <= MF_LDS_BUDGET) return launch_variant<NCH, true>(p, t0, t1, xnorm2max, s);
+    return launch_variant<NCH, false>(p, t0, t1, xnorm2max, s);
 }
 
 }  // namespace
 
 bool mfma_kernel_supports(int k, int d, int b, const void *x)
 {
-    if (d % 4 != 0 || d > 128 || k < 2 || k > 65535 || (((uintptr_t)x) & 15u) != 0) return false;
-    return mfma_lds_bytes(k, d, b) <= 150 * 1024;
-}
-
-size_t mfma_waug_floats(int k, int d, int W)
-{
-    const MfmaGeom g = mfma_geom(k, d);
-    return (size_t)W * g.kpad * g.daug8;
+    if (d % 4 != 0 || d > 128 || k < 2 || k > 32768 || b > 65535 || (((uintptr_t)x) & 15u) != 0) return false;
+    return mfma_geom(k, b, mfma_chunks(d), false).bytes <= MF_LDS_BUDGET;
 }
 
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s)
@@ -486,21 +713,14 @@ hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out,
     return e != hipSuccess ? e : e2;
 }
 
-hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, float *waug, const float *xnorm2max,
-                             hipStream_t s)
+hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
 {
-    const size_t lds = mfma_lds_bytes(p.k, p.d, p.b);
-    hipError_t e;
-    if (p.d <= 64) {
-        e = hipFuncSetAttribute((const void *)mfma_steps_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((mfma_steps_kernel<1>), dim3(p.W), dim3(MF_THREADS), lds, s, p, t0, t1, waug, xnorm2max);
-    } else {
-        e = hipFuncSetAttribute((const void *)mfma_steps_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((mfma_steps_kernel<2>), dim3(p.W), dim3(MF_THREADS), lds, s, p, t0, t1, waug, xnorm2max);
+    switch (mfma_chunks(p.d)) {
+        case 4: return launch_nch<4>(p, t0, t1, xnorm2max, s);
+        case 8: return launch_nch<8>(p, t0, t1, xnorm2max, s);
+        case 13: return launch_nch<13>(p, t0, t1, xnorm2max, s);
+        default: return launch_nch<16>(p, t0, t1, xnorm2max, s);
     }
-    return hipGetLastError();
 }
 
 }  // namespace asgd
