@@ -198,6 +198,10 @@ class ASGD:
         self._dump = torch.empty(steps * self.W * self.b, dtype=torch.int32, device=self._x.device)
         asgd_set_assign_dump(self.h, self._dump.data_ptr(), self._dump.numel())
 
+    def disable_assign_dump(self):
+        asgd_set_assign_dump(self.h, None, 0)
+        self._dump = None
+
     def assign_dump(self, steps):
         return self._dump[:steps * self.W * self.b].cpu().numpy().reshape(steps, self.W, self.b)
 
