@@ -5,6 +5,10 @@ A "step" is one pass of the whole path (assignment, gradient, merge, update, sen
 synthetic streaming workload: one epoch of N = 1e8 fp32 samples, d = 10, k = 10, W = 1024
 workers, b = 1000, exchange every 8 mini-batches, deterministic mode.  The samples are
 resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+--config 2, 3 or 4 times the other workloads the same way (one epoch per step): the wider one
+(k = d = 100), the 100 GB one, and the contraction-bound one (k = 1024, d = 128), whose roofline
+is the fp32 matrix-core peak instead of the HBM bandwidth.
 """
 import argparse
 import json
@@ -17,11 +21,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_MATRIX_PEAK_TFLOPS = 157.3 # MI355X published dense fp32 matrix (and packed vector) rate
+KERNEL_NAMES = {1: "generic_steps_kernel", 2: "small_steps_kernel", 3: "mfma_steps_kernel"}
 
 
-def traffic_from_profile():
+def traffic_from_profile(kernel_name, workload_name):
     """HBM bytes per launch measured with rocprofv3 counters (committed summary), or None."""
-    path = os.path.join(ROOT, "profiles", "small_steps_kernel_cfg1_streaming_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel_name, workload_name))
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
         return float(m.group(1)) if m else None
@@ -29,19 +35,28 @@ def traffic_from_profile():
         return None
 
 
-def cpu_baseline(wl, X_host):
-    """The oracle as it stands, timed on the host cores over one full epoch of the same samples."""
+def cpu_baseline(wl, X):
+    """The oracle as it stands, timed on the host cores over the first steps of the same workload: as many
+    steps (all W workers each) as about 20 s of CPU work allow, at most one epoch."""
     from oracle import asgd_oracle
     asgd_oracle.build()
     cores = min(asgd_oracle.threads(), 16)
     asgd_oracle.set_threads(cores)
-    o = asgd_oracle.OracleASGD(X_host, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+    est_rate = cores * 4.0e8 / (wl.k * wl.d)              # rough samples/s of the fp64 oracle, to size the sample
+    steps = int(max(1, min(wl.S, 20.0 * est_rate / (wl.W * wl.b))))
+    if steps > wl.E >= 1:
+        steps = min(wl.S, max(steps, 2 * wl.E + 1))       # at least two communication rounds
+    rows = steps * wl.b
+    # the rows those steps touch, shard by shard (for the 100 GB workload the whole array would not fit the host)
+    Xc = X[:wl.W * wl.H].view(wl.W, wl.H, wl.d)[:, :rows, :].contiguous().cpu().numpy().reshape(wl.W * rows, wl.d)
+    o = asgd_oracle.OracleASGD(Xc, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
     t0 = time.perf_counter()
-    o.run_epochs(1)
+    o.run_steps(steps)
     dt = time.perf_counter() - t0
-    return {"value": wl.processed_per_epoch / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
-            "sample": "one full epoch of the same workload (%d samples), fp64, %d OpenMP threads over workers"
-                      % (wl.processed_per_epoch, cores)}, o
+    n = steps * wl.W * wl.b
+    return {"value": n / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": "the first %d of the %d steps of an epoch of the same workload, all %d workers (%d samples, %.1f s), "
+                      "fp64, %d OpenMP threads over workers" % (steps, wl.S, wl.W, n, dt, cores)}
 
 
 def main():
@@ -98,7 +113,19 @@ def main():
     value = args.steps * samples / elapsed
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
     algo_bytes = samples * wl.d * 4            # one read of every processed sample
-    achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    algo_flops = samples * (2.0 * wl.k * wl.d + wl.k + wl.d)   # expanded-form scores, compares, accumulation
+    kname = KERNEL_NAMES.get(int(st.kernel), "?")
+    if int(st.kernel) == B.KERNEL_MFMA:
+        achieved = algo_flops / (avg_kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": FP32_MATRIX_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / FP32_MATRIX_PEAK_TFLOPS, "algorithmic_flops_per_step": algo_flops,
+                    "hbm_GBps": algo_bytes / (avg_kernel_ms * 1e-3) / 1e9}
+    else:
+        achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBPS, "algorithmic_bytes_per_launch": algo_bytes}
+    roofline.update({"traffic": traffic_from_profile(kname, wl.name), "kernel": kname, "kernel_ms": avg_kernel_ms,
+                     "launches": int(st.launches)})
     out = {
         "metric": "samples/sec (assign+grad+update+merge) and % of peak HBM GB/s, 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -107,17 +134,12 @@ def main():
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "k": wl.k, "W": wl.W, "b": wl.b, "lr": wl.lr,
                    "exchange_every": wl.E, "epochs_per_step": 1, "mode": "deterministic",
                    "samples_per_step": samples, "kernel": int(st.kernel), "launches_per_step": int(st.launches)},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profile(),
-                     "kernel": "small_steps_kernel", "kernel_ms": avg_kernel_ms,
-                     "algorithmic_bytes_per_launch": algo_bytes},
+        "roofline": roofline,
         "stats": {"messages_sent": int(st.sent), "messages_received": int(st.received),
                   "messages_accepted": int(st.accepted), "exact_rechecks": int(st.exact_rechecks)},
     }
     if not args.no_cpu_baseline:
-        X_host = X.cpu().numpy()
-        base, _ = cpu_baseline(wl, X_host)
-        out["cpu_baseline"] = base
+        out["cpu_baseline"] = cpu_baseline(wl, X)
     print(json.dumps(out), flush=True)
     g.close()
 
