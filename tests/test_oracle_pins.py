@@ -401,3 +401,24 @@ def test_configs_table():
     c = workloads.CONFIGS
     assert [(x.H, x.S) for x in c] == [(25000, 50), (97656, 97), (39062, 19), (610351, 610), (19531, 4)]
     assert c[1].processed_per_epoch == 99_328_000 and c[4].processed_per_epoch == 4_194_304
+
+
+def test_stored_values_of_tiny_workload(oracle):
+    """The stored values under tests/golden were written by tests/golden/make_golden.py (oracle only);
+    the oracle must still produce them (guards against silent changes of its arithmetic)."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.compute()
+    stored = json.load(open(os.path.join(here, "golden", "cfg0_oracle.json")))
+    assert now["counters_sent_received_accepted"] == stored["counters_sent_received_accepted"]
+    assert now["peers_round0"] == stored["peers_round0"]
+    for key in ("quant_error_worker0_by_epoch", "state_worker0_row0", "state_sum_by_worker"):
+        assert np.allclose(now[key], stored[key], rtol=1e-12, atol=0), key
+    assert abs(now["quant_error_mean_state"] - stored["quant_error_mean_state"]) <= 1e-12 * stored["quant_error_mean_state"]
+    qe = stored["quant_error_worker0_by_epoch"]
+    assert all(b < a for a, b in zip(qe, qe[1:]))          # Eq. 8 falls epoch by epoch on this workload

@@ -228,6 +228,64 @@ def test_matrix_core_kernel_options(B, oracle):
         bad.run_steps(1)
 
 
+def test_stored_values_of_tiny_workload(B):
+    """GPU path against the values the oracle wrote to tests/golden/cfg0_oracle.json."""
+    import json
+    import os
+    stored = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg0_oracle.json")))
+    wl = workloads.CONFIGS[0]
+    X = workloads.generate_host(wl)
+    for kernel in (0, 1):
+        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, kernel=kernel)
+        g.load_shards(to_dev(X))
+        qe = [g.quant_error(0)]
+        for _ in range(wl.epochs):
+            g.run_epochs(1)
+            qe.append(g.quant_error(0))
+        assert np.allclose(qe, stored["quant_error_worker0_by_epoch"], rtol=TOL, atol=0)
+        st = g.stats()
+        assert [st.sent, st.received, st.accepted] == stored["counters_sent_received_accepted"]
+        w = g.get_state()
+        assert np.allclose(w[0, 0], stored["state_worker0_row0"], rtol=TOL)
+        assert np.allclose(w.reshape(wl.W, -1).sum(1), stored["state_sum_by_worker"], rtol=TOL)
+        assert abs(g.quant_error(-1) - stored["quant_error_mean_state"]) <= TOL * stored["quant_error_mean_state"]
+        assert [B.asgd_schedule_peer(wl.schedule_seed, 0, i, wl.W) for i in range(wl.W)] == stored["peers_round0"]
+
+
+@pytest.mark.parametrize("kernel,k,d,W,b,E", [
+    (2, 10, 10, 64, 500, 2),        # small-state kernel
+    (1, 10, 10, 64, 500, 2),        # generic kernel
+    (3, 64, 32, 16, 512, 2),        # matrix-core kernel
+])
+def test_free_running_mode(B, kernel, k, d, W, b, E):
+    """Free-running mode keeps the paper's races (Sec. 4.4): every sender draws its own recipient, a later
+    message overwrites an earlier one, a buffer may be read while it is written.  The result is not
+    reproducible, so there is no element-wise parity; what must hold: finite states, every worker sends once
+    per round, nobody receives more than was sent, and the quantization error (Eq. 8) ends close to that of
+    the deterministic run on the same data."""
+    steps = 40
+    X = make_data(W * b * 12, d, k, seed=31)
+    Xg = to_dev(X)
+    res = {}
+    for mode in (B.MODE_DETERMINISTIC, B.MODE_FREE_RUNNING):
+        g = B.ASGD(k, d, W, b, 0.05, E=E, seed=5, mode=mode, kernel=kernel)
+        g.load_shards(Xg)
+        q0 = g.quant_error(0)
+        g.run_steps(steps)
+        st = g.stats()
+        w = g.get_state()
+        assert st.kernel == kernel and np.all(np.isfinite(w))
+        assert st.sent == W * (steps // E)
+        assert 0 < st.received <= st.sent and 0 <= st.accepted <= st.received
+        res[mode] = (g.quant_error(0), g.quant_error(-1), st)
+        assert res[mode][0] < q0
+    qd, qf = res[B.MODE_DETERMINISTIC], res[B.MODE_FREE_RUNNING]
+    print("\n[free-running] kernel %d: E(w_0) deterministic %.6g, free-running %.6g; received %d vs %d of %d sent"
+          % (kernel, qd[0], qf[0], qd[2].received, qf[2].received, qf[2].sent))
+    assert abs(qf[0] - qd[0]) <= 0.2 * qd[0]             # about half of the messages are overwritten before use
+    assert qd[2].received == W * ((steps - 1) // E)      # the cyclic shift delivers exactly one message per worker and round
+
+
 def test_error_paths(B):
     import torch
     with pytest.raises(B.AsgdError):
