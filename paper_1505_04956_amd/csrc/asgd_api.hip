@@ -31,6 +31,9 @@ struct asgd_ctx {
 
     float *w = nullptr, *slot = nullptr, *acc = nullptr, *xabsmax = nullptr, *mean = nullptr;
     float *xnorm2max = nullptr;    // matrix-core kernel only, allocated on first use
+    size_t slot_bytes = 0;         // size of the exchange buffers (both parities, all workers)
+    int *shift_tab = nullptr;      // schedule table of the small-state kernel, grown on demand
+    long long shift_cap = 0;
     bool xnorm2max_valid = false;
     int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
     long long *ncum = nullptr, *counters = nullptr;
@@ -60,7 +63,7 @@ size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
 void free_all(asgd_ctx *c)
 {
     void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->consumed, c->cnt, c->assign_tmp,
-                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max};
+                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max, c->shift_tab};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
@@ -85,7 +88,9 @@ StepParams make_params(const asgd_ctx *c)
 
 int clear_exchange(asgd_ctx *c)
 {
-    HIP_TRY(c, hipMemsetAsync(c->slot, 0, 2 * (size_t)c->W * kd_of(c) * sizeof(float), c->stream));
+    // all bits set: empty in both message formats (stamp -1 inside the small-state kernel's pairs; the other
+    // kernels look at `stamp` before they read a buffer)
+    HIP_TRY(c, hipMemsetAsync(c->slot, 0xFF, c->slot_bytes, c->stream));
     HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->W * sizeof(int), c->stream));   // -1
     return ASGD_OK;
 }
@@ -128,9 +133,13 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { delete c; return ASGD_EHIP; }
     const size_t kd = kd_of(c), Wz = (size_t)W;
+    {
+        const size_t plain = kd * sizeof(float), own = small_kernel_message_bytes(k, d);
+        c->slot_bytes = 2 * Wz * (plain > own ? plain : own);
+    }
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&c->w, Wz * kd * sizeof(float)},
-        {(void **)&c->slot, 2 * Wz * kd * sizeof(float)},
+        {(void **)&c->slot, c->slot_bytes},
         {(void **)&c->acc, Wz * kd * sizeof(float)},
         {(void **)&c->xabsmax, (size_t)d * sizeof(float)},
         {(void **)&c->mean, kd * sizeof(float)},
@@ -307,8 +316,30 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         }
     }
 
+    // The kernels keep a message in flight in different formats; one is in flight exactly at a merge point.
+    if (ctx->last_kernel != 0 && kernel != ctx->last_kernel && ctx->E > 0 && ctx->W > 1 && ctx->t > 0 &&
+        ctx->t % ctx->E == 0)
+        return ASGD_ESTATE;
+
     StepParams p = make_params(ctx);
     const long long t_end = ctx->t + steps;
+    if (kernel == ASGD_KERNEL_SMALL && ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1 && steps > 0) {
+        // cyclic shifts of the rounds this call touches: the round before the first step up to the last step's
+        const long long r_lo = ctx->t / ctx->E > 0 ? ctx->t / ctx->E - 1 : 0;
+        const long long r_hi = (t_end - 1) / ctx->E;
+        const long long n = r_hi - r_lo + 1;
+        if (n > (long long)1 << 30) return ASGD_EINVAL;
+        if (n > ctx->shift_cap) {
+            if (ctx->shift_tab) (void)hipFree(ctx->shift_tab);
+            ctx->shift_tab = nullptr;
+            ctx->shift_cap = 0;
+            HIP_TRY(ctx, hipMalloc((void **)&ctx->shift_tab, (size_t)n * sizeof(int)));
+            ctx->shift_cap = n;
+        }
+        HIP_TRY(ctx, launch_schedule_table(ctx->seed, r_lo, (int)n, ctx->W, ctx->shift_tab, ctx->stream));
+        p.shift_tab = ctx->shift_tab;
+        p.shift_r0 = r_lo;
+    }
     // Deterministic mode: a worker may only read the message of round r-1 once its sender has
     // finished that round.  Either the whole run is one launch of co-resident workgroups that wait
     // for each other's stamps (small-state kernel), or a launch never crosses a multiple of E, so

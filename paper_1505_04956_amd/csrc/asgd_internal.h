@@ -49,7 +49,7 @@ enum { CNT_SENT = 0, CNT_RECEIVED = 1, CNT_ACCEPTED = 2, CNT_PARZEN_NEAR = 3, CN
 struct StepParams {
     const float *x;        // N x d samples
     float *w;              // W x k x d states
-    float *slot;           // 2 x W x k x d exchange buffers (parity, worker)
+    float *slot;           // 2 x W exchange buffers (parity, worker): k x d floats, or the small-state kernel's pairs
     int *stamp;            // 2 x W round number of the buffered message, -1 = empty
     int *consumed;         // W: last round whose merge point the worker has passed
     long long *ncum;       // W x k cumulative counts (1/count step size only)
@@ -60,6 +60,8 @@ struct StepParams {
     int32_t *dump;         // optional assignment dump (step-major), or nullptr
     const float *xabsmax;  // d per-dimension max |x| over the loaded samples
     int *error_flag;       // set non-zero by a kernel whose bounded wait expired
+    const int *shift_tab;  // deterministic schedule: cyclic shift of round r at [r - shift_r0] (small-state kernel)
+    long long shift_r0;
     long long H, S;        // shard length, steps per epoch
     long long t_dump0;     // step counter value at which the dump buffer starts
     uint64_t seed;
@@ -76,12 +78,16 @@ hipError_t launch_init_first_k(const StepParams &p, hipStream_t s);
 hipError_t launch_absmax(const float *x, long long rows, int d, float *out, hipStream_t s);
 hipError_t launch_generic_steps(const StepParams &p, long long t0, long long t1, hipStream_t s);
 bool small_kernel_supports(int k, int d, int b);
+// bytes of one exchange buffer in the small-state kernel's own message format (0: kernel not applicable)
+size_t small_kernel_message_bytes(int k, int d);
 // persistent = true: the whole range in one cooperative launch with in-kernel waits between rounds
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent);
 // Matrix-core kernel: needs d % 4 == 0, d <= 128, 16-byte aligned samples and its LDS budget.
 bool mfma_kernel_supports(int k, int d, int b, const void *x);
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s);   // max_n |x_n|^2
 hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s);
+// shift_tab[q] = 1 + round_hash(seed, r0 + q) % (W - 1) for q in [0, n)
+hipError_t launch_schedule_table(uint64_t seed, long long r0, int n, int W, int *shift_tab, hipStream_t s);
 hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s);
 // Eq. 8 over rows [0, N): partials is scratch of quant_partials_count() doubles.
 int quant_partials_count();

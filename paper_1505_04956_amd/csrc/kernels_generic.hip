@@ -371,6 +371,18 @@ hipError_t launch_quant_error(const float *x, long long N, int d, int k, const f
     return hipGetLastError();
 }
 
+__global__ void schedule_table_kernel(uint64_t seed, long long r0, int n, int W, int *shift_tab)
+{
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < n) shift_tab[q] = (int)(1 + round_hash(seed, r0 + q) % (uint64_t)(W - 1));
+}
+
+hipError_t launch_schedule_table(uint64_t seed, long long r0, int n, int W, int *shift_tab, hipStream_t s)
+{
+    hipLaunchKernelGGL(schedule_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, seed, r0, n, W, shift_tab);
+    return hipGetLastError();
+}
+
 hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s)
 {
     hipLaunchKernelGGL(mean_state_kernel, dim3((kd + 255) / 256), dim3(256), 0, s, w, W, kd, out);

@@ -123,15 +123,23 @@ __device__ __forceinline__ void phase_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
-// Exchange buffers are written and read with relaxed device-scope atomic accesses: these go through
-// to the memory level all workgroups share, so that no cache-wide write-back or invalidation is
-// needed.  Order (payload before stamp on the sender, stamp before payload on the receiver) is kept
-// by waiting for the outstanding accesses of the wave (a workgroup-scope fence) in between.
-__device__ __forceinline__ void store_shared(float *p, float v)
+// A message of this kernel is self-validating: every element travels as a 64-bit pair (value, round
+// stamp), written and read with relaxed device-scope 64-bit atomic accesses (single-copy atomic; they go
+// through to the memory level all workgroups share, so no cache-wide write-back or invalidation is
+// needed).  The receiver accepts a message when every pair carries the expected stamp.  Hence the sender
+// needs no ordering between payload and a separate flag - it never waits for its stores, which on this
+// chip would also drain the sample loads in flight - and the receiver can fetch the pairs long before it
+// needs them and only has to look again if they had not arrived yet.  A message of lane l < NT is the four
+// pairs [4l, 4l+4) of its buffer (task layout, elements that do not exist included).
+__device__ __forceinline__ unsigned long long pack_pair(float v, int stamp)
+{
+    return ((unsigned long long)(unsigned)stamp << 32) | (unsigned long long)__float_as_uint(v);
+}
+__device__ __forceinline__ void store_pair(unsigned long long *p, unsigned long long v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float load_shared(const float *p)
+__device__ __forceinline__ unsigned long long load_pair(const unsigned long long *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -305,7 +313,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 hsq = fmaf(w4[c4], w4[c4], hsq);
             }
             hq[wave][lane] = hsq;
-            __syncthreads();
+            phase_fence();      // the copies are per wave: the lanes of this wave only have to see each other's writes
             float wv[KD - D];                                    // w_k - w_0 for k >= 1
 #pragma unroll
             for (int e = 0; e < KD - D; ++e) wv[e] = wdc[wave][e];
@@ -336,6 +344,30 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             const float Abound = wave_max_nonneg(dabs) * sum_xmax;
             const float thr = 3.0f * 5.9604645e-8f *
                               ((float)(D + 33) * Abound + (float)(D + 34) * (hdmax + 1.0f) + (float)(2 * D + 2) * hmax);
+
+            // ---- exchange, early part: fetch what the end of this step will need, so that the latency of these
+            // accesses (they bypass the caches) runs behind the mini-batch ----
+            const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && te == 0);
+            const bool send_point = (p.E > 0 && p.W > 1 && te + 1 == p.E);
+            const int rpar = det ? (int)((round - 1) & 1) : 0;
+            const unsigned long long *mslot =
+                reinterpret_cast<const unsigned long long *>(p.slot) + (((size_t)rpar * p.W + i) * NT + (has_task ? lane : 0)) * 4;
+            unsigned long long mp[4] = {0ull, 0ull, 0ull, 0ull};
+            if (merge_point) {
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4) mp[c4] = load_pair(mslot + c4);
+            }
+            int peer = 0, ackv = 0;
+            if (send_point && wave == 0) {
+                if (det) {
+                    // (the shifts of the rounds of this launch come from a table: no 64-bit division in here)
+                    peer = i + p.shift_tab[round - p.shift_r0];
+                    if (peer >= p.W) peer -= p.W;
+                    if (sync && round >= 2) ackv = __hip_atomic_load(p.consumed + peer, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    peer = peer_free(p.seed, round, i, p.W);
+                }
+            }
 
             const long long s_next = (s_epoch + 1 == p.S) ? 0 : s_epoch + 1;
             const float *xb = xs + (size_t)s_epoch * b * D;                       // this mini-batch
@@ -480,7 +512,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     }
                 }
             }
-            __syncthreads();
+            phase_fence();      // a wave sums its own rows
 
             // ---- sum the rows of every centroid in a fixed order, clear them ----
             // lane = (part, task): task = one float4 column (centroid, float4 number); part = its share of the rows
@@ -518,24 +550,35 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             parity ^= 1;
 
             // ---- merge point? (a buffer is looked at once, at the first step of a round) ----
-            const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && te == 0);
-            const int rpar = det ? (int)((round - 1) & 1) : 0;
             bool has_ext = false;
             if (merge_point) {
-                const int *stp = p.stamp + (size_t)rpar * p.W + i;
-                if (sync && det) {
-                    // the sender of the message of round-1 under the cyclic-shift schedule
-                    const uint64_t shift = 1 + round_hash(p.seed, round - 1) % (uint64_t)(p.W - 1);
-                    const int sender = (int)(((uint64_t)i + (uint64_t)p.W - shift) % (uint64_t)p.W);
-                    if (!wait_failed && !message_dropped(p.seed, round - 1, sender, p.drop_thr)) {
-                        if (!wait_flag(stp, (int)(round - 1), false)) wait_failed = 1;
+                // complete = every pair of every task lane carries the stamp of round-1 (free-running: any stamp)
+                auto complete = [&]() -> bool {
+                    bool ok = true;
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        const int st = (int)(mp[c4] >> 32);
+                        ok = ok && (det ? st == (int)(round - 1) : st >= 0);
+                    }
+                    return __ballot(has_task && !ok) == 0ull;
+                };
+                has_ext = complete();
+                if (!has_ext && sync && det && !wait_failed) {
+                    // not there yet: wait for the sender of round-1 under the cyclic-shift schedule, unless its
+                    // message is one of those the loss hook drops
+                    int sender = i - p.shift_tab[round - 1 - p.shift_r0];
+                    if (sender < 0) sender += p.W;
+                    if (!(p.drop_thr != 0 && message_dropped(p.seed, round - 1, sender, p.drop_thr))) {
+                        for (int spin = 0; spin < (1 << 18) && !has_ext; ++spin) {
+                            __builtin_amdgcn_s_sleep(4);
+#pragma unroll
+                            for (int c4 = 0; c4 < 4; ++c4) mp[c4] = load_pair(mslot + c4);
+                            has_ext = complete();
+                        }
+                        if (!has_ext) wait_failed = 1;
                     }
                 }
-                const int st = __hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                has_ext = det ? (st == (int)(round - 1)) : (st >= 0);
             }
-            const float *ext = p.slot + ((size_t)rpar * p.W + i) * KD;
             float G[4], we[4];
             double lhs = 0.0, rhs = 0.0, nrm = 0.0;
 #pragma unroll
@@ -543,7 +586,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 G[c4] = tv[c4] ? (cnt * w4[c4] - S4[c4]) * inv_b : 0.0f;      // descent gradient of Eq. 9
                 we[c4] = 0.0f;
                 if (has_ext && tv[c4]) {
-                    we[c4] = load_shared(ext + te_[c4]);
+                    we[c4] = __uint_as_float((unsigned)(mp[c4] & 0xFFFFFFFFull));
                     const double wed = (double)we[c4];
                     const double a = ((double)w4[c4] - (double)p.eps * (double)G[c4]) - wed;
                     const double c2 = (double)w4[c4] - wed;
@@ -571,34 +614,34 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 w4[c4] = w4[c4] - p.eps * step;
             }
             if (merge_point) {
-                // every wave has read the buffer: empty it and tell senders of later rounds so
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                // every wave has read the buffer (the values were used above): tell senders of later rounds so.
+                // Deterministic mode: the stamps in the buffer never match again, which empties it.  Free-running
+                // mode: a message is used once, so it is marked empty.
                 if constexpr (NW > 1) __syncthreads();
-                if (threadIdx.x == 0) {
-                    __hip_atomic_store(p.stamp + (size_t)rpar * p.W + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (threadIdx.x == 0)
                     __hip_atomic_store(p.consumed + i, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!det && has_ext && wave == 0 && has_task) {
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4)
+                        store_pair(const_cast<unsigned long long *>(mslot) + c4, ~0ull);
                 }
             }
 
             // ---- send (Alg. 5 line 9): the first wave writes ----
-            if (p.E > 0 && p.W > 1 && te + 1 == p.E && wave == 0) {
-                if (!message_dropped(p.seed, round, i, p.drop_thr)) {
-                    const int peer = det ? peer_deterministic(p.seed, round, i, p.W) : peer_free(p.seed, round, i, p.W);
+            if (send_point && wave == 0) {
+                if (!(p.drop_thr != 0 && message_dropped(p.seed, round, i, p.drop_thr))) {
                     const int spar = det ? (int)(round & 1) : 0;
-                    if (sync && det && round >= 2 && !wait_failed) {
+                    if (sync && det && round >= 2 && !wait_failed && ackv < (int)(round - 1)) {
                         // the buffer still holds the message of round-2 until the recipient has passed
-                        // the merge point of round-1
+                        // the merge point of round-1 (it had not when this step began: look again)
                         if (!wait_flag(p.consumed + peer, (int)(round - 1), true)) wait_failed = 1;
                     }
-                    float *dst = p.slot + ((size_t)spar * p.W + peer) * KD;
+                    unsigned long long *dst =
+                        reinterpret_cast<unsigned long long *>(p.slot) + (((size_t)spar * p.W + peer) * NT + (has_task ? lane : 0)) * 4;
+                    if (has_task) {
 #pragma unroll
-                    for (int c4 = 0; c4 < 4; ++c4) {
-                        if (tv[c4]) store_shared(dst + te_[c4], w4[c4]);
+                        for (int c4 = 0; c4 < 4; ++c4) store_pair(dst + c4, pack_pair(w4[c4], (int)round));
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                    if (lane == 0)
-                        __hip_atomic_store(p.stamp + (size_t)spar * p.W + peer, (int)round, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
                 }
                 if (lane == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
             }
@@ -677,6 +720,12 @@ hipError_t launch_shape(const StepParams &p, long long t0, long long t1, hipStre
 }
 
 }  // namespace
+
+size_t small_kernel_message_bytes(int k, int d)
+{
+    if (!(k == 10 && d == 10)) return 0;
+    return (size_t)k * ((d + 1 + 3) / 4) * 4 * sizeof(unsigned long long);      // NT lanes x 4 (value, stamp) pairs
+}
 
 bool small_kernel_supports(int k, int d, int b)
 {
