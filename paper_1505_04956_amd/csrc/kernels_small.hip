@@ -345,6 +345,15 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             const float thr = 3.0f * 5.9604645e-8f *
                               ((float)(D + 33) * Abound + (float)(D + 34) * (hdmax + 1.0f) + (float)(2 * D + 2) * hmax);
 
+            // The instruction arbiter of a SIMD prefers the older of its two waves, which makes the workgroups that
+            // were dispatched later run ~40 % slower - and with rounds coupled through the exchange everybody ends
+            // up waiting for them.  Alternating the wave priority step by step, in opposite phase for the two
+            // halves of the grid (dispatch order), evens the shares out.
+            if (((int)(t & 1) ^ (blockIdx.x * 2 >= gridDim.x ? 1 : 0)) != 0)
+                __builtin_amdgcn_s_setprio(1);
+            else
+                __builtin_amdgcn_s_setprio(0);
+
             // ---- exchange, early part: fetch what the end of this step will need, so that the latency of these
             // accesses (they bypass the caches) runs behind the mini-batch ----
             const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && te == 0);
@@ -402,6 +411,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                             for (int j = 0; j < D; ++j) sc = fmaf(xc[j], wv[(c - 1) * D + j], sc);
                             tk[c] = __uint_as_float((__float_as_uint(sc) & 0xFFFFFFF0u) | (unsigned)(15 - c));
                         }
+                        // keep the order chains / row phase / chains ...: the LDS read issued at the end of a phase
+                        // then returns under the next chains instead of being waited for at once
+                        __builtin_amdgcn_sched_barrier(0);
                         float add[4];
 #pragma unroll
                         for (int c4 = 0; c4 < 4; ++c4) {
@@ -419,6 +431,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                             if constexpr (RS == 2) phase_fence();
                             pr = prow[qoff[ph + 1]];
                         }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     // buffer `up` is free now: refill it with the group PF-1 turns ahead
                     {
