@@ -36,9 +36,7 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int MF_THREADS = 512;
-constexpr int MF_WAVES = 8;
-constexpr int TM = 256;          // samples per tile (32 per wave)
+// Waves per workgroup is a template parameter NWV (8 or 4): a tile has 32 samples per wave.
 constexpr int WB = 64;           // centroid rows per block (2 matrix tiles of 32)
 constexpr int RB = 4;            // rows per wave and iteration in the row passes (loads in flight)
 constexpr int GS = 16;           // sample rows in flight per wave in the gather
@@ -75,18 +73,18 @@ __device__ __forceinline__ float wave_sum_f(float v)
 struct MfmaGeom {
     int kpad;      // k rounded up to a multiple of WB
     int nblocks;   // kpad / WB
-    int kq;        // centroids per owner wave, rounded up
-    int ns;        // 8 * kq sort slots: slot(c) = (c % 8) * kq + c / 8
+    int kq;        // centroids per owner wave (c % nwv), rounded up
+    int ns;        // nwv * kq sort slots: slot(c) = (c % nwv) * kq + c / nwv
     size_t off_h, off_cstart, off_cursor, off_idx, off_perm, bytes;
 };
-__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident)
+__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv)
 {
     MfmaGeom g;
     const int DP = nch * 8 + 4;
     g.kpad = (k + WB - 1) / WB * WB;
     g.nblocks = g.kpad / WB;
-    g.kq = (k + MF_WAVES - 1) / MF_WAVES;
-    g.ns = MF_WAVES * g.kq;
+    g.kq = (k + nwv - 1) / nwv;
+    g.ns = nwv * g.kq;
     size_t o = (size_t)(resident ? g.kpad : 2 * WB) * DP * sizeof(float);
     g.off_h = o;            o += (size_t)g.kpad * sizeof(float);
     g.off_cstart = o;       o += ((size_t)g.ns + 4) / 4 * 4 * sizeof(int);
@@ -129,8 +127,11 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
 // NCH = number of 8-dimension chunks of the contraction (d <= 8 * NCH).
 // RES: the whole padded state fits in LDS.  It is then staged once per step and phase 1 needs no barriers.
 // Otherwise blocks of WB rows are streamed through a two-deep stage with one barrier per block.
-template <int NCH, bool RES>
-__global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
+// NWV: waves per workgroup.  8 by default (two per SIMD).  4 when the state is resident, two workgroups fit a CU
+// and there are more workers than CUs: two workers then share a CU and one's memory-bound phase 2 runs under the
+// other's matrix work.
+template <int NCH, bool RES, int NWV>
+__global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
                                                                  const float *xnorm2max_ptr)
 {
     constexpr int DP8 = NCH * 8;                 // padded row length
@@ -138,6 +139,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
     constexpr int NJ = DP8 > 64 ? 2 : 1;         // dimensions per lane in the row passes (lane l owns l, l + 64)
     constexpr int ROW4 = NCH * 2;                // float4 per padded row
     constexpr int NVEC = WB * ROW4;              // float4 per staged block
+    constexpr int MF_THREADS = 64 * NWV, MF_WAVES = NWV, TM = 32 * NWV;
     constexpr int NST = (NVEC + MF_THREADS - 1) / MF_THREADS;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = lane >> 5, l32 = lane & 31;
     const int k = p.k, d = p.d, b = p.b;
-    const MfmaGeom g = mfma_geom(k, b, NCH, RES);
+    const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV);
     const size_t kd = (size_t)k * d;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
 
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
         __syncthreads();                                   // also: idx complete
         for (int n = tid; n < b; n += MF_THREADS) {
             const int c = idx[n];
-            atomicAdd(&cursor[(c & 7) * g.kq + (c >> 3)], 1);
+            atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);
         }
         __syncthreads();
         if (wave == 0) {
@@ -471,7 +473,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
         for (int n0 = 0; n0 < b; n0 += 64) {
             const int n = n0 + lane;
             const int c = n < b ? (int)idx[n] : -1;
-            const bool own = n < b && (c & 7) == wave;
+            const bool own = n < b && (c % NWV) == wave;
             unsigned long long rem = __ballot(own);
             int rank = 0;
             bool last = false;
@@ -486,7 +488,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
                 rem &= ~same;
             }
             if (own) {
-                const int s = (c & 7) * g.kq + (c >> 3);
+                const int s = (c % NWV) * g.kq + c / NWV;
                 const int base = cursor[s];
                 perm[base + rank] = (unsigned short)n;
                 if (last) cursor[s] = base + rank + 1;
@@ -558,7 +560,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
 #pragma unroll
                 for (int q = 0; q < RB; ++q) {
                     const int c = c0 + q < k ? c0 + q : k - 1;
-                    const int s = (c & 7) * g.kq + (c >> 3);
+                    const int s = (c % NWV) * g.kq + c / NWV;
                     cn[q] = cstart[s + 1] - cstart[s];
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
@@ -609,7 +611,7 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
 #pragma unroll
                 for (int q = 0; q < RB; ++q) {
                     const int c = c0 + q < k ? c0 + q : k - 1;
-                    const int s = (c & 7) * g.kq + (c >> 3);
+                    const int s = (c % NWV) * g.kq + c / NWV;
                     cn[q] = cstart[s + 1] - cstart[s];
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
@@ -675,20 +677,24 @@ __global__ __launch_bounds__(MF_THREADS) void mfma_steps_kernel(StepParams p, lo
 
 constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 
-template <int NCH, bool RES>
+template <int NCH, bool RES, int NWV>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
 {
-    const size_t lds = mfma_geom(p.k, p.b, NCH, RES).bytes;
-    hipError_t e = hipFuncSetAttribute((const void *)mfma_steps_kernel<NCH, RES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV).bytes;
+    hipError_t e = hipFuncSetAttribute((const void *)mfma_steps_kernel<NCH, RES, NWV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES>), dim3(p.W), dim3(MF_THREADS), lds, s, p, t0, t1, xnorm2max);
+    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max);
     return hipGetLastError();
 }
 template <int NCH>
 hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
 {
-    if (mfma_geom(p.k, p.b, NCH, true).bytes <= MF_LDS_BUDGET) return launch_variant<NCH, true>(p, t0, t1, xnorm2max, s);
-    return launch_variant<NCH, false>(p, t0, t1, xnorm2max, s);
+    // tune bit 0 forces 8 waves, bit 1 forces 4 waves (resident variant only)
+    const size_t half_cu = 78 * 1024;      // two workgroups per CU must fit 160 KB, a little is reserved
+    if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2)))
+        return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s);
+    if (mfma_geom(p.k, p.b, NCH, true, 8).bytes <= MF_LDS_BUDGET) return launch_variant<NCH, true, 8>(p, t0, t1, xnorm2max, s);
+    return launch_variant<NCH, false, 8>(p, t0, t1, xnorm2max, s);
 }
 
 }  // namespace
@@ -696,7 +702,7 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
 bool mfma_kernel_supports(int k, int d, int b, const void *x)
 {
     if (d % 4 != 0 || d > 128 || k < 2 || k > 32768 || b > 65535 || (((uintptr_t)x) & 15u) != 0) return false;
-    return mfma_geom(k, b, mfma_chunks(d), false).bytes <= MF_LDS_BUDGET;
+    return mfma_geom(k, b, mfma_chunks(d), false, 8).bytes <= MF_LDS_BUDGET;
 }
 
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s)

@@ -202,6 +202,18 @@ def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights
     assert g.stats().kernel == 3
 
 
+@pytest.mark.parametrize("k,d,W,b,E,steps,N", [
+    (100, 100, 4, 2000, 2, 7, 4 * 2000 * 3),
+    (33, 36, 5, 300, 3, 8, 5 * 1000 + 3),
+    (70, 8, 3, 100, 2, 9, 3 * 450 + 2),
+])
+def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N):
+    # the variant with four waves per worker (two workers per CU), which large W selects by itself
+    X = make_data(N, d, k, seed=23)
+    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=2)
+    assert g.stats().kernel == 3
+
+
 def test_matrix_core_kernel_options(B, oracle):
     X = make_data(6 * 1200, 20, 40, seed=22)
     run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11, parzen=False, kernel=3)
