@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = streaming workload of the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", type=int, default=0)
+    ap.add_argument("--mode", choices=("deterministic", "free", "silent"), default="deterministic",
+                    help="deterministic: seeded schedule, reproducible (the metric); free: free-running exchange with "
+                         "the paper's races; silent: no exchange at all (E = 0), for the merge-overhead column")
     ap.add_argument("--plain-launch", action="store_true",
                     help="start the single-launch kernel with a plain launch instead of a cooperative one "
                          "(same kernel, same grid); needed under rocprofv3, whose tool library crashes at "
@@ -94,7 +97,8 @@ def main():
         torch.mul(X, 1.0, out=Y)      # an elementwise kernel: reads N*d*4 bytes, writes N*d*4 bytes
         torch.cuda.synchronize()
         del Y
-    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, tune=args.tune,
+    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=(0 if args.mode == "silent" else wl.E), seed=wl.schedule_seed,
+               mode=(B.MODE_FREE_RUNNING if args.mode == "free" else B.MODE_DETERMINISTIC), tune=args.tune,
                cooperative=not args.plain_launch)
     g.load_shards(X)
     for _ in range(args.warmup):
@@ -132,7 +136,7 @@ def main():
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "k": wl.k, "W": wl.W, "b": wl.b, "lr": wl.lr,
-                   "exchange_every": wl.E, "epochs_per_step": 1, "mode": "deterministic",
+                   "exchange_every": (0 if args.mode == "silent" else wl.E), "epochs_per_step": 1, "mode": args.mode,
                    "samples_per_step": samples, "kernel": int(st.kernel), "launches_per_step": int(st.launches)},
         "roofline": roofline,
         "stats": {"messages_sent": int(st.sent), "messages_received": int(st.received),

@@ -135,3 +135,30 @@ def test_hbm_scale_workload(oracle):
     lo, hi = float(X[:1_000_000].min()), float(X[:1_000_000].max())
     assert w_after.min() >= lo - 1.0 and w_after.max() <= hi + 1.0
     assert not np.array_equal(w_before, w_after)
+
+
+def test_free_running_full_size():
+    """Free-running mode (the paper's races, Sec. 4.4) at the streaming workload's full size, against the
+    deterministic and the silent run on the same data: no element-wise parity exists for it, so properties:
+    finite states, every worker sends once per round, Eq. 8 of worker 0 and of the mean state within 2 % of
+    the deterministic run's and not worse than the silent run's by more than 2 %."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[1]
+    X = workloads.generate_device(wl, device="cuda:0")
+    res = {}
+    for name, kw in (("deterministic", dict(E=wl.E)), ("free", dict(E=wl.E, mode=B.MODE_FREE_RUNNING)), ("silent", dict(E=0))):
+        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, seed=wl.schedule_seed, **kw)
+        g.load_shards(X)
+        g.run_epochs(2)
+        st = g.stats()
+        w = g.get_state()
+        assert np.all(np.isfinite(w)) and st.kernel == B.KERNEL_SMALL and st.launches == 1
+        res[name] = (g.quant_error(0), g.quant_error(-1), st.sent, st.received, st.accepted, st.last_run_ms)
+        print("[%s] E(w_0) %.6g  E(mean w) %.6g  sent/received/good %d/%d/%d  %.3f ms" % ((name,) + res[name]))
+        g.close()
+    rounds = (2 * wl.S) // wl.E
+    assert res["deterministic"][2] == res["free"][2] == wl.W * rounds and res["silent"][2] == 0
+    assert 0 < res["free"][3] <= res["free"][2] and 0 < res["free"][4] <= res["free"][3]
+    for q in (0, 1):
+        assert abs(res["free"][q] - res["deterministic"][q]) <= 0.02 * res["deterministic"][q]
+        assert res["free"][q] <= 1.02 * res["silent"][q]
