@@ -75,7 +75,7 @@ struct MfmaGeom {
     int nblocks;   // kpad / WB
     int kq;        // centroids per owner wave (c % nwv), rounded up
     int ns;        // nwv * kq sort slots: slot(c) = (c % nwv) * kq + c / nwv
-    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, bytes;
+    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, bytes;
 };
 __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv)
 {
@@ -91,7 +91,9 @@ __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool reside
     g.off_cursor = o;       o += ((size_t)g.ns + 3) / 4 * 4 * sizeof(int);
     g.off_idx = o;          o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
-    g.bytes = o;
+    g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
+    if (resident) o += (size_t)nwv * 32 * ((b + 32 * nwv - 1) / (32 * nwv)) * sizeof(unsigned short);
+    g.bytes = (o + 15) / 16 * 16;
     return g;
 }
 inline int mfma_chunks(int d) { return d <= 32 ? 4 : d <= 64 ? 8 : d <= 104 ? 13 : 16; }
@@ -161,6 +163,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns counts, then cursors
     unsigned short *idx = reinterpret_cast<unsigned short *>(smem_raw + g.off_idx);   // b assignments
     unsigned short *perm = reinterpret_cast<unsigned short *>(smem_raw + g.off_perm); // b samples sorted by centroid
+    unsigned short *flist = reinterpret_cast<unsigned short *>(smem_raw + g.off_flist);
 
     float *wst = p.w + (size_t)i * kd;                  // state of this worker
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
@@ -344,7 +347,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const bool close3 = close2 && !(top.v1 - top.v3 > thr);
             // exact decision between two candidates, four flagged samples at a time:
             // |x - w_a|^2 - |x - w_b|^2 = sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j), in fp64
-            unsigned long long pm = __ballot(close2 && !close3);
+            unsigned long long pm = RES ? 0ull : __ballot(close2 && !close3);
             while (pm) {
                 int L[4], ca[4], cb2[4];
 #pragma unroll
@@ -406,7 +409,15 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             if (mine) {
                 idx[n] = (unsigned short)arg;
-                if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
+                if constexpr (RES) {
+                    // two close candidates: decided after the last tile, all such samples of the wave at once;
+                    // until then perm[] (unused during this phase) keeps the second candidate
+                    const bool pairf = close2 && !close3;
+                    perm[n] = pairf ? (unsigned short)top.i2 : (unsigned short)0xFFFF;
+                    if (p.dump && !pairf) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
+                } else {
+                    if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
+                }
             }
         };
         if constexpr (RES) {
@@ -424,6 +435,50 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) xa[ch] = frag(rowoff_of(0), ch);
             for (int tile0 = 0; tile0 < b; tile0 += TM) do_tile(xa, tile0);
+        }
+        if constexpr (RES) {
+            // ---- deferred exact decisions between two candidates ----
+            // The state rows are still in LDS.  A lane pair (l32, half 0/1) takes one flagged sample: its half of the
+            // dimensions of sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j) in fp64, x fetched again (it is cache-hot), then
+            // the halves are added.  32 samples per pass, so the memory latency is paid once per pass, not per sample.
+            unsigned short *mylist = flist + wave * 32 * ((b + TM - 1) / TM);
+            int nfl = 0;
+            for (int tile0 = 0; tile0 < b; tile0 += TM) {
+                const int n = tile0 + wave * 32 + l32;
+                const bool fl = half == 0 && n < b && perm[n] != (unsigned short)0xFFFF;
+                const unsigned long long m = __ballot(fl);
+                if (fl) mylist[nfl + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)n;
+                nfl += __popcll(m);
+            }
+            for (int e0 = 0; e0 < nfl; e0 += 32) {
+                const bool act = e0 + l32 < nfl;
+                const int n = act ? (int)mylist[e0 + l32] : 0;
+                const int ca = idx[n], cb2 = act ? (int)perm[n] : ca;
+                const float *ra = Ws + ca * DP + 4 * half, *rb = Ws + cb2 * DP + 4 * half;
+                const unsigned rowoff = (unsigned)n * (unsigned)d;
+                float4 xv[NCH];
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) xv[ch] = frag(rowoff, ch);
+                double dd = 0.0;
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const float4 wa = *reinterpret_cast<const float4 *>(ra + ch * 8);
+                    const float4 wb = *reinterpret_cast<const float4 *>(rb + ch * 8);
+                    // columns past d: the state rows are zero there, so the term vanishes whatever x holds
+                    dd += ((double)wa.x - (double)wb.x) * (((double)wa.x + (double)wb.x) - 2.0 * (double)xv[ch].x);
+                    dd += ((double)wa.y - (double)wb.y) * (((double)wa.y + (double)wb.y) - 2.0 * (double)xv[ch].y);
+                    dd += ((double)wa.z - (double)wb.z) * (((double)wa.z + (double)wb.z) - 2.0 * (double)xv[ch].z);
+                    dd += ((double)wa.w - (double)wb.w) * (((double)wa.w + (double)wb.w) - 2.0 * (double)xv[ch].w);
+                }
+                dd += __shfl_xor(dd, 32, 64);
+                if (act && half == 0) {
+                    const int lo = ca < cb2 ? ca : cb2;
+                    const int res = dd < 0.0 ? ca : (dd > 0.0 ? cb2 : lo);
+                    idx[n] = (unsigned short)res;
+                    if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = res;
+                }
+            }
+            rechecks += (lane == 0) ? nfl : 0;
         }
 
         // ================= phase 2: gradient, merge, update =================
@@ -470,23 +525,21 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         __syncthreads();
         // placement: every wave walks all samples in order and places those of its own centroids
+        int nbits = 1;
+        while ((1 << nbits) < k) ++nbits;
         for (int n0 = 0; n0 < b; n0 += 64) {
             const int n = n0 + lane;
             const int c = n < b ? (int)idx[n] : -1;
             const bool own = n < b && (c % NWV) == wave;
-            unsigned long long rem = __ballot(own);
-            int rank = 0;
-            bool last = false;
-            while (rem) {
-                const int L = __builtin_ctzll(rem);
-                const int cL = __builtin_amdgcn_readlane(c, L);
-                const unsigned long long same = __ballot(own && c == cL);
-                if (own && c == cL) {
-                    rank = __popcll(same & ((1ull << lane) - 1ull));
-                    last = (same >> lane) == 1ull;
-                }
-                rem &= ~same;
+            // lanes of this chunk with the same centroid as this lane: intersect, bit by bit of the index, the
+            // ballot of the lanes that agree with this lane in that bit (no loop over distinct values)
+            unsigned long long same = __ballot(own);
+            for (int bit = 0; bit < nbits; ++bit) {
+                const unsigned long long set = __ballot(((c >> bit) & 1) != 0);
+                same &= ((c >> bit) & 1) ? set : ~set;
             }
+            const int rank = __popcll(same & ((1ull << lane) - 1ull));
+            const bool last = (same >> lane) == 1ull;
             if (own) {
                 const int s = (c % NWV) * g.kq + c / NWV;
                 const int base = cursor[s];
