@@ -71,7 +71,15 @@ __global__ void absmax_partial_kernel(const float *__restrict__ x, long long n, 
     __syncthreads();
     if (g < stride) {
         float m = 0.0f;
-        for (long long e = g; e < total; e += stride) m = fmaxf(m, fabsf(x[e]));
+        long long e = g;
+        for (; e + 7 * stride < total; e += 8 * stride) {      // eight independent loads in flight per thread
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = x[e + q * stride];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) m = fmaxf(m, fabsf(v[q]));
+        }
+        for (; e < total; e += stride) m = fmaxf(m, fabsf(x[e]));
         // max is order independent; |x| >= 0, so the integer order of the bit patterns is the
         // floating-point order and an integer atomic is exact
         atomicMax((unsigned int *)&sm[g % d], __float_as_uint(m));
@@ -342,7 +350,7 @@ hipError_t launch_absmax(const float *x, long long rows, int d, float *out, hipS
     hipLaunchKernelGGL(absmax_final_kernel, dim3(1), dim3(256), 0, s, partial, nblocks, d, out);
     e = hipGetLastError();
     hipError_t e2 = hipStreamSynchronize(s);
-    hipFree(partial);
+    (void)hipFree(partial);
     return e != hipSuccess ? e : e2;
 }
 

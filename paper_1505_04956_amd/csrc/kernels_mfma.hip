@@ -151,7 +151,6 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int half = lane >> 5, l32 = lane & 31;
     const int k = p.k, d = p.d, b = p.b;
     const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV);
     const size_t kd = (size_t)k * d;
