@@ -54,7 +54,11 @@ enum {
     ASGD_OPT_DROP_RATE = 6,      /* test hook: probability in [0,1] that a message is lost on
                                     the way (Sec. 4.4: a lost message is harmless).  Default 0. */
     ASGD_OPT_KERNEL = 7,         /* ASGD_KERNEL_*: which implementation runs the steps.
-                                    Default auto.  All give the same results to rounding. */
+                                    Default auto.  All give the same results to rounding.  The kernels keep
+                                    a message in flight in different formats, and one is in flight exactly
+                                    when the step counter is a positive multiple of E: a run that would
+                                    start there with another kernel than the previous run fails with
+                                    ASGD_ESTATE (run up to a step that is not a multiple of E first). */
     ASGD_OPT_TUNE = 8,           /* launch-shape variant of the chosen kernel (0 = default); for
                                     performance experiments, never changes what is computed */
     ASGD_OPT_COOPERATIVE = 9     /* 1 (default): a run that needs all its workgroups resident at the

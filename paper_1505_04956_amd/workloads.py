@@ -117,3 +117,15 @@ def generate_device(wl: Workload, device="cuda:0", chunk_rows: int = 1 << 24):
         out += c_dev[comp]
         del comp
     return X
+
+
+def centre_error(w: np.ndarray, wl: Workload) -> float:
+    """Error against the generator's centres as the paper uses it for its synthetic data (Sec. 5.3, last
+    paragraph: the distance between the centres of the generation step and the centres returned; a relative
+    measure only).  The paper gives no formula; reading: for every generated centre the Euclidean distance
+    to the nearest returned centroid, averaged.  Evaluation helper on the host, not part of the hot path."""
+    c, _ = mixture_parameters(wl)
+    c = c.astype(np.float64)
+    w = np.asarray(w, dtype=np.float64).reshape(-1, wl.d)
+    d2 = ((c[:, None, :] - w[None, :, :]) ** 2).sum(-1)
+    return float(np.sqrt(d2.min(1)).mean())

@@ -422,3 +422,22 @@ def test_stored_values_of_tiny_workload(oracle):
     assert abs(now["quant_error_mean_state"] - stored["quant_error_mean_state"]) <= 1e-12 * stored["quant_error_mean_state"]
     qe = stored["quant_error_worker0_by_epoch"]
     assert all(b < a for a, b in zip(qe, qe[1:]))          # Eq. 8 falls epoch by epoch on this workload
+
+
+def test_centre_error_convergence_of_tiny_workload(oracle):
+    """Shape of the paper's convergence figures on the synthetic generator (Sec. 5.4): the distance between
+    the generator's centres and the returned ones falls with the number of samples touched; the helper is
+    zero for the centres themselves and invariant to the order of the centroids."""
+    wl = workloads.CONFIGS[0]
+    c, _ = workloads.mixture_parameters(wl)
+    assert workloads.centre_error(c, wl) == 0.0
+    assert workloads.centre_error(c[::-1], wl) == 0.0
+    X = workloads.generate_host(wl)
+    o = oracle.OracleASGD(X, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+    errs = [workloads.centre_error(o.w[0], wl)]           # the state of the first worker is what Alg. 5 returns
+    for _ in range(wl.epochs):
+        o.run_epochs(1)
+        errs.append(workloads.centre_error(o.w[0], wl))
+    print("centre error of worker 0 by epoch:", ["%.3f" % e for e in errs])
+    assert errs[-1] < 0.8 * errs[0]
+    assert all(b <= a * 1.02 for a, b in zip(errs, errs[1:]))

@@ -319,6 +319,26 @@ def test_error_paths(B):
         g2.run_steps(1)                                  # 1/count step size needs silent mode
 
 
+def test_kernel_switch_between_runs(B, oracle):
+    # Kernels keep the message in flight in their own format; one is in flight exactly at a merge point.
+    X = make_data(24_000, 10, 10, seed=2)
+    g = B.ASGD(10, 10, 6, 200, 0.1, E=2, kernel=2)
+    g.load_shards(to_dev(X))
+    g.run_steps(2)                                    # t = 2: the messages of round 0 wait to be merged
+    g.set_option(B.OPT_KERNEL, 1)
+    with pytest.raises(B.AsgdError) as e:
+        g.run_steps(1)
+    assert e.value.code == B.ESTATE
+    g.set_option(B.OPT_KERNEL, 2)
+    g.run_steps(1)                                    # t = 3: nothing in flight
+    g.set_option(B.OPT_KERNEL, 1)
+    g.run_steps(4)                                    # the generic kernel takes over, sends and merges in its format
+    o = oracle.OracleASGD(X, k=10, W=6, b=200, lr=0.1, E=2)
+    o.run_steps(7)
+    assert rel_fro(g.get_state(), o.w).max() <= TOL
+    assert np.array_equal(g.worker_counters(), o.counters)
+
+
 def test_schedule_matches_oracle(B, oracle):
     for W in (2, 5, 1024):
         for r in range(5):
