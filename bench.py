@@ -36,27 +36,38 @@ def traffic_from_profile(kernel_name, workload_name):
 
 
 def cpu_baseline(wl, X):
-    """The oracle as it stands, timed on the host cores over the first steps of the same workload: as many
-    steps (all W workers each) as about 20 s of CPU work allow, at most one epoch."""
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload: about 15 s of
+    its work.  The sample is the first steps of the run, all W workers; if an epoch is shorter than that, the
+    run simply goes on into further epochs; if the rows those steps touch would not fit the host (100 GB
+    workload), the prefix that fits 8 GB is run several times."""
     from oracle import asgd_oracle
     asgd_oracle.build()
     cores = min(asgd_oracle.threads(), 16)
     asgd_oracle.set_threads(cores)
-    est_rate = cores * 4.0e8 / (wl.k * wl.d)              # rough samples/s of the fp64 oracle, to size the sample
-    steps = int(max(1, min(wl.S, 20.0 * est_rate / (wl.W * wl.b))))
-    if steps > wl.E >= 1:
-        steps = min(wl.S, max(steps, 2 * wl.E + 1))       # at least two communication rounds
-    rows = steps * wl.b
-    # the rows those steps touch, shard by shard (for the 100 GB workload the whole array would not fit the host)
+    est_rate = cores * 2.0e9 / (wl.k * wl.d)              # rough samples/s of the fp64 oracle, to size the sample
+    want = 15.0 * est_rate                                # samples
+    steps = int(max(1, want / (wl.W * wl.b)))
+    if wl.E >= 1:
+        steps = max(steps, 2 * wl.E + 1)                  # at least two communication rounds
+    rows = min(steps, wl.S) * wl.b                        # rows per worker those steps touch
+    max_rows = int(8e9 / (wl.W * wl.d * 4))
+    reps = 1
+    if rows > max_rows:
+        steps = max(1, max_rows // wl.b)
+        rows = steps * wl.b
+        reps = int(max(1, round(want / (steps * wl.W * wl.b))))
+    # shard by shard (the oracle sees W shards of `rows` rows; a run longer than that wraps like an epoch does)
     Xc = X[:wl.W * wl.H].view(wl.W, wl.H, wl.d)[:, :rows, :].contiguous().cpu().numpy().reshape(wl.W * rows, wl.d)
-    o = asgd_oracle.OracleASGD(Xc, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
-    t0 = time.perf_counter()
-    o.run_steps(steps)
-    dt = time.perf_counter() - t0
-    n = steps * wl.W * wl.b
+    dt = 0.0
+    for _ in range(reps):
+        o = asgd_oracle.OracleASGD(Xc, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+        t0 = time.perf_counter()
+        o.run_steps(steps)
+        dt += time.perf_counter() - t0
+    n = reps * steps * wl.W * wl.b
     return {"value": n / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
-            "sample": "the first %d of the %d steps of an epoch of the same workload, all %d workers (%d samples, %.1f s), "
-                      "fp64, %d OpenMP threads over workers" % (steps, wl.S, wl.W, n, dt, cores)}
+            "sample": "%d x the first %d steps (an epoch has %d) of the same workload, all %d workers: %d samples in "
+                      "%.1f s, fp64, %d OpenMP threads over workers" % (reps, steps, wl.S, wl.W, n, dt, cores)}
 
 
 def main():
