@@ -319,6 +319,29 @@ def test_error_paths(B):
         g2.run_steps(1)                                  # 1/count step size needs silent mode
 
 
+def test_two_contexts_and_a_side_stream(B, oracle):
+    # contexts are independent (no global state); the library launches on the stream handed to load_shards
+    import torch
+    X1 = make_data(24_000, 10, 10, seed=41)
+    X2 = make_data(4 * 600 * 4, 20, 40, seed=42)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        a = B.ASGD(10, 10, 6, 200, 0.1, E=2, seed=3)
+        a.load_shards(to_dev(X1))
+    c = B.ASGD(40, 20, 4, 600, 0.05, E=3, seed=4)
+    c.load_shards(to_dev(X2))
+    for _ in range(3):                                  # interleave the two
+        a.run_steps(5)
+        c.run_steps(3)
+    assert a.stats().kernel == B.KERNEL_SMALL and c.stats().kernel == B.KERNEL_MFMA
+    oa = oracle.OracleASGD(X1, k=10, W=6, b=200, lr=0.1, E=2, seed=3); oa.run_steps(15)
+    oc = oracle.OracleASGD(X2, k=40, W=4, b=600, lr=0.05, E=3, seed=4); oc.run_steps(9)
+    assert rel_fro(a.get_state(), oa.w).max() <= TOL and rel_fro(c.get_state(), oc.w).max() <= TOL
+    assert np.array_equal(a.worker_counters(), oa.counters) and np.array_equal(c.worker_counters(), oc.counters)
+    a.run_steps(0)                                      # nothing to do is not an error
+    assert a.stats().steps == 15
+
+
 def test_kernel_switch_between_runs(B, oracle):
     # Kernels keep the message in flight in their own format; one is in flight exactly at a merge point.
     X = make_data(24_000, 10, 10, seed=2)
