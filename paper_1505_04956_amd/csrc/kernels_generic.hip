@@ -372,10 +372,21 @@ hipError_t launch_quant_error(const float *x, long long N, int d, int k, const f
                               hipStream_t s)
 {
     const size_t kd = (size_t)k * d;
-    const int w_in_lds = kd * sizeof(float) <= 60 * 1024;
-    hipLaunchKernelGGL(quant_error_kernel, dim3(QE_BLOCKS), dim3(QE_THREADS), w_in_lds ? kd * sizeof(float) : 0, s, x, N,
-                       d, k, w, w_in_lds, partials);
-    hipLaunchKernelGGL(quant_error_final_kernel, dim3(1), dim3(64), 0, s, partials, QE_BLOCKS, out);
+    int nparts = QE_BLOCKS;
+    hipError_t e = hipSuccess;
+    if (small_kernel_supports(k, d, 1)) {
+        e = launch_quant_error_small(x, N, w, partials, nparts, s);            // streaming shape: HBM bound
+    } else if (mfma_quant_error_supports(k, d, x)) {
+        nparts = 256;                                                           // one workgroup per CU
+        e = launch_quant_error_mfma(x, N, d, k, w, partials, nparts, s);       // contraction shape: matrix cores
+    } else {
+        const int w_in_lds = kd * sizeof(float) <= 60 * 1024;
+        hipLaunchKernelGGL(quant_error_kernel, dim3(QE_BLOCKS), dim3(QE_THREADS), w_in_lds ? kd * sizeof(float) : 0, s, x,
+                           N, d, k, w, w_in_lds, partials);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(quant_error_final_kernel, dim3(1), dim3(64), 0, s, partials, nparts, out);
     return hipGetLastError();
 }
 

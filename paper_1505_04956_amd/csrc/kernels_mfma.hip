@@ -727,6 +727,150 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         atomicAdd((unsigned long long *)&p.counters[(size_t)i * CNT_STRIDE + CNT_RECHECK], (unsigned long long)rechecks);
 }
 
+// Eq. 8 for the contraction shapes: the same matrix-core scores as phase 1 of the step kernel, for ONE state and
+// all N samples.  min_c |x - w_c|^2 / 2 = |x|^2 / 2 - max_c (x.w_c - |w_c|^2/2): only the running maximum per sample
+// is kept.  A workgroup (8 waves) walks tiles of 256 samples with a fixed stride, every lane pair adds its samples
+// in fp64 in a fixed order, the partials are added in a fixed order: the result does not depend on scheduling.
+template <int NCH>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void quant_error_mfma_kernel(
+    const float *__restrict__ x, long long N, int k, int d, const float *__restrict__ w, double *partials)
+{
+    constexpr int NWV = 8, MF_THREADS = 512, TM = 256;
+    constexpr int DP8 = NCH * 8, DP = DP8 + 4, ROW4 = NCH * 2, NVEC = WB * ROW4;
+    constexpr int NST = (NVEC + MF_THREADS - 1) / MF_THREADS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __shared__ double red[NWV];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int kpad = (k + WB - 1) / WB * WB, nblocks = kpad / WB;
+    float *Ws = reinterpret_cast<float *>(smem_raw);                      // 2 x WB x DP
+    float *hs = Ws + 2 * WB * DP;                                         // kpad
+
+    for (int c0 = wave * RB; c0 < kpad; c0 += NWV * RB) {                 // h_c = -|w_c|^2 / 2
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const int c = c0 + q;
+            float sq = 0.0f;
+            for (int j = lane; j < d; j += 64) {
+                const float v = w[(size_t)(c < k ? c : 0) * d + j];
+                sq = fmaf(v, v, sq);
+            }
+            sq = wave_sum_f(sq);
+            if (lane == 0) hs[c] = c < k ? -0.5f * sq : PAD_SCORE;
+        }
+    }
+    const int col0 = (half && d >= 8) ? 4 : 0;
+    const int collim = half ? (d >= 8 ? (d - 8) / 8 * 8 + 4 : 0) : (d - 4) / 8 * 8;
+    auto fetch_block = [&](float4(&st)[NST], int cb) {
+#pragma unroll
+        for (int q = 0; q < NST; ++q) {
+            const int e = tid + q * MF_THREADS;
+            const int r = (e < NVEC ? e : 0) / ROW4, c4 = (e < NVEC ? e : 0) - r * ROW4;
+            const int c = cb * WB + r, col = 4 * c4;
+            const bool ok = c < k && col < d;
+            float4 v = *reinterpret_cast<const float4 *>(w + (size_t)(ok ? c : 0) * d + (ok ? col : 0));
+            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            st[q] = v;
+        }
+    };
+    auto store_block = [&](const float4(&st)[NST], float *dst) {
+#pragma unroll
+        for (int q = 0; q < NST; ++q) {
+            const int e = tid + q * MF_THREADS;
+            if (e < NVEC) {
+                const int r = e / ROW4, c4 = e - r * ROW4;
+                *reinterpret_cast<float4 *>(&dst[r * DP + 4 * c4]) = st[q];
+            }
+        }
+    };
+
+    double sum = 0.0;
+    for (long long tile0 = (long long)blockIdx.x * TM; tile0 < N; tile0 += (long long)gridDim.x * TM) {
+        const long long n = tile0 + wave * 32 + l32;
+        const bool ok = n < N;
+        const float *row = x + (size_t)(ok ? n : 0) * d;
+        float4 xf[NCH];
+        float x2 = 0.0f;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int col = ch * 8 + col0;
+            xf[ch] = *reinterpret_cast<const float4 *>(row + (col < collim ? col : collim));
+            if (ch * 8 + 4 * half < d) {            // a real column (clamped ones repeat data and meet zero state rows)
+                x2 = fmaf(xf[ch].x, xf[ch].x, x2); x2 = fmaf(xf[ch].y, xf[ch].y, x2);
+                x2 = fmaf(xf[ch].z, xf[ch].z, x2); x2 = fmaf(xf[ch].w, xf[ch].w, x2);
+            }
+        }
+        float4 st[NST];
+        __syncthreads();                 // nobody still reads the stage (and hs is complete)
+        fetch_block(st, 0);
+        store_block(st, Ws);
+        float best = -INFINITY;
+        for (int cb = 0; cb < nblocks; ++cb) {
+            __syncthreads();
+            const float *Wc = Ws + (cb & 1) * WB * DP;
+            const bool more = cb + 1 < nblocks;
+            floatx16 acc0, acc1;
+            {
+                const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 h0 = hp[2 * q], h1 = hp[8 + 2 * q];
+                    acc0[4 * q + 0] = h0.x; acc0[4 * q + 1] = h0.y; acc0[4 * q + 2] = h0.z; acc0[4 * q + 3] = h0.w;
+                    acc1[4 * q + 0] = h1.x; acc1[4 * q + 1] = h1.y; acc1[4 * q + 2] = h1.z; acc1[4 * q + 3] = h1.w;
+                }
+            }
+            const float *w0row = Wc + l32 * DP + 4 * half;
+            const float *w1row = Wc + (32 + l32) * DP + 4 * half;
+            float4 a0 = *reinterpret_cast<const float4 *>(w0row);
+            float4 a1 = *reinterpret_cast<const float4 *>(w1row);
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                float4 n0 = a0, n1 = a1;
+                if (ch + 1 < NCH) {
+                    n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
+                    n1 = *reinterpret_cast<const float4 *>(w1row + (ch + 1) * 8);
+                }
+                const float4 xv = xf[ch];
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
+                if (ch == 0 && more) fetch_block(st, cb + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                a0 = n0; a1 = n1;
+            }
+            if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) best = fmaxf(best, fmaxf(acc0[r], acc1[r]));
+        }
+        best = fmaxf(best, __shfl_xor(best, 32, 64));       // the other half-wave saw the other centroid rows
+        x2 += __shfl_xor(x2, 32, 64);                       // ... and holds the other half of the dimensions
+        if (half == 0 && ok) sum += (double)fmaxf(0.5f * x2 - best, 0.0f);
+    }
+    sum = wave_sum_d(sum);
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = 0.0;
+        for (int v = 0; v < NWV; ++v) tot += red[v];
+        partials[blockIdx.x] = tot;
+    }
+}
+
+template <int NCH>
+hipError_t launch_qe_nch(const float *x, long long N, int d, int k, const float *w, double *partials, int nblocks, hipStream_t s)
+{
+    const int kpad = (k + WB - 1) / WB * WB;
+    const size_t lds = ((size_t)2 * WB * (NCH * 8 + 4) + kpad) * sizeof(float);
+    hipError_t e = hipFuncSetAttribute((const void *)quant_error_mfma_kernel<NCH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((quant_error_mfma_kernel<NCH>), dim3(nblocks), dim3(512), lds, s, x, N, k, d, w, partials);
+    return hipGetLastError();
+}
+
 constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 
 template <int NCH, bool RES, int NWV>
@@ -755,6 +899,24 @@ bool mfma_kernel_supports(int k, int d, int b, const void *x)
 {
     if (d % 4 != 0 || d > 128 || k < 2 || k > 32768 || b > 65535 || (((uintptr_t)x) & 15u) != 0) return false;
     return mfma_geom(k, b, mfma_chunks(d), false, 8).bytes <= MF_LDS_BUDGET;
+}
+
+bool mfma_quant_error_supports(int k, int d, const void *x)
+{
+    if (d % 4 != 0 || d < 16 || d > 128 || k < 32 || k > 32768 || (((uintptr_t)x) & 15u) != 0) return false;
+    const int kpad = (k + WB - 1) / WB * WB;
+    return ((size_t)2 * WB * (mfma_chunks(d) * 8 + 4) + kpad) * sizeof(float) <= MF_LDS_BUDGET;
+}
+
+hipError_t launch_quant_error_mfma(const float *x, long long N, int d, int k, const float *w, double *partials,
+                                   int nblocks, hipStream_t s)
+{
+    switch (mfma_chunks(d)) {
+        case 4: return launch_qe_nch<4>(x, N, d, k, w, partials, nblocks, s);
+        case 8: return launch_qe_nch<8>(x, N, d, k, w, partials, nblocks, s);
+        case 13: return launch_qe_nch<13>(x, N, d, k, w, partials, nblocks, s);
+        default: return launch_qe_nch<16>(x, N, d, k, w, partials, nblocks, s);
+    }
 }
 
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s)

@@ -734,6 +734,77 @@ hipError_t launch_shape(const StepParams &p, long long t0, long long t1, hipStre
 
 }  // namespace
 
+namespace {
+
+// Eq. 8 for k = d = 10: a lane takes a sample (40 B straight into registers, four samples in flight), forms
+// the expanded-form scores x.w_c - |w_c|^2/2 against register copies of the state and adds
+// |x|^2/2 - max_c score = min_c |x - w_c|^2 / 2 in fp64.  The assignment of samples to threads is fixed,
+// so is every order of summation: the result does not depend on scheduling.
+template <int K, int D>
+__global__ __launch_bounds__(256) void quant_error_small_kernel(const float *__restrict__ x, long long N,
+                                                                const float *__restrict__ w, double *partials)
+{
+    __shared__ float sw[K * D];
+    __shared__ float sh[K];
+    __shared__ double red[256];
+    for (int e = threadIdx.x; e < K * D; e += 256) sw[e] = w[e];
+    __syncthreads();
+    if (threadIdx.x < K) {
+        float s = 0.0f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) s = fmaf(sw[threadIdx.x * D + j], sw[threadIdx.x * D + j], s);
+        sh[threadIdx.x] = -0.5f * s;
+    }
+    __syncthreads();
+    float wv[K * D], hv[K];
+#pragma unroll
+    for (int e = 0; e < K * D; ++e) wv[e] = sw[e];
+#pragma unroll
+    for (int c = 0; c < K; ++c) hv[c] = sh[c];
+
+    constexpr int U = 4;
+    const long long stride = (long long)gridDim.x * 256;
+    double sum = 0.0;
+    for (long long n0 = (long long)blockIdx.x * 256 + threadIdx.x; n0 < N; n0 += U * stride) {
+        float xr[U][D];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long n = n0 + u * stride;
+            load_row<D>(xr[u], x + (size_t)(n < N ? n : N - 1) * D);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float x2 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < D; ++j) x2 = fmaf(xr[u][j], xr[u][j], x2);
+            float best = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < K; ++c) {
+                float sc = hv[c];
+#pragma unroll
+                for (int j = 0; j < D; ++j) sc = fmaf(xr[u][j], wv[c * D + j], sc);
+                best = fmaxf(best, sc);
+            }
+            if (n0 + u * stride < N) sum += (double)fmaxf(0.5f * x2 - best, 0.0f);
+        }
+    }
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partials[blockIdx.x] = red[0];
+}
+
+}  // namespace
+
+hipError_t launch_quant_error_small(const float *x, long long N, const float *w, double *partials, int nblocks, hipStream_t s)
+{
+    hipLaunchKernelGGL((quant_error_small_kernel<10, 10>), dim3(nblocks), dim3(256), 0, s, x, N, w, partials);
+    return hipGetLastError();
+}
+
 size_t small_kernel_message_bytes(int k, int d)
 {
     if (!(k == 10 && d == 10)) return 0;
