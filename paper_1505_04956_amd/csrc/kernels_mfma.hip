@@ -56,6 +56,19 @@ __device__ __forceinline__ void top3_insert(Top3 &t, float s, int c)
     t.v1 = g1 ? s : t.v1;
 }
 
+// Value-only insert into a sorted triple (v1 >= v2 >= v3): three instructions.  Used on scores whose low five
+// mantissa bits were replaced by the number of the accumulator register they came from.
+__device__ __forceinline__ void top3_insert_value(Top3 &t, float s)
+{
+    t.v3 = __builtin_amdgcn_fmed3f(t.v2, t.v3, s);
+    t.v2 = __builtin_amdgcn_fmed3f(t.v1, t.v2, s);
+    t.v1 = __builtin_amdgcn_fmed3f(t.v1, s, INFINITY);
+}
+__device__ __forceinline__ float tag_low5(float v, int r)
+{
+    return __int_as_float((__float_as_int(v) & ~31) | r);
+}
+
 __device__ __forceinline__ double wave_sum_d(double v)
 {
 #pragma unroll
@@ -211,7 +224,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         // roundings inside h_c, each relative to |x||w_c| + |h_c| <= sqrt(max|x|^2 max|w|^2) + max|w|^2/2,
         // doubled in case the matrix core truncates where a vector instruction would round to nearest.
         const float Bb = sqrtf(xn2) * sqrtf(wn2max) + 0.5f * wn2max;
-        const float thr = 2.0f * (float)(2 * DP8 + 18) * 5.9604645e-8f * Bb;
+        // ... plus 2^-18 relative for each of the two scores compared: the register tag in their low mantissa bits.
+        const float thr = (2.0f * (float)(2 * DP8 + 18) * 5.9604645e-8f + 7.62939453125e-6f) * Bb;
 
         // ================= phase 1: assignment =================
         // Fragment ch of the sample in row `rowoff` (an offset in floats).  Columns past d are read from a clamped,
@@ -322,13 +336,27 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 else if (lastb) chunk_loop(std::integral_constant<int, 2>());
                 else chunk_loop(std::integral_constant<int, 0>());
                 if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
-                // running arg-max of this lane's sample over the 32 rows it sees in this block: register r of a
-                // 32x32 tile is row 8*(r/4) + 4*half + r%4, visited in increasing order
-                const int cbase = cb * WB + 4 * half;
+                // Running top three of this lane's sample over the 32 rows it sees in this block.  The register number
+                // (0..31) rides in the low five mantissa bits of the score (2^-18 relative, covered by thr), so an
+                // insert is three value-only instructions; which BLOCK the two largest came from is found once per
+                // block by comparing bit patterns before and after (i1, i2 hold block numbers until the loop ends).
+                // Two different elements with the same bit pattern end up as v1 == v2 or v2 == v3, which the
+                // decisions below treat as "more than two candidates".
+                const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert(top, acc0[r], cbase + 8 * (r >> 2) + (r & 3));
+                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc0[r], r));
 #pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert(top, acc1[r], cbase + 32 + 8 * (r >> 2) + (r & 3));
+                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], 16 + r));
+                const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2);
+                const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : cb);
+                top.i1 = (n1 != o1) ? cb : top.i1;
+                top.i2 = nb2;
+            }
+            {
+                // block number + register number -> centroid: register r of a 32x32 tile is row 8*(r/4) + 4*half + r%4
+                const int r1 = __float_as_int(top.v1) & 31, r2 = __float_as_int(top.v2) & 31;
+                top.i1 = top.i1 * WB + 32 * (r1 >> 4) + 8 * ((r1 & 15) >> 2) + 4 * half + (r1 & 3);
+                top.i2 = top.i2 * WB + 32 * (r2 >> 4) + 8 * ((r2 & 15) >> 2) + 4 * half + (r2 & 3);
             }
             // merge the two half-waves (same sample, other centroid rows)
             {
@@ -343,7 +371,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const bool mine = half == 0 && n < b;
             int arg = top.i1;
             const bool close2 = mine && !(top.v1 - top.v2 > thr);
-            const bool close3 = close2 && !(top.v1 - top.v3 > thr);
+            const bool close3 = close2 && (!(top.v1 - top.v3 > thr) || __float_as_int(top.v1) == __float_as_int(top.v2));
             // exact decision between two candidates, four flagged samples at a time:
             // |x - w_a|^2 - |x - w_b|^2 = sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j), in fp64
             unsigned long long pm = RES ? 0ull : __ballot(close2 && !close3);
