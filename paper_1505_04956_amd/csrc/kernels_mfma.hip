@@ -275,88 +275,111 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             Top3 top;
             top.v1 = top.v2 = top.v3 = -INFINITY;
             top.i1 = top.i2 = 0;
+            // The 64 rows of a block are done as two half-blocks of 32 rows (one 32x32 accumulator each), and the running
+            // top three of a half-block's scores is updated while the matrix cores work on the NEXT half-block: the
+            // wave issues one matrix instruction per 64 cycles, the vector instructions of the inserts fit in between.
+            // acc1 therefore lives across iterations.
+            floatx16 acc0, acc1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+            // Inserts the 16 scores of `prev` (tag = 2*block + which accumulator; -1: nothing real) spread over the
+            // chunks of the half-block that is being computed into `acc`.  The register number (0..15) rides in the
+            // low mantissa bits of a score (2^-18 relative, covered by thr), so an insert is three value-only
+            // instructions; which half-block the two largest came from is found by comparing bit patterns before and
+            // after (i1, i2 hold tags until the loop ends).  Two different elements with the same bit pattern end up
+            // as v1 == v2 or v2 == v3, which the decisions below treat as "more than two candidates".
+            auto half_block = [&](auto mode, auto ins, floatx16 &acc, const float *wrow, const floatx16 &prev, int prev_tag,
+                                  int cb) {
+                constexpr int MODE = decltype(mode)::value;
+                constexpr bool INS = decltype(ins)::value;      // false: first half-block of a tile, nothing to insert
+                unsigned nextoff = 0;
+                if constexpr (MODE == 2) {
+                    nextoff = rowoff_of(tile0 + TM);
+                    asm volatile("" : "+v"(nextoff));          // keep the address arithmetic inside this block
+                }
+                const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
+                float4 a = *reinterpret_cast<const float4 *>(wrow);
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    // operands of the next chunk are read under the matrix work of this one; the scheduling
+                    // barrier keeps the compiler from hoisting the reads of ALL chunks to the top (registers)
+                    float4 nx = a;
+                    if (ch + 1 < NCH) nx = *reinterpret_cast<const float4 *>(wrow + (ch + 1) * 8);
+                    const float4 xv = xf[ch];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, xv.x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, xv.y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, xv.z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, xv.w, acc, 0, 0, 0);
+                    if constexpr (INS) {
+#pragma unroll
+                        for (int r = ch * 16 / NCH; r < (ch + 1) * 16 / NCH; ++r)
+                            top3_insert_value(top, tag_low5(prev[r], r));
+                    }
+                    if constexpr (MODE == 1) {
+                        if (ch == 0) fetch_block(st, cb + 1);   // not before the first chunk: it waits for all loads
+                    }
+                    // the last half-block has used this fragment for the last time: fetch the next tile's into its
+                    // place, so that the fetch runs behind the matrix work and the epilogue of this tile
+                    if constexpr (MODE == 2) xf[ch] = frag(nextoff, ch);
+                    __builtin_amdgcn_sched_barrier(0);
+                    a = nx;
+                }
+                if constexpr (INS) {
+                    const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2);
+                    const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : prev_tag);
+                    top.i1 = (n1 != o1) ? prev_tag : top.i1;
+                    top.i2 = nb2;
+                }
+            };
+            using M0 = std::integral_constant<int, 0>;
+            using M1 = std::integral_constant<int, 1>;
+            using M2 = std::integral_constant<int, 2>;
             for (int cb = 0; cb < g.nblocks; ++cb) {
                 if constexpr (!RES) __syncthreads();      // Ws[cb & 1] complete; Ws[(cb + 1) & 1] free
                 const float *Wc = Ws + (RES ? cb : (cb & 1)) * WB * DP;
                 const bool more = !RES && cb + 1 < g.nblocks;
                 const bool lastb = refill && cb + 1 == g.nblocks;
-                floatx16 acc0, acc1;
-                {
-                    const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 h0 = hp[2 * q], h1 = hp[8 + 2 * q];
-                        acc0[4 * q + 0] = h0.x; acc0[4 * q + 1] = h0.y; acc0[4 * q + 2] = h0.z; acc0[4 * q + 3] = h0.w;
-                        acc1[4 * q + 0] = h1.x; acc1[4 * q + 1] = h1.y; acc1[4 * q + 2] = h1.z; acc1[4 * q + 3] = h1.w;
-                    }
-                }
+                const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
                 const float *w0row = Wc + l32 * DP + 4 * half;
                 const float *w1row = Wc + (32 + l32) * DP + 4 * half;
-                // MODE 0: plain; 1: fetch the next block of the state after the first chunk (not before it: the first
-                // chunk waits for all outstanding loads); 2: last block, refill the fragments.  No control flow
-                // inside, so that the operand reads of a chunk can be scheduled under the matrix work of the previous.
-                auto chunk_loop = [&](auto mode) {
-                    constexpr int MODE = decltype(mode)::value;
-                    unsigned nextoff = 0;
-                    if constexpr (MODE == 2) {
-                        nextoff = rowoff_of(tile0 + TM);
-                        asm volatile("" : "+v"(nextoff));          // keep the address arithmetic inside this block
-                    }
-                    float4 a0 = *reinterpret_cast<const float4 *>(w0row);
-                    float4 a1 = *reinterpret_cast<const float4 *>(w1row);
 #pragma unroll
-                    for (int ch = 0; ch < NCH; ++ch) {
-                        // operands of the next chunk are read under the matrix work of this one; the scheduling
-                        // barrier keeps the compiler from hoisting the reads of ALL chunks to the top (registers)
-                        float4 n0 = a0, n1 = a1;
-                        if (ch + 1 < NCH) {
-                            n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
-                            n1 = *reinterpret_cast<const float4 *>(w1row + (ch + 1) * 8);
-                        }
-                        const float4 xv = xf[ch];
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
-                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
-                        if constexpr (MODE == 1) {
-                            if (ch == 0) fetch_block(st, cb + 1);
-                        }
-                        // the last block has used this fragment for the last time: fetch the next tile's into its
-                        // place, so that the fetch runs behind the matrix work and the epilogue of this tile
-                        if constexpr (MODE == 2) xf[ch] = frag(nextoff, ch);
-                        __builtin_amdgcn_sched_barrier(0);
-                        a0 = n0; a1 = n1;
-                    }
-                };
-                if (more) chunk_loop(std::integral_constant<int, 1>());
-                else if (lastb) chunk_loop(std::integral_constant<int, 2>());
-                else chunk_loop(std::integral_constant<int, 0>());
+                for (int q = 0; q < 4; ++q) {
+                    const float4 h0 = hp[2 * q];
+                    acc0[4 * q + 0] = h0.x; acc0[4 * q + 1] = h0.y; acc0[4 * q + 2] = h0.z; acc0[4 * q + 3] = h0.w;
+                }
+                // rows 0..31 of this block; meanwhile the scores of rows 32..63 of the previous block are inserted
+                if (cb == 0) {
+                    if (more) half_block(M1(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    else half_block(M0(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                } else {
+                    if (more) half_block(M1(), std::true_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
+                    else half_block(M0(), std::true_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 h1 = hp[8 + 2 * q];
+                    acc1[4 * q + 0] = h1.x; acc1[4 * q + 1] = h1.y; acc1[4 * q + 2] = h1.z; acc1[4 * q + 3] = h1.w;
+                }
+                // rows 32..63; meanwhile the scores of rows 0..31 are inserted
+                if (lastb) half_block(M2(), std::true_type(), acc1, w1row, acc0, 2 * cb, cb);
+                else half_block(M0(), std::true_type(), acc1, w1row, acc0, 2 * cb, cb);
                 if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
-                // Running top three of this lane's sample over the 32 rows it sees in this block.  The register number
-                // (0..31) rides in the low five mantissa bits of the score (2^-18 relative, covered by thr), so an
-                // insert is three value-only instructions; which BLOCK the two largest came from is found once per
-                // block by comparing bit patterns before and after (i1, i2 hold block numbers until the loop ends).
-                // Two different elements with the same bit pattern end up as v1 == v2 or v2 == v3, which the
-                // decisions below treat as "more than two candidates".
+            }
+            {
+                // the last half-block's scores
                 const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc0[r], r));
-#pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], 16 + r));
-                const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2);
-                const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : cb);
-                top.i1 = (n1 != o1) ? cb : top.i1;
+                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], r));
+                const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2), tg = 2 * g.nblocks - 1;
+                const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : tg);
+                top.i1 = (n1 != o1) ? tg : top.i1;
                 top.i2 = nb2;
             }
             {
-                // block number + register number -> centroid: register r of a 32x32 tile is row 8*(r/4) + 4*half + r%4
-                const int r1 = __float_as_int(top.v1) & 31, r2 = __float_as_int(top.v2) & 31;
-                top.i1 = top.i1 * WB + 32 * (r1 >> 4) + 8 * ((r1 & 15) >> 2) + 4 * half + (r1 & 3);
-                top.i2 = top.i2 * WB + 32 * (r2 >> 4) + 8 * ((r2 & 15) >> 2) + 4 * half + (r2 & 3);
+                // half-block tag + register number -> centroid: register r of a 32x32 tile is row 8*(r/4) + 4*half + r%4
+                const int r1 = __float_as_int(top.v1) & 15, r2 = __float_as_int(top.v2) & 15;
+                top.i1 = top.i1 * 32 + 8 * (r1 >> 2) + 4 * half + (r1 & 3);
+                top.i2 = top.i2 * 32 + 8 * (r2 >> 2) + 4 * half + (r2 & 3);
             }
             // merge the two half-waves (same sample, other centroid rows)
             {
