@@ -39,7 +39,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // Waves per workgroup is a template parameter NWV (8 or 4): a tile has 32 samples per wave.
 constexpr int WB = 64;           // centroid rows per block (2 matrix tiles of 32)
 constexpr int RB = 4;            // rows per wave and iteration in the row passes (loads in flight)
-constexpr int GS = 16;           // sample rows in flight per wave in the gather
+constexpr int GS = 16;           // sample rows in flight per wave in the gather (small clusters)
+constexpr int GU = 16;           // sample rows in flight per half-wave in the gather (large clusters)
 constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the nearest
 
 struct Top3 {
@@ -213,6 +214,11 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     long long rechecks = 0;
 
     for (long long t = t0; t < t1; ++t) {
+        // Two workgroups share a CU and the older one would win every arbitration for the matrix pipe, finish the
+        // launch early and leave the CU half empty: they take turns at the higher priority instead.  The phases
+        // after the matrix work issue few instructions and wait on memory: highest priority.
+        if (((int)(t & 1) != 0) != (blockIdx.x * 2 >= gridDim.x)) __builtin_amdgcn_s_setprio(2);
+        else __builtin_amdgcn_s_setprio(1);
         // Fresh, opaque copies of the lane id per phase: everything derived from them (addresses, masks) is then
         // recomputed per phase instead of being kept in registers across the whole step loop.
         int lane_p1 = threadIdx.x & 63;
@@ -486,6 +492,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int ch = 0; ch < NCH; ++ch) xa[ch] = frag(rowoff_of(0), ch);
             for (int tile0 = 0; tile0 < b; tile0 += TM) do_tile(xa, tile0);
         }
+        __builtin_amdgcn_s_setprio(3);
         if constexpr (RES) {
             // ---- deferred exact decisions between two candidates ----
             // The state rows are still in LDS.  A lane pair (l32, half 0/1) takes one flagged sample: its half of the
@@ -597,8 +604,44 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if (last) cursor[s] = base + rank + 1;
             }
         }
-        // gather: this wave's samples in (centroid, sample) order, GS rows in flight
-        {
+        // gather, large clusters: the wave's 64 lanes are two half-waves of 32 float4 columns; each half-wave sums
+        // the sample rows of one of the wave's centroids, in sample order, GU rows in flight per half-wave
+        if (b >= 8 * k) {
+            const int hw = lane >> 5, q4 = lane & 31;
+            const bool colok = 4 * q4 < d;
+            const int col = colok ? 4 * q4 : 0;
+            const int *cs = cstart + wave * g.kq;
+            for (int mp = 0; mp < g.kq; mp += 2) {
+                const int m = mp + hw;
+                const int c = wave + NWV * m;
+                const bool cok = m < g.kq && c < k;
+                const int a = cok ? (int)cs[m] : 0;
+                const int nrow = cok ? (int)cs[m + 1] - a : 0;
+                const int nmax = max(__builtin_amdgcn_readlane(nrow, 0), __builtin_amdgcn_readlane(nrow, 32));
+                float4 S = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                for (int it0 = 0; it0 < nmax; it0 += GU) {
+                    // past the end of its list a half-wave re-reads a valid row and adds 0 instead, so the loop
+                    // has no divergent branch
+                    float4 v[GU];
+                    int id[GU];
+#pragma unroll
+                    for (int u = 0; u < GU; ++u) id[u] = perm[it0 + u < nrow ? a + it0 + u : 0];
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < GU; ++u) v[u] = *reinterpret_cast<const float4 *>(xb + (id[u] * d + col));
+#pragma unroll
+                    for (int u = 0; u < GU; ++u) {
+                        const bool ok = it0 + u < nrow;
+                        S.x += ok ? v[u].x : 0.0f; S.y += ok ? v[u].y : 0.0f;
+                        S.z += ok ? v[u].z : 0.0f; S.w += ok ? v[u].w : 0.0f;
+                    }
+                }
+                if (colok && cok) *reinterpret_cast<float4 *>(gsc + (size_t)c * d + 4 * q4) = S;
+            }
+        }
+        // gather, small clusters: this wave's samples in (centroid, sample) order, GS rows in flight whatever the
+        // cluster boundaries; one lane per column
+        else {
             const int pos0 = __builtin_amdgcn_readfirstlane(cstart[wave * g.kq]);
             const int pos1 = __builtin_amdgcn_readfirstlane(cstart[(wave + 1) * g.kq]);
             int cur = -1;
