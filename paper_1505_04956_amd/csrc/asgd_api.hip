@@ -342,18 +342,21 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     }
     // Deterministic mode: a worker may only read the message of round r-1 once its sender has
     // finished that round.  Either the whole run is one launch of co-resident workgroups that wait
-    // for each other's stamps (small-state kernel), or a launch never crosses a multiple of E, so
-    // that the message was written by an earlier launch on the same stream.
+    // for each other's stamps (small-state and matrix-core kernels, when the workers all fit the
+    // device), or a launch never crosses a multiple of E, so that the message was written by an
+    // earlier launch on the same stream.
     const bool rounds = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
     int launches = 0;
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
     bool done = false;
-    if (rounds && kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3 && steps > 0) {
+    const bool one_launch = (kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3) || (kernel == ASGD_KERNEL_MFMA && !(ctx->tune & 4));
+    if (rounds && one_launch && steps > 0) {
         // every worker has passed the merge points before the first step of this run
         const long long r0 = ctx->t / ctx->E;
         const int passed = (int)((ctx->t % ctx->E) != 0 ? r0 : (r0 > 0 ? r0 - 1 : 0));
         HIP_TRY(ctx, hipMemsetD32Async((hipDeviceptr_t)ctx->consumed, passed, (size_t)ctx->W, ctx->stream));
-        hipError_t e = launch_small_steps(p, ctx->t, t_end, ctx->stream, true);
+        hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ctx->t, t_end, ctx->stream, true)
+                                                     : launch_mfma_steps(p, ctx->t, t_end, ctx->xnorm2max, ctx->stream, true);
         if (e == hipSuccess) {
             done = true;
             launches = 1;
@@ -371,7 +374,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         }
         hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ta, tb, ctx->stream, false)
                        : (kernel == ASGD_KERNEL_MFMA)
-                           ? launch_mfma_steps(p, ta, tb, ctx->xnorm2max, ctx->stream)
+                           ? launch_mfma_steps(p, ta, tb, ctx->xnorm2max, ctx->stream, false)
                            : launch_generic_steps(p, ta, tb, ctx->stream);
         HIP_TRY(ctx, e);
         ++launches;

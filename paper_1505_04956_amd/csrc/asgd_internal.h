@@ -85,7 +85,10 @@ hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, h
 // Matrix-core kernel: needs d % 4 == 0, d <= 128, 16-byte aligned samples and its LDS budget.
 bool mfma_kernel_supports(int k, int d, int b, const void *x);
 hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out, hipStream_t s);   // max_n |x_n|^2
-hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s);
+// persistent = true: as for the small-state kernel (deterministic mode; hipErrorCooperativeLaunchTooLarge when the
+// workers do not all fit the device at once)
+hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s,
+                             bool persistent);
 // shift_tab[q] = 1 + round_hash(seed, r0 + q) % (W - 1) for q in [0, n)
 hipError_t launch_schedule_table(uint64_t seed, long long r0, int n, int W, int *shift_tab, hipStream_t s);
 hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStream_t s);

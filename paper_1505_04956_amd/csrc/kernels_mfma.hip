@@ -43,6 +43,17 @@ constexpr int GS = 16;           // sample rows in flight per wave in the gather
 constexpr int GU = 16;           // sample rows in flight per half-wave in the gather (large clusters)
 constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the nearest
 
+// Bounded wait for a flag that another workgroup writes: false when the bound (a fraction of a second) expires.
+__device__ __forceinline__ bool mf_wait_flag(const int *flag, int want, bool at_least)
+{
+    for (int spin = 0; spin < (1 << 19); ++spin) {
+        const int v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (at_least ? (v >= want) : (v == want)) return true;
+        __builtin_amdgcn_s_sleep(8);
+    }
+    return false;
+}
+
 struct Top3 {
     float v1, v2, v3;
     int i1, i2;
@@ -146,9 +157,16 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
 // NWV: waves per workgroup.  8 by default (two per SIMD).  4 when the state is resident, two workgroups fit a CU
 // and there are more workers than CUs: two workers then share a CU and one's memory-bound phase 2 runs under the
 // other's matrix work.
+// sync = 0: the launch holds nothing a worker has to wait for (silent or free-running mode, or the host ends every
+//           launch at a multiple of E).
+// sync = 1: deterministic mode, the whole run is one launch of co-resident workgroups.  At a merge point a worker
+//           waits for the stamp of the message addressed to it (its sender writes it at the end of the round
+//           before), and a sender waits until the recipient has passed the merge point that read the older message
+//           in the same buffer.  Every wait is on an earlier round, so the waits cannot form a cycle, and every
+//           wait is bounded: when the bound expires the worker goes on without the message and the host reports it.
 template <int NCH, bool RES, int NWV>
 __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
-                                                                 const float *xnorm2max_ptr)
+                                                                 const float *xnorm2max_ptr, int sync)
 {
     constexpr int DP8 = NCH * 8;                 // padded row length
     constexpr int DP = DP8 + 4;                  // LDS row stride
@@ -574,13 +592,27 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (tid == MF_THREADS - 1) {
             int has = 0;
             if (merge_point) {
-                const int st = p.stamp[(size_t)rpar * p.W + i];
-                has = det ? (st == (int)(r_now - 1)) : (st >= 0);
-                p.stamp[(size_t)rpar * p.W + i] = -1;
+                int *stp = p.stamp + (size_t)rpar * p.W + i;
+                if (det) {
+                    // stamps of one buffer only grow, so the test for the round needs no clearing
+                    if (sync) {
+                        const long long rs = r_now - 1;
+                        const int shift = (int)(1 + round_hash(p.seed, rs) % (uint64_t)(p.W - 1));
+                        const int sender = (i - shift + p.W) % p.W;
+                        if (!message_dropped(p.seed, rs, sender, p.drop_thr) && !mf_wait_flag(stp, (int)rs, false))
+                            atomicOr(p.error_flag, 1);
+                    }
+                    has = __hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)(r_now - 1);
+                } else {
+                    has = *stp >= 0;
+                    *stp = -1;
+                }
             }
             s_has_ext = has;
         }
         __syncthreads();
+        // the message was written by another workgroup, maybe on another XCD, during this launch
+        if (sync && merge_point) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         // placement: every wave walks all samples in order and places those of its own centroids
         int nbits = 1;
         while ((1 << nbits) < k) ++nbits;
@@ -797,18 +829,27 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
         }
 
+        // every wave has read the external state for the last time (barrier above): its buffer may be written again
+        if (sync && merge_point && tid == 0)
+            __hip_atomic_store(p.consumed + i, (int)r_now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
         // ---- send (Alg. 5 line 9) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
             const long long r = t / p.E;
             if (!message_dropped(p.seed, r, i, p.drop_thr)) {
                 const int peer = det ? peer_deterministic(p.seed, r, i, p.W) : peer_free(p.seed, r, i, p.W);
                 const int spar = det ? (int)(r & 1) : 0;
+                if (sync && r >= 2) {
+                    // the buffer still holds the message of round r - 2 until the peer has passed merge point r - 1
+                    if (tid == 0 && !mf_wait_flag(p.consumed + peer, (int)(r - 1), true)) atomicOr(p.error_flag, 1);
+                    __syncthreads();
+                }
                 float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)spar * p.W + peer) * kd);
                 const float4 *src = reinterpret_cast<const float4 *>(wst);
                 for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
                 __threadfence();
                 __syncthreads();
-                if (tid == 0) p.stamp[(size_t)spar * p.W + peer] = (int)r;
+                if (tid == 0) __hip_atomic_store(p.stamp + (size_t)spar * p.W + peer, (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }
@@ -968,23 +1009,45 @@ hipError_t launch_qe_nch(const float *x, long long N, int d, int k, const float 
 constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 
 template <int NCH, bool RES, int NWV>
-hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
+hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
     const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV).bytes;
-    hipError_t e = hipFuncSetAttribute((const void *)mfma_steps_kernel<NCH, RES, NWV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV>;
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max);
+    if (!persistent) {
+        hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max, 0);
+        return hipGetLastError();
+    }
+    // one launch with waits inside: every workgroup must be resident
+    int dev = 0, cus = 0, per_cu = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NWV, lds);
+    if (e != hipSuccess) return e;
+    if ((long long)per_cu * cus < p.W) return hipErrorCooperativeLaunchTooLarge;
+    StepParams pp = p;
+    long long a0 = t0, a1 = t1;
+    const float *xn = xnorm2max;
+    int sync = 1;
+    void *args[] = {&pp, &a0, &a1, &xn, &sync};
+    if (p.cooperative) return hipLaunchCooperativeKernel(kern, dim3(p.W), dim3(64 * NWV), args, (unsigned)lds, s);
+    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, pp, a0, a1, xn, sync);
     return hipGetLastError();
 }
 template <int NCH>
-hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
+hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
     // tune bit 0 forces 8 waves, bit 1 forces 4 waves (resident variant only)
     const size_t half_cu = 78 * 1024;      // two workgroups per CU must fit 160 KB, a little is reserved
     if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2)))
-        return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s);
-    if (mfma_geom(p.k, p.b, NCH, true, 8).bytes <= MF_LDS_BUDGET) return launch_variant<NCH, true, 8>(p, t0, t1, xnorm2max, s);
-    return launch_variant<NCH, false, 8>(p, t0, t1, xnorm2max, s);
+        return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);
+    // One workgroup per CU: the workers keep pace by themselves and one launch per round measured 1 % faster than the
+    // waits inside one launch; two workgroups per CU drift apart and gain 3 % from not meeting at every round.
+    if (persistent && !(p.tune & 8)) return hipErrorNotSupported;
+    if (mfma_geom(p.k, p.b, NCH, true, 8).bytes <= MF_LDS_BUDGET)
+        return launch_variant<NCH, true, 8>(p, t0, t1, xnorm2max, s, persistent);
+    return launch_variant<NCH, false, 8>(p, t0, t1, xnorm2max, s, persistent);
 }
 
 }  // namespace
@@ -1027,13 +1090,14 @@ hipError_t launch_rownorm2max(const float *x, long long rows, int d, float *out,
     return e != hipSuccess ? e : e2;
 }
 
-hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s)
+hipError_t launch_mfma_steps(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s,
+                             bool persistent)
 {
     switch (mfma_chunks(p.d)) {
-        case 4: return launch_nch<4>(p, t0, t1, xnorm2max, s);
-        case 8: return launch_nch<8>(p, t0, t1, xnorm2max, s);
-        case 13: return launch_nch<13>(p, t0, t1, xnorm2max, s);
-        default: return launch_nch<16>(p, t0, t1, xnorm2max, s);
+        case 4: return launch_nch<4>(p, t0, t1, xnorm2max, s, persistent);
+        case 8: return launch_nch<8>(p, t0, t1, xnorm2max, s, persistent);
+        case 13: return launch_nch<13>(p, t0, t1, xnorm2max, s, persistent);
+        default: return launch_nch<16>(p, t0, t1, xnorm2max, s, persistent);
     }
 }
 

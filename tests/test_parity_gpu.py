@@ -240,6 +240,26 @@ def test_matrix_core_kernel_options(B, oracle):
         bad.run_steps(1)
 
 
+@pytest.mark.parametrize("tune", [2, 8])
+def test_matrix_core_kernel_one_launch(B, oracle, tune):
+    """Deterministic mode as ONE launch whose workgroups wait for each other's messages (four waves per worker:
+    the default there; eight waves: forced by the tune bit), against the oracle and, bit for bit, against one launch
+    per round; with lost messages, and continued in the middle of a round."""
+    X = make_data(12 * 900 + 5, 20, 40, seed=27)
+    for drop in (0.0, 0.4):
+        g, o = run_both(B, oracle, X, 40, 12, 100, 0.05, 2, 17, drop_rate=drop, kernel=3, tune=tune)
+        assert g.stats().kernel == 3 and g.stats().launches == 1
+        Xg = to_dev(X)
+        per_round = B.ASGD(40, 20, 12, 100, 0.05, E=2, drop_rate=drop, kernel=3, tune=(tune & 2) | 4)
+        per_round.load_shards(Xg); per_round.run_steps(17)
+        assert per_round.stats().launches == 9
+        assert np.array_equal(g.get_state(), per_round.get_state())
+        assert np.array_equal(g.worker_counters(), per_round.worker_counters())
+        parts = B.ASGD(40, 20, 12, 100, 0.05, E=2, drop_rate=drop, kernel=3, tune=tune)
+        parts.load_shards(Xg); parts.run_steps(5); parts.run_steps(1); parts.run_steps(11)
+        assert np.array_equal(g.get_state(), parts.get_state())
+
+
 def test_stored_values_of_tiny_workload(B):
     """GPU path against the values the oracle wrote to tests/golden/cfg0_oracle.json."""
     import json
