@@ -180,6 +180,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     __shared__ double red_d[3][MF_WAVES];
     __shared__ float red_f[MF_WAVES];
     __shared__ int s_has_ext;
+    __shared__ int s_next_rows;
 
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -262,8 +263,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int col = ch * 8 + col0 < collim ? ch * 8 + col0 : collim;
             return *reinterpret_cast<const float4 *>(xb + (rowoff + (unsigned)col));
         };
-        auto rowoff_of = [&](int tile0) -> unsigned {
-            const int n = tile0 + wave * 32 + l32;
+        auto rowoff_of = [&](int nbase) -> unsigned {      // nbase: first of the wave's 32 rows
+            const int n = nbase + l32;
             return (unsigned)(n < b ? n : 0) * (unsigned)d;
         };
         auto fetch_block = [&](float4(&st)[NST], int cb) {       // block cb of the state -> registers
@@ -288,8 +289,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             }
         };
-        auto do_tile = [&](float4(&xf)[NCH], int tile0) {
-            const bool refill = tile0 + TM < b;
+        // the wave's rows nbase .. nbase + 31; its next rows start at nbase_next (past the mini-batch: none)
+        auto do_tile = [&](float4(&xf)[NCH], int nbase, int nbase_next, bool refill) {
             float4 st[NST];
             if constexpr (!RES) {
                 __syncthreads();             // nobody still reads the stage
@@ -318,7 +319,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 constexpr bool INS = decltype(ins)::value;      // false: first half-block of a tile, nothing to insert
                 unsigned nextoff = 0;
                 if constexpr (MODE == 2) {
-                    nextoff = rowoff_of(tile0 + TM);
+                    nextoff = rowoff_of(nbase_next);
                     asm volatile("" : "+v"(nextoff));          // keep the address arithmetic inside this block
                 }
                 const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
@@ -413,7 +414,6 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 top3_insert(top, pv2, pi2);
                 top.v3 = fmaxf(top.v3, pv3);
             }
-            const int nbase = tile0 + wave * 32;
             const int n = nbase + l32;                    // this lane pair's sample
             const bool mine = half == 0 && n < b;
             int arg = top.i1;
@@ -502,13 +502,28 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     store_block(st, Ws + cb * WB * DP);
                 }
             }
+            if (tid == 0) s_next_rows = TM;                   // the first 32 rows of every wave are fixed
             __syncthreads();
         }
         {
             float4 xa[NCH];
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) xa[ch] = frag(rowoff_of(0), ch);
-            for (int tile0 = 0; tile0 < b; tile0 += TM) do_tile(xa, tile0);
+            for (int ch = 0; ch < NCH; ++ch) xa[ch] = frag(rowoff_of(wave * 32), ch);
+            if constexpr (RES) {
+                // No barrier inside this phase: the waves take their groups of 32 rows from a counter, so that a
+                // wave that is held up (it shares its SIMD with a wave of another workgroup) does fewer of them.
+                int cur = wave * 32;
+                while (cur < b) {
+                    int v = 0;
+                    if (lane == 0) v = atomicAdd(&s_next_rows, 32);
+                    const int nxt = __builtin_amdgcn_readfirstlane(v);
+                    do_tile(xa, cur, nxt, nxt < b);
+                    cur = nxt;
+                }
+            } else {
+                for (int tile0 = 0; tile0 < b; tile0 += TM)
+                    do_tile(xa, tile0 + wave * 32, tile0 + TM + wave * 32, tile0 + TM < b);
+            }
         }
         __builtin_amdgcn_s_setprio(3);
         if constexpr (RES) {
@@ -516,6 +531,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             // The state rows are still in LDS.  A lane pair (l32, half 0/1) takes one flagged sample: its half of the
             // dimensions of sum_j (w_aj - w_bj)(w_aj + w_bj - 2 x_j) in fp64, x fetched again (it is cache-hot), then
             // the halves are added.  32 samples per pass, so the memory latency is paid once per pass, not per sample.
+            __syncthreads();       // the flags of a wave's rows below may come from any wave
             unsigned short *mylist = flist + wave * 32 * ((b + TM - 1) / TM);
             int nfl = 0;
             for (int tile0 = 0; tile0 < b; tile0 += TM) {
