@@ -21,6 +21,7 @@
  *   update w <- w - eps * merged step ....................... Alg. 5 line 8, Fig. 4 stage IV
  *   send of the new state to one other worker ............... Alg. 5 line 9, Fig. 2 stage I
  *   empty external buffer <=> zero norm ..................... Eq. 3 (lambda)
+ *   merge of N external buffers, each gated on its own ...... Eq. 3 (no gate), Eq. 6 (gated)
  *   quantization error E(w) ................................. Eq. 8
  *
  * Readings taken where the paper is silent or inconsistent (each is listed with its
@@ -35,9 +36,14 @@
  *     E = 0 never sends = SimuParallelSGD with mini-batches); the receiver looks at
  *     its buffer at the start of the following step, uses the message once, and
  *     clears the buffer;
- *   - one external buffer per worker and one recipient per message; the recipient
- *     is worker (i + 1 + h(seed, round) mod (W-1)) mod W, a cyclic shift shared by
- *     all senders of a round, so every worker receives exactly one message per round;
+ *   - N external buffers per worker (default 1) and as many recipients per message:
+ *     copy n of a message goes to worker (i + 1 + (h(seed, round) + n) mod (W-1)) mod W,
+ *     a cyclic shift shared by all senders of a round, into the recipient's buffer n, so
+ *     every worker receives exactly N messages per round, from N different senders;
+ *   - in Eq. 3 the count |N| runs over the external buffers only (the printed sum starts
+ *     at n = 0, which would count the local state twice and would not give Eq. 2 for N = 1);
+ *     with the gate switched off every non-empty buffer takes part (Eq. 3), with the gate
+ *     on every buffer is tested by Eq. 4 against the same projected local step (Eq. 6);
  *   - Eq. 4 uses whole-state norms and a strict "<".
  *
  * Parity status: every function here is pinned by tests/test_oracle_pins.py.
@@ -62,19 +68,29 @@ static uint64_t round_hash(uint64_t seed, int64_t r)
     return mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(r + 1));
 }
 
-/* Recipient of worker i's message of round r (deterministic schedule). W >= 2. */
-int64_t asgd_oracle_peer(uint64_t seed, int64_t r, int64_t i, int64_t W)
+/* Recipient of copy n of worker i's message of round r (deterministic schedule).
+   W >= 2, 0 <= n < W - 1: the shifts of one round are different and never 0. */
+int64_t asgd_oracle_peer_n(uint64_t seed, int64_t r, int64_t i, int64_t W, int64_t n)
 {
-    uint64_t shift = 1 + round_hash(seed, r) % (uint64_t)(W - 1);
+    uint64_t shift = 1 + (round_hash(seed, r) % (uint64_t)(W - 1) + (uint64_t)n) % (uint64_t)(W - 1);
     return (int64_t)(((uint64_t)i + shift) % (uint64_t)W);
 }
+int64_t asgd_oracle_peer(uint64_t seed, int64_t r, int64_t i, int64_t W)
+{
+    return asgd_oracle_peer_n(seed, r, i, W, 0);
+}
 
-/* Test hook: is the message that `sender` emits in round r lost on the way?
+/* Test hook: is copy n of the message that `sender` emits in round r lost on the way?
    drop_threshold is a 24-bit fixed-point probability (0 = never, 2^24 = always). */
+int asgd_oracle_dropped_n(uint64_t seed, int64_t r, int64_t sender, int64_t n, uint32_t drop_threshold)
+{
+    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1) +
+                       0xD1B54A32D192ED03ULL * (uint64_t)n) >> 40;
+    return u < (uint64_t)drop_threshold;
+}
 int asgd_oracle_dropped(uint64_t seed, int64_t r, int64_t sender, uint32_t drop_threshold)
 {
-    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1)) >> 40;
-    return u < (uint64_t)drop_threshold;
+    return asgd_oracle_dropped_n(seed, r, sender, 0, drop_threshold);
 }
 
 int asgd_oracle_threads(void)
@@ -142,11 +158,11 @@ double asgd_oracle_quant_error(const float *X, int64_t n, int d, int k, const do
 /* ---- one worker, one mini-batch step ------------------------------------------------
    w:       k*d state at the start of the step (read only)
    wnew:    k*d state after the step
-   ext:     external buffer content or NULL when there is nothing to merge
-   returns bit 0 = message was looked at (received), bit 1 = accepted by Eq. 4,
-           bit 2 = Parzen near-tie (|lhs-rhs|/rhs < 1e-6)                                */
+   ext:     the next non-empty external buffers of this merge point (next = 0: nothing to merge)
+   returns the number of buffers accepted by Eq. 4 (or merged without the gate) in bits 0-7,
+           bit 8 = a Parzen near-tie (|lhs-rhs|/rhs < 1e-6) in one of them                  */
 static int worker_step(const float *M, int b, int k, int d, double eps, int lr_mode, int parzen,
-                       const double *w, double *wnew, const double *ext, int64_t *ncum,
+                       const double *w, double *wnew, const double *const *ext, int next, int64_t *ncum,
                        int32_t *assign_out, double *gap_out, int64_t *argmin_near)
 {
     const size_t kd = (size_t)k * d;
@@ -188,26 +204,32 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
                 size_t e = (size_t)c * d + j;
                 G[e] = ((double)cnt[c] * w[e] - Ssum[e]) / (double)b;
             }
-        int delta = 0;
-        if (ext) {
-            flags |= 1;
+        int delta[256];
+        int ndelta = 0;
+        for (int n = 0; n < next; ++n) {
             /* Eq. 4: compare the projected local step with the current state, both
                measured from the external state. */
             double lhs = 0.0, rhs = 0.0;
             for (size_t e = 0; e < kd; ++e) {
-                double a = (w[e] - eps * G[e]) - ext[e];
-                double c2 = w[e] - ext[e];
+                double a = (w[e] - eps * G[e]) - ext[n][e];
+                double c2 = w[e] - ext[n][e];
                 lhs += a * a;
                 rhs += c2 * c2;
             }
-            delta = parzen ? (lhs < rhs) : 1;
-            if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) flags |= 4;
-            if (delta) flags |= 2;
+            delta[n] = parzen ? (lhs < rhs) : 1;
+            if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) flags |= 256;
+            ndelta += delta[n];
         }
-        /* Eq. 7 then Alg. 5 line 8. */
+        flags |= ndelta;
+        /* Eq. 6 (one buffer: Eq. 7; gate off: Eq. 3) with the mini-batch gradient, then Alg. 5 line 8. */
         for (size_t e = 0; e < kd; ++e) {
             double Gbar = G[e];
-            if (delta) Gbar += w[e] - 0.5 * (w[e] + ext[e]);
+            if (ndelta > 0) {
+                double sum = w[e];
+                for (int n = 0; n < next; ++n)
+                    if (delta[n]) sum += ext[n][e];
+                Gbar += w[e] - sum / (double)(ndelta + 1);
+            }
             wnew[e] = w[e] - eps * Gbar;
         }
     }
@@ -222,18 +244,20 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
  *
  * X           N x d fp32 row-major; shard i = rows [i*H, (i+1)*H), H = floor(N/W)
  * w           W*k*d fp64 states, in/out
- * slot        W*k*d fp64 external buffers, in/out (all-zero = empty, Eq. 3)
- * slot_stamp  W round numbers of the buffered messages (-1 = none), in/out
+ * nb          external buffers per worker = recipients per message (1 <= nb <= 255, nb < W or W == 1)
+ * slot        nb*W*k*d fp64 external buffers, buffer n of worker i at (n*W + i)*k*d, in/out
+ *             (all-zero = empty, Eq. 3)
+ * slot_stamp  nb*W round numbers of the buffered messages (-1 = none), in/out
  * ncum        W*k cumulative assignment counts (lr_mode 1 only), in/out
  * t_io        global step counter shared by all workers, in/out
- * counters    W*3: sent, received, accepted ("good" messages), in/out
+ * counters    W*3: sending rounds, messages looked at, messages merged ("good" messages), in/out
  * near        2 counters: argmin near-ties, Parzen near-ties, in/out
  * assign_out  optional nsteps*W*b assignments, step-major then worker then sample
  * gap_out     optional, same shape: (d2-d1)/d1 of each assignment
  * lr_mode     0 = constant eps, 1 = per-centroid 1/count (requires E == 0)
  * returns 0, or -1 on invalid arguments
  */
-int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, double eps, int E,
+int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, double eps, int E, int nb,
                       uint64_t seed, int parzen, int lr_mode, uint32_t drop_threshold,
                       int64_t nsteps, double *w, double *slot, int64_t *slot_stamp, int64_t *ncum,
                       int64_t *t_io, int64_t *counters, int64_t *near, int32_t *assign_out,
@@ -244,9 +268,11 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
     const int64_t S = H / b;           /* full mini-batches per epoch */
     if (H < k || S < 1) return -1;
     if (lr_mode == 1 && E != 0) return -1;
+    if (nb < 1 || nb > 255 || (W > 1 && nb > W - 1)) return -1;
     const size_t kd = (size_t)k * d;
     double *wnew = (double *)malloc((size_t)W * kd * sizeof(double));
     int *flags = (int *)malloc((size_t)W * sizeof(int));
+    int *looked = (int *)malloc((size_t)W * sizeof(int));
     int64_t *near_w = (int64_t *)calloc((size_t)W, sizeof(int64_t));
     int64_t t = *t_io;
 
@@ -256,35 +282,41 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
 #pragma omp parallel for schedule(static)
         for (int i = 0; i < W; ++i) {
             const float *M = X + ((size_t)i * H + (size_t)s * b) * d;
-            const double *ext = NULL;
-            if (merge_point && slot_stamp[i] == t / E - 1) {
+            const double *ext[256];
+            int next = 0;
+            for (int n = 0; merge_point && n < nb; ++n) {
+                const double *buf = slot + ((size_t)n * W + i) * kd;
+                if (slot_stamp[(size_t)n * W + i] != t / E - 1) continue;
                 double nrm = 0.0;
-                for (size_t e = 0; e < kd; ++e) nrm += slot[i * kd + e] * slot[i * kd + e];
-                if (nrm > 0.0) ext = slot + i * kd;     /* lambda of Eq. 3 */
+                for (size_t e = 0; e < kd; ++e) nrm += buf[e] * buf[e];
+                if (nrm > 0.0) ext[next++] = buf;       /* lambda of Eq. 3 */
             }
+            looked[i] = next;
             int32_t *ao = assign_out ? assign_out + ((size_t)n * W + i) * b : NULL;
             double *go = gap_out ? gap_out + ((size_t)n * W + i) * b : NULL;
-            flags[i] = worker_step(M, b, k, d, eps, lr_mode, parzen, w + i * kd, wnew + i * kd, ext,
+            flags[i] = worker_step(M, b, k, d, eps, lr_mode, parzen, w + i * kd, wnew + i * kd, ext, next,
                                    ncum + (size_t)i * k, ao, go, &near_w[i]);
         }
         for (int i = 0; i < W; ++i) {
-            if (flags[i] & 1) counters[i * 3 + 1] += 1;
-            if (flags[i] & 2) counters[i * 3 + 2] += 1;
-            if (flags[i] & 4) near[1] += 1;
-            if (merge_point) {           /* a buffer is looked at once, then emptied */
-                memset(slot + i * kd, 0, kd * sizeof(double));
-                slot_stamp[i] = -1;
-            }
+            counters[i * 3 + 1] += looked[i];
+            counters[i * 3 + 2] += flags[i] & 255;
+            if (flags[i] & 256) near[1] += 1;
+        }
+        if (merge_point) {               /* a buffer is looked at once, then emptied */
+            memset(slot, 0, (size_t)nb * W * kd * sizeof(double));
+            for (size_t q = 0; q < (size_t)nb * W; ++q) slot_stamp[q] = -1;
         }
         memcpy(w, wnew, (size_t)W * kd * sizeof(double));
         if (E > 0 && W > 1 && (t + 1) % E == 0) {       /* Alg. 5 line 9 */
             const int64_t r = t / E;
             for (int i = 0; i < W; ++i) {
                 counters[i * 3 + 0] += 1;
-                if (asgd_oracle_dropped(seed, r, i, drop_threshold)) continue;
-                int64_t p = asgd_oracle_peer(seed, r, i, W);
-                memcpy(slot + p * kd, w + i * kd, kd * sizeof(double));
-                slot_stamp[p] = r;
+                for (int n = 0; n < nb; ++n) {
+                    if (asgd_oracle_dropped_n(seed, r, i, n, drop_threshold)) continue;
+                    int64_t p = asgd_oracle_peer_n(seed, r, i, W, n);
+                    memcpy(slot + ((size_t)n * W + p) * kd, w + i * kd, kd * sizeof(double));
+                    slot_stamp[(size_t)n * W + p] = r;
+                }
             }
         }
     }
@@ -292,6 +324,7 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
     *t_io = t;
     free(wnew);
     free(flags);
+    free(looked);
     free(near_w);
     return 0;
 }

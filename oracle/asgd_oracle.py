@@ -40,6 +40,10 @@ def lib():
         L.asgd_oracle_peer.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64]
         L.asgd_oracle_dropped.restype = C.c_int
         L.asgd_oracle_dropped.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_uint32]
+        L.asgd_oracle_peer_n.restype = C.c_int64
+        L.asgd_oracle_peer_n.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
+        L.asgd_oracle_dropped_n.restype = C.c_int
+        L.asgd_oracle_dropped_n.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, C.c_uint32]
         L.asgd_oracle_threads.restype = C.c_int
         L.asgd_oracle_set_threads.argtypes = [C.c_int]
         L.asgd_oracle_assign.restype = None
@@ -48,7 +52,7 @@ def lib():
         L.asgd_oracle_quant_error.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, f64p]
         L.asgd_oracle_steps.restype = C.c_int
         L.asgd_oracle_steps.argtypes = [
-            C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int,
+            C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int,
             C.c_uint64, C.c_int, C.c_int, C.c_uint32, C.c_int64,
             f64p, f64p, i64p, i64p, i64p, i64p, i64p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -61,12 +65,12 @@ def _f32(X) -> np.ndarray:
     return X
 
 
-def peer(seed: int, r: int, i: int, W: int) -> int:
-    return int(lib().asgd_oracle_peer(seed, r, i, W))
+def peer(seed: int, r: int, i: int, W: int, n: int = 0) -> int:
+    return int(lib().asgd_oracle_peer_n(seed, r, i, W, n))
 
 
-def dropped(seed: int, r: int, sender: int, threshold: int) -> bool:
-    return bool(lib().asgd_oracle_dropped(seed, r, sender, threshold))
+def dropped(seed: int, r: int, sender: int, threshold: int, n: int = 0) -> bool:
+    return bool(lib().asgd_oracle_dropped_n(seed, r, sender, n, threshold))
 
 
 def threads() -> int:
@@ -105,11 +109,12 @@ def drop_threshold(rate: float) -> int:
 
 
 class OracleASGD:
-    """Run state of the oracle: W fp64 states, one external buffer per worker, counters."""
+    """Run state of the oracle: W fp64 states, `buffers` external buffers per worker (slot[n, i] is buffer n of
+    worker i; with one buffer the leading axis is dropped), counters."""
 
     LR_CONST, LR_INV_COUNT = 0, 1
 
-    def __init__(self, X, k, W, b, lr, E=0, seed=1, parzen=True, lr_mode=0, drop_rate=0.0, w0=None):
+    def __init__(self, X, k, W, b, lr, E=0, seed=1, parzen=True, lr_mode=0, drop_rate=0.0, w0=None, buffers=1):
         self.X = _f32(X)
         self.N, self.d = self.X.shape
         self.k, self.W, self.b, self.lr, self.E = int(k), int(W), int(b), float(lr), int(E)
@@ -126,8 +131,10 @@ class OracleASGD:
             w0 = np.asarray(w0, dtype=np.float64)
             self.w = np.ascontiguousarray(np.broadcast_to(w0, (self.W, self.k, self.d))).copy()
         self.w = np.ascontiguousarray(self.w)
-        self.slot = np.zeros((self.W, self.k, self.d), dtype=np.float64)
-        self.slot_stamp = np.full(self.W, -1, dtype=np.int64)
+        self.buffers = int(buffers)
+        lead = () if self.buffers == 1 else (self.buffers,)
+        self.slot = np.zeros(lead + (self.W, self.k, self.d), dtype=np.float64)
+        self.slot_stamp = np.full(lead + (self.W,), -1, dtype=np.int64)
         self.ncum = np.zeros((self.W, self.k), dtype=np.int64)
         self.t = np.zeros(1, dtype=np.int64)
         self.counters = np.zeros((self.W, 3), dtype=np.int64)   # sent, received, accepted
@@ -138,9 +145,9 @@ class OracleASGD:
         a = np.empty((nsteps, self.W, self.b), dtype=np.int32) if dump else None
         g = np.empty((nsteps, self.W, self.b), dtype=np.float64) if dump else None
         rc = lib().asgd_oracle_steps(
-            self.X.ctypes.data, self.N, self.k, self.d, self.W, self.b, self.lr, self.E,
+            self.X.ctypes.data, self.N, self.k, self.d, self.W, self.b, self.lr, self.E, self.buffers,
             self.seed, int(self.parzen), self.lr_mode, self.drop_threshold, nsteps,
-            self.w.reshape(-1), self.slot.reshape(-1), self.slot_stamp, self.ncum.reshape(-1),
+            self.w.reshape(-1), self.slot.reshape(-1), self.slot_stamp.reshape(-1), self.ncum.reshape(-1),
             self.t, self.counters.reshape(-1), self.near,
             a.ctypes.data if dump else None, g.ctypes.data if dump else None)
         if rc != 0:

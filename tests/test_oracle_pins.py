@@ -42,17 +42,17 @@ def splitmix64_stream(seed, n):
     return out
 
 
-def py_peer(seed, r, i, W):
-    return (i + 1 + splitmix64_stream(seed, r + 1)[r] % (W - 1)) % W
+def py_peer(seed, r, i, W, n=0):
+    return (i + 1 + (splitmix64_stream(seed, r + 1)[r] % (W - 1) + n) % (W - 1)) % W
 
 
-def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True):
-    """Whole lockstep ASGD (Alg. 5 + Eq. 4 + Eq. 7) in NumPy, vectorised differently from the oracle."""
+def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1):
+    """Whole lockstep ASGD (Alg. 5 + Eq. 4 + Eq. 6/7) in NumPy, vectorised differently from the oracle."""
     N, d = X.shape
     H = N // W
     S = H // b
     w = np.stack([X[i * H:i * H + k] for i in range(W)]).astype(np.float64)
-    buf = [None] * W
+    buf = [[None] * buffers for _ in range(W)]
     stats = np.zeros((W, 3), dtype=np.int64)
     for t in range(steps):
         s = t % S
@@ -65,24 +65,28 @@ def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True):
             cnt = onehot.sum(0)
             G = (cnt[:, None] * w[i] - onehot.T @ M) / b
             step = G
-            if E > 0 and t > 0 and t % E == 0 and buf[i] is not None and np.linalg.norm(buf[i]) > 0:
-                we = buf[i]
-                stats[i, 1] += 1
-                ok = np.sum(((w[i] - lr * G) - we) ** 2) < np.sum((w[i] - we) ** 2)
-                if ok or not parzen:
-                    stats[i, 2] += 1
-                    step = (w[i] - 0.5 * (w[i] + we)) + G
+            if E > 0 and t > 0 and t % E == 0:
+                good = []
+                for we in buf[i]:
+                    if we is None or np.linalg.norm(we) == 0:
+                        continue
+                    stats[i, 1] += 1
+                    ok = np.sum(((w[i] - lr * G) - we) ** 2) < np.sum((w[i] - we) ** 2)
+                    if ok or not parzen:
+                        good.append(we)
+                if good:
+                    stats[i, 2] += len(good)
+                    step = (w[i] - np.mean(np.stack(good + [w[i]]), axis=0)) + G
             new[i] = w[i] - lr * step
         if E > 0 and t > 0 and t % E == 0:
-            buf = [None] * W
+            buf = [[None] * buffers for _ in range(W)]
         w = new
         if E > 0 and W > 1 and (t + 1) % E == 0:
             r = t // E
-            nxt = list(buf)
             for i in range(W):
                 stats[i, 0] += 1
-                nxt[py_peer(seed, r, i, W)] = w[i].copy()
-            buf = nxt
+                for n in range(buffers):
+                    buf[py_peer(seed, r, i, W, n)][n] = w[i].copy()
     return w, stats
 
 
@@ -284,15 +288,119 @@ def test_stale_or_empty_buffers_are_ignored(oracle):
     assert stale.counters[:, 1].sum() == 0 and zero.counters[:, 1].sum() == 0
 
 
+# ---------------------------------------------------------------- N external buffers (Eq. 3, Eq. 6)
+def _merge_case_n(oracle, cs, lr=0.2, parzen=True, present=None):
+    """Worker pair at a merge point with buffer n holding w - cs[n]*G (buffers not in `present` stay empty)."""
+    X = small_data(N=1200, d=3, k=4, seed=3)
+    k, W, b, E, nb = 4, len(cs) + 1, 40, 2, len(cs)
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, parzen=parzen, buffers=nb)
+    o.t[0] = E
+    w = o.w.copy()
+    G = np.zeros_like(w)
+    for i in range(W):
+        M = X[i * o.H + (E % o.S) * b:i * o.H + (E % o.S + 1) * b].astype(np.float64)
+        a, _ = brute_assign(M, w[i])
+        for c_ in range(k):
+            G[i, c_] = ((a == c_).sum() * w[i][c_] - M[a == c_].sum(0)) / b
+    slot = o.slot.reshape(nb, W, k, 3)
+    stamp = o.slot_stamp.reshape(nb, W)
+    for n, c in enumerate(cs):
+        if present is None or n in present:
+            slot[n] = w - c * G
+            stamp[n] = 0
+    o.run_steps(1)
+    return o, w, G
+
+
+@pytest.mark.parametrize("cs", [(0.5,), (0.5, 0.5), (0.5, 0.05), (3.0, 0.11, 0.7), (0.01, -1.0, 0.09), (0.3, 0.3, 0.3, 0.3)])
+def test_n_buffers_each_gated_on_its_own(oracle, cs):
+    """Buffer n at w - c_n G passes Eq. 4 iff c_n > eps/2, whatever the others hold; Eq. 6 then moves the state by
+    eps * (sum of the accepted c_n) / (D + 1) further along -G, D = number accepted."""
+    lr = 0.2
+    o, w, G = _merge_case_n(oracle, cs, lr=lr)
+    acc = [c for c in cs if c > lr / 2]
+    assert np.all(o.counters[:, 1] == len(cs)) and np.all(o.counters[:, 2] == len(acc))
+    expect = w - lr * G * (1.0 + sum(acc) / (len(acc) + 1.0))
+    assert np.allclose(o.w, expect, rtol=1e-12, atol=1e-13)
+    assert np.all(o.slot == 0) and np.all(o.slot_stamp == -1)
+
+
+def test_n_buffers_gate_off_counts_only_the_buffers_that_hold_a_message(oracle):
+    """Eq. 3: lambda = 0 for an empty buffer, so the mean runs over the local state and the non-empty ones."""
+    cs = (0.4, -2.0, 1.5)
+    o, w, G = _merge_case_n(oracle, cs, parzen=False, present=(0, 2))
+    assert np.all(o.counters[:, 1] == 2) and np.all(o.counters[:, 2] == 2)
+    assert np.allclose(o.w, w - 0.2 * G * (1.0 + (0.4 + 1.5) / 3.0), rtol=1e-12, atol=1e-13)
+    o, w, G = _merge_case_n(oracle, cs, parzen=False)
+    assert np.allclose(o.w, w - 0.2 * G * (1.0 + (0.4 - 2.0 + 1.5) / 4.0), rtol=1e-12, atol=1e-13)
+
+
+def test_n_buffers_zero_gradient_unit_step_is_the_plain_average(oracle):
+    """eps = 1, gate off, G = 0 (k = 1, every sample equals the centroid): the new state is the arithmetic mean of
+    the local state and the N external ones."""
+    x = np.array([1.5, -2.0, 0.25], dtype=np.float32)
+    X = np.tile(x, (600, 1))
+    nb, W = 3, 4
+    o = oracle.OracleASGD(X, k=1, W=W, b=10, lr=1.0, E=1, parzen=False, buffers=nb, w0=x[None, :].astype(np.float64))
+    o.t[0] = 1
+    rng = np.random.default_rng(5)
+    ext = rng.normal(size=(nb, W, 1, 3))
+    o.slot[:] = ext
+    o.slot_stamp[:] = 0
+    o.run_steps(1)
+    expect = (ext.sum(0) + x.astype(np.float64)) / (nb + 1)
+    assert np.allclose(o.w, expect, rtol=1e-14, atol=1e-15)
+    # the order of the buffers does not matter
+    o2 = oracle.OracleASGD(X, k=1, W=W, b=10, lr=1.0, E=1, parzen=False, buffers=nb, w0=x[None, :].astype(np.float64))
+    o2.t[0] = 1
+    o2.slot[:] = ext[::-1]
+    o2.slot_stamp[:] = 0
+    o2.run_steps(1)
+    assert np.allclose(o.w, o2.w, rtol=1e-14, atol=1e-15)
+
+
+def test_n_buffers_schedule(oracle):
+    """Copy n of a round's messages is a cyclic shift of its own: every worker gets exactly one message per buffer,
+    the N senders of a worker differ, nobody sends to itself; copy 0 is the one-buffer schedule."""
+    for W, nb in [(2, 1), (5, 4), (7, 3), (64, 4)]:
+        for r in range(40):
+            for n in range(nb):
+                rec = [oracle.peer(11, r, i, W, n) for i in range(W)]
+                assert sorted(rec) == list(range(W)) and all(rec[i] != i for i in range(W))
+                assert rec == [py_peer(11, r, i, W, n) for i in range(W)]
+            for i in range(W):
+                assert len({oracle.peer(11, r, i, W, n) for n in range(nb)}) == nb
+            assert [oracle.peer(11, r, i, W) for i in range(W)] == [oracle.peer(11, r, i, W, 0) for i in range(W)]
+    X = small_data(N=800)
+    with pytest.raises(ValueError):
+        oracle.OracleASGD(X, k=4, W=3, b=40, lr=0.2, E=2, buffers=3).run_steps(1)       # needs N < W
+
+
+def test_n_buffers_loss_hook_is_per_copy(oracle):
+    thr = oracle.drop_threshold(0.5)
+    lost = np.array([[oracle.dropped(9, r, s, thr, n) for n in range(4)] for r in range(50) for s in range(20)])
+    assert np.array_equal(lost[:, 0], np.array([oracle.dropped(9, r, s, thr) for r in range(50) for s in range(20)]))
+    frac = lost.mean(0)
+    assert np.all(np.abs(frac - 0.5) < 0.06)
+    assert np.abs(np.corrcoef(lost[:, 0], lost[:, 1])[0, 1]) < 0.1
+    X = small_data(N=2400)
+    o = oracle.OracleASGD(X, k=4, W=6, b=20, lr=0.2, E=2, buffers=3, drop_rate=0.5, seed=9)
+    o.run_steps(41)
+    rounds = 20
+    expected = sum(not oracle.dropped(9, r, s, thr, n) for r in range(rounds) for s in range(6) for n in range(3))
+    assert o.counters[:, 0].sum() == 6 * rounds and o.counters[:, 1].sum() == expected
+
+
 # ---------------------------------------------------------------- whole algorithm vs NumPy
-@pytest.mark.parametrize("W,E,parzen", [(4, 3, True), (3, 1, True), (5, 2, False)])
-def test_full_run_matches_independent_numpy_asgd(oracle, W, E, parzen):
+@pytest.mark.parametrize("W,E,parzen,buffers", [(4, 3, True, 1), (3, 1, True, 1), (5, 2, False, 1),
+                                                (5, 2, True, 2), (4, 1, True, 3), (6, 3, False, 4)])
+def test_full_run_matches_independent_numpy_asgd(oracle, W, E, parzen, buffers):
     X = small_data(N=3000, d=3, k=4, seed=5)
     k, b, lr, seed = 4, 30, 0.3, 42
-    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen)
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, buffers=buffers)
     steps = 2 * o.S + 5
     o.run_steps(steps)
-    ref_w, ref_stats = asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=parzen)
+    ref_w, ref_stats = asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=parzen, buffers=buffers)
     assert np.allclose(o.w, ref_w, rtol=1e-11, atol=1e-12)
     assert np.array_equal(o.counters, ref_stats)
     assert ref_stats[:, 2].sum() > 0                       # the merge path really ran
