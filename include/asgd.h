@@ -61,11 +61,23 @@ enum {
                                     ASGD_ESTATE (run up to a step that is not a multiple of E first). */
     ASGD_OPT_TUNE = 8,           /* launch-shape variant of the chosen kernel (0 = default); for
                                     performance experiments, never changes what is computed */
-    ASGD_OPT_COOPERATIVE = 9     /* 1 (default): a run that needs all its workgroups resident at the
+    ASGD_OPT_COOPERATIVE = 9,    /* 1 (default): a run that needs all its workgroups resident at the
                                     same time is started with a cooperative launch, which refuses
                                     grids that cannot be; 0: plain launch of the same grid (for tools
                                     that cannot follow cooperative launches).  The in-kernel waits are
                                     bounded either way. */
+    ASGD_OPT_BUFFERS = 10        /* N of Eq. 3 / Eq. 6: external buffers per worker, 1 (default) .. 4.  A
+                                    worker then sends every message to N different workers (copy n goes
+                                    into the recipient's buffer n; deterministic schedule: a cyclic shift
+                                    per round and copy, so every worker receives N messages per round from
+                                    N different senders) and merges, of the buffers that hold a message,
+                                    those that pass Eq. 4 on their own: w - (sum of them + w)/(their
+                                    number + 1) is added to the step.  With ASGD_OPT_PARZEN = 0 every
+                                    non-empty buffer takes part (Eq. 3).  Needs N < W at run time
+                                    (ASGD_EINVAL otherwise); may only be set before the first step
+                                    (ASGD_ESTATE after); reallocates the exchange buffers (2 * N * W states).
+                                    N > 1 is not available in the small-state kernel (ASGD_KERNEL_AUTO then
+                                    picks another one). */
 };
 enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
 enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };
@@ -179,8 +191,10 @@ int asgd_get_stats(asgd_ctx *ctx, asgd_stats *out);
 int asgd_get_worker_counters(asgd_ctx *ctx, int64_t *sent, int64_t *received, int64_t *accepted);
 
 /* Recipient of worker i's message of round r under the deterministic schedule
-   (host-side copy of what the kernels compute; W >= 2). */
+   (host-side copy of what the kernels compute; W >= 2); _n: of copy n of it, 0 <= n < W - 1
+   (ASGD_OPT_BUFFERS; copy 0 is the one-buffer schedule).  -1 on invalid arguments. */
 int64_t asgd_schedule_peer(uint64_t seed, int64_t r, int64_t i, int64_t W);
+int64_t asgd_schedule_peer_n(uint64_t seed, int64_t r, int64_t i, int64_t W, int64_t n);
 
 /* hipError_t of the last failed HIP call of this context (0 if none). */
 int asgd_last_hip_error(asgd_ctx *ctx);

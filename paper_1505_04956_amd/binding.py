@@ -14,7 +14,7 @@ import numpy as np
 from . import build as _build
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, ESYNC = 0, -1, -2, -3, -4, -5
-OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE = range(1, 10)
+OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE, OPT_BUFFERS = range(1, 11)
 MODE_DETERMINISTIC, MODE_FREE_RUNNING = 0, 1
 LR_CONST, LR_INV_COUNT = 0, 1
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_SMALL, KERNEL_MFMA = 0, 1, 2, 3
@@ -24,7 +24,7 @@ SYMBOLS = (
     "asgd_create", "asgd_set_option", "asgd_load_shards", "asgd_set_state", "asgd_set_step",
     "asgd_run_epochs", "asgd_run_steps", "asgd_set_assign_dump", "asgd_get_state",
     "asgd_get_mean_state", "asgd_quant_error", "asgd_last_run_ms", "asgd_get_stats", "asgd_get_worker_counters",
-    "asgd_schedule_peer", "asgd_last_hip_error", "asgd_destroy", "asgd_strerror",
+    "asgd_schedule_peer", "asgd_schedule_peer_n", "asgd_last_hip_error", "asgd_destroy", "asgd_strerror",
 )
 
 
@@ -68,6 +68,7 @@ def lib():
             "asgd_get_stats": (C.c_int, [vp, C.POINTER(asgd_stats)]),
             "asgd_get_worker_counters": (C.c_int, [vp, vp, vp, vp]),
             "asgd_schedule_peer": (i64, [u64, i64, i64, i64]),
+            "asgd_schedule_peer_n": (i64, [u64, i64, i64, i64, i64]),
             "asgd_last_hip_error": (C.c_int, [vp]),
             "asgd_destroy": (None, [vp]),
             "asgd_strerror": (C.c_char_p, [C.c_int]),
@@ -162,6 +163,10 @@ def asgd_schedule_peer(seed, r, i, W) -> int:
     return int(lib().asgd_schedule_peer(seed, r, i, W))
 
 
+def asgd_schedule_peer_n(seed, r, i, W, n) -> int:
+    return int(lib().asgd_schedule_peer_n(seed, r, i, W, n))
+
+
 def asgd_destroy(h):
     lib().asgd_destroy(h)
 
@@ -169,13 +174,13 @@ def asgd_destroy(h):
 # ---- convenience wrapper: owns a handle, keeps the borrowed tensors alive -----------------
 class ASGD:
     def __init__(self, k, d, W, b, lr, E=0, seed=1, mode=MODE_DETERMINISTIC, parzen=True,
-                 lr_mode=LR_CONST, drop_rate=0.0, kernel=KERNEL_AUTO, tune=0, cooperative=True):
+                 lr_mode=LR_CONST, drop_rate=0.0, kernel=KERNEL_AUTO, tune=0, cooperative=True, buffers=1):
         self.k, self.d, self.W, self.b = k, d, W, b
         self.h = asgd_create(k, d, W, b, lr)
         for key, val in ((OPT_EXCHANGE_EVERY, E), (OPT_SEED, seed), (OPT_MODE, mode),
                          (OPT_PARZEN, int(parzen)), (OPT_LR_MODE, lr_mode),
                          (OPT_DROP_RATE, drop_rate), (OPT_KERNEL, kernel), (OPT_TUNE, tune),
-                         (OPT_COOPERATIVE, int(cooperative))):
+                         (OPT_COOPERATIVE, int(cooperative)), (OPT_BUFFERS, buffers)):
             asgd_set_option(self.h, key, val)
         self._x = None
         self._dump = None

@@ -20,6 +20,8 @@ struct asgd_ctx {
     double drop_rate = 0.0;
     int kernel_opt = ASGD_KERNEL_AUTO;
     int tune = 0;
+    int nb = 1;                 // external buffers per worker
+    size_t slot_bytes_one = 0;  // bytes of both parities of ONE buffer per worker
     int cooperative = 1;
 
     int device = 0;
@@ -78,7 +80,7 @@ StepParams make_params(const asgd_ctx *c)
     p.counters = c->counters; p.acc = c->acc; p.cnt = c->cnt; p.assign_tmp = c->assign_tmp;
     p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->error_flag;
     p.H = c->H; p.S = c->S; p.t_dump0 = c->t; p.seed = c->seed;
-    p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr;
+    p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr; p.nb = c->nb;
     p.parzen = c->parzen; p.lr_mode = c->lr_mode; p.mode = c->mode;
     p.drop_thr = (uint32_t)llround(c->drop_rate * (double)(1u << 24));
     p.tune = c->tune;
@@ -91,7 +93,7 @@ int clear_exchange(asgd_ctx *c)
     // all bits set: empty in both message formats (stamp -1 inside the small-state kernel's pairs; the other
     // kernels look at `stamp` before they read a buffer)
     HIP_TRY(c, hipMemsetAsync(c->slot, 0xFF, c->slot_bytes, c->stream));
-    HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->W * sizeof(int), c->stream));   // -1
+    HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->nb * c->W * sizeof(int), c->stream));   // -1
     return ASGD_OK;
 }
 
@@ -110,6 +112,12 @@ const char *asgd_strerror(int code)
         case ASGD_ESYNC: return "bounded wait inside a kernel expired";
         default: return "unknown error code";
     }
+}
+
+int64_t asgd_schedule_peer_n(uint64_t seed, int64_t r, int64_t i, int64_t W, int64_t n)
+{
+    if (W < 2 || W > 0x7fffffff || i < 0 || i >= W || r < 0 || n < 0 || n >= W - 1) return -1;
+    return peer_deterministic(seed, r, (int)i, (int)W, (int)n);
 }
 
 int64_t asgd_schedule_peer(uint64_t seed, int64_t r, int64_t i, int64_t W)
@@ -135,7 +143,8 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
     const size_t kd = kd_of(c), Wz = (size_t)W;
     {
         const size_t plain = kd * sizeof(float), own = small_kernel_message_bytes(k, d);
-        c->slot_bytes = 2 * Wz * (plain > own ? plain : own);
+        c->slot_bytes_one = 2 * Wz * (plain > own ? plain : own);
+        c->slot_bytes = c->slot_bytes_one;
     }
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&c->w, Wz * kd * sizeof(float)},
@@ -216,6 +225,29 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
             if (value != 0 && value != 1) return ASGD_EINVAL;
             ctx->cooperative = (int)value;
             return ASGD_OK;
+        case ASGD_OPT_BUFFERS: {
+            if (value < 1 || value > MAX_BUFFERS || value != floor(value)) return ASGD_EINVAL;
+            if (ctx->t != 0) return ASGD_ESTATE;
+            const int nb = (int)value;
+            if (nb == ctx->nb) return ASGD_OK;
+            HIP_TRY(ctx, hipSetDevice(ctx->device));
+            HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+            float *slot = nullptr;
+            int *stamp = nullptr;
+            hipError_t e = hipMalloc((void **)&slot, (size_t)nb * ctx->slot_bytes_one);
+            if (e == hipSuccess) e = hipMalloc((void **)&stamp, 2 * (size_t)nb * ctx->W * sizeof(int));
+            if (e != hipSuccess) {
+                if (slot) (void)hipFree(slot);
+                HIP_TRY(ctx, e);
+            }
+            (void)hipFree(ctx->slot);
+            (void)hipFree(ctx->stamp);
+            ctx->slot = slot;
+            ctx->stamp = stamp;
+            ctx->slot_bytes = (size_t)nb * ctx->slot_bytes_one;
+            ctx->nb = nb;
+            return clear_exchange(ctx);
+        }
         case ASGD_OPT_TUNE:
             if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
             ctx->tune = (int)value;
@@ -299,7 +331,8 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     HIP_TRY(ctx, hipSetDevice(ctx->device));
 
     int kernel = ctx->kernel_opt;
-    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST;
+    if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
+    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->nb == 1;
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
     if (kernel == ASGD_KERNEL_AUTO) {
         // the matrix-core kernel pays off once the k x d contraction dominates a step

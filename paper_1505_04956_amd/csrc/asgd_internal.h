@@ -21,26 +21,33 @@ __host__ __device__ inline uint64_t round_hash(uint64_t seed, int64_t r)
 {
     return mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(r + 1));
 }
-// Deterministic schedule: one cyclic shift per round, shared by all senders, so that every
-// worker receives exactly one message per round (Alg. 5 line 9 asks only for "a random node
-// other than i").
-__host__ __device__ inline int peer_deterministic(uint64_t seed, int64_t r, int i, int W)
+// Deterministic schedule: one cyclic shift per round and copy, shared by all senders, so that every
+// worker receives exactly one message per round in each of its buffers (Alg. 5 line 9 asks only for
+// "a random node other than i").  Copy n of a message (0 <= n < number of buffers < W) goes into the
+// recipient's buffer n; the shifts of one round differ, so a worker's senders differ.
+__host__ __device__ inline int shift_deterministic(uint64_t seed, int64_t r, int W, int n = 0)
 {
-    uint64_t shift = 1 + round_hash(seed, r) % (uint64_t)(W - 1);
-    return (int)(((uint64_t)i + shift) % (uint64_t)W);
+    return (int)(1 + (round_hash(seed, r) % (uint64_t)(W - 1) + (uint64_t)n) % (uint64_t)(W - 1));
 }
-// Free-running schedule: every sender draws its own recipient; collisions are the data race
-// of Fig. 2 (III) and are allowed.
-__host__ __device__ inline int peer_free(uint64_t seed, int64_t r, int i, int W)
+__host__ __device__ inline int peer_deterministic(uint64_t seed, int64_t r, int i, int W, int n = 0)
 {
-    uint64_t h = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(i + 1) + 0x5851F42D4C957F2DULL);
+    return (int)(((uint64_t)i + (uint64_t)shift_deterministic(seed, r, W, n)) % (uint64_t)W);
+}
+// Free-running schedule: every sender draws its own recipients; collisions are the data race
+// of Fig. 2 (III) and are allowed.
+__host__ __device__ inline int peer_free(uint64_t seed, int64_t r, int i, int W, int n = 0)
+{
+    uint64_t h = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(i + 1) + 0x5851F42D4C957F2DULL +
+                       0xD1B54A32D192ED03ULL * (uint64_t)n);
     return (int)(((uint64_t)i + 1 + h % (uint64_t)(W - 1)) % (uint64_t)W);
 }
-__host__ __device__ inline bool message_dropped(uint64_t seed, int64_t r, int sender, uint32_t thr)
+__host__ __device__ inline bool message_dropped(uint64_t seed, int64_t r, int sender, uint32_t thr, int n = 0)
 {
-    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1)) >> 40;
+    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1) +
+                       0xD1B54A32D192ED03ULL * (uint64_t)n) >> 40;
     return u < (uint64_t)thr;
 }
+enum { MAX_BUFFERS = 4 };   // external buffers per worker (Eq. 3)
 
 // Per-worker counters kept in device memory.
 enum { CNT_SENT = 0, CNT_RECEIVED = 1, CNT_ACCEPTED = 2, CNT_PARZEN_NEAR = 3, CNT_RECHECK = 4, CNT_STRIDE = 8 };
@@ -49,8 +56,8 @@ enum { CNT_SENT = 0, CNT_RECEIVED = 1, CNT_ACCEPTED = 2, CNT_PARZEN_NEAR = 3, CN
 struct StepParams {
     const float *x;        // N x d samples
     float *w;              // W x k x d states
-    float *slot;           // 2 x W exchange buffers (parity, worker): k x d floats, or the small-state kernel's pairs
-    int *stamp;            // 2 x W round number of the buffered message, -1 = empty
+    float *slot;           // 2 x nb x W exchange buffers (parity, buffer, worker): k x d floats, or the small-state kernel's pairs
+    int *stamp;            // 2 x nb x W round number of the buffered message, -1 = empty
     int *consumed;         // W: last round whose merge point the worker has passed
     long long *ncum;       // W x k cumulative counts (1/count step size only)
     long long *counters;   // W x CNT_STRIDE
@@ -66,6 +73,7 @@ struct StepParams {
     long long t_dump0;     // step counter value at which the dump buffer starts
     uint64_t seed;
     int k, d, W, b, E;
+    int nb;                // external buffers per worker = recipients per message (Eq. 3), 1 .. MAX_BUFFERS
     float eps;
     int parzen, lr_mode, mode;
     uint32_t drop_thr;

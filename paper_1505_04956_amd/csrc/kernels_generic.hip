@@ -197,35 +197,39 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
         const int rpar = det ? (int)((r_now - 1) & 1) : 0;
         if (tid == 0) {
-            int has = 0;
-            if (merge_point) {
-                const int st = p.stamp[(size_t)rpar * p.W + i];
-                has = det ? (st == (int)(r_now - 1)) : (st >= 0);
-                p.stamp[(size_t)rpar * p.W + i] = -1;
+            int has = 0;                       // bit n: buffer n holds a message for this merge point
+            for (int n = 0; merge_point && n < p.nb; ++n) {
+                int *stp = p.stamp + ((size_t)(rpar * p.nb + n) * p.W + i);
+                const int st = *stp;
+                if (det ? (st == (int)(r_now - 1)) : (st >= 0)) has |= 1 << n;
+                *stp = -1;
             }
             s_has_ext = has;
         }
         __syncthreads();
-        const float *ext = p.slot + ((size_t)rpar * p.W + i) * kd;
-        int delta = 0;
+        const int has_mask = s_has_ext;        // uniform over the block
+        const float *ext[MAX_BUFFERS];
+        for (int n = 0; n < MAX_BUFFERS; ++n) ext[n] = p.slot + ((size_t)(rpar * p.nb + (n < p.nb ? n : 0)) * p.W + i) * kd;
         // descent gradient of Eq. 9, G = (c_k * w_k - S_k) / b, stored over the sums
-        double lhs = 0.0, rhs = 0.0, nrm = 0.0;
-        const bool has_ext = s_has_ext != 0;
         for (size_t e = tid; e < kd; e += GEN_THREADS) {
             const int c = (int)(e / d);
-            const float g = ((float)cntp[c] * wp[e] - sp[e]) / (float)b;
-            sp[e] = g;
-            if (has_ext) {
-                const double we = (double)ext[e];
-                const double a = ((double)wp[e] - (double)p.eps * (double)g) - we;
+            sp[e] = ((float)cntp[c] * wp[e] - sp[e]) / (float)b;
+        }
+        int delta_mask = 0, ndelta = 0;
+        for (int n = 0; n < p.nb; ++n) {
+            if (!(has_mask >> n & 1)) continue;
+            double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+            for (size_t e = tid; e < kd; e += GEN_THREADS) {
+                const double we = (double)ext[n][e];
+                const double a = ((double)wp[e] - (double)p.eps * (double)sp[e]) - we;
                 const double c2 = (double)wp[e] - we;
                 lhs += a * a; rhs += c2 * c2; nrm += we * we;
             }
-        }
-        if (has_ext) {   // uniform over the block
             block_sum3(lhs, rhs, nrm, red);
             if (nrm > 0.0) {                      // lambda of Eq. 3: an all-zero buffer is empty
-                delta = p.parzen ? (lhs < rhs) : 1;   // Eq. 4
+                const int delta = p.parzen ? (lhs < rhs) : 1;   // Eq. 4, every buffer on its own (Eq. 6)
+                delta_mask |= delta << n;
+                ndelta += delta;
                 if (tid == 0) {
                     long long *cn = p.counters + (size_t)i * CNT_STRIDE;
                     cn[CNT_RECEIVED] += 1;
@@ -234,11 +238,16 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 }
             }
         }
-        // Eq. 7 and Alg. 5 line 8
+        // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
+        const float inv = 1.0f / (float)(ndelta + 1);
         for (size_t e = tid; e < kd; e += GEN_THREADS) {
             float step = sp[e];
-            const float we = delta ? ext[e] : 0.0f;
-            if (delta) step += wp[e] - 0.5f * (wp[e] + we);
+            if (ndelta) {
+                float sum = wp[e];
+                for (int n = 0; n < p.nb; ++n)
+                    if (delta_mask >> n & 1) sum += ext[n][e];
+                step += wp[e] - inv * sum;
+            }
             wp[e] = wp[e] - p.eps * step;
         }
         __syncthreads();
@@ -246,14 +255,15 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         // ---- send (Alg. 5 line 9) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
             const long long r = t / p.E;
-            if (!message_dropped(p.seed, r, i, p.drop_thr)) {
-                const int peer = det ? peer_deterministic(p.seed, r, i, p.W) : peer_free(p.seed, r, i, p.W);
+            for (int n = 0; n < p.nb; ++n) {
+                if (message_dropped(p.seed, r, i, p.drop_thr, n)) continue;
+                const int peer = det ? peer_deterministic(p.seed, r, i, p.W, n) : peer_free(p.seed, r, i, p.W, n);
                 const int spar = det ? (int)(r & 1) : 0;
-                float *dst = p.slot + ((size_t)spar * p.W + peer) * kd;
+                float *dst = p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd;
                 for (size_t e = tid; e < kd; e += GEN_THREADS) dst[e] = wp[e];
                 __threadfence();
                 __syncthreads();
-                if (tid == 0) p.stamp[(size_t)spar * p.W + peer] = (int)r;
+                if (tid == 0) p.stamp[(size_t)(spar * p.nb + n) * p.W + peer] = (int)r;
             }
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }

@@ -606,21 +606,20 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const long long r_now = p.E > 0 ? t / p.E : 0;
         const int rpar = det ? (int)((r_now - 1) & 1) : 0;
         if (tid == MF_THREADS - 1) {
-            int has = 0;
-            if (merge_point) {
-                int *stp = p.stamp + (size_t)rpar * p.W + i;
+            int has = 0;                       // bit n: buffer n holds a message for this merge point
+            for (int n = 0; merge_point && n < p.nb; ++n) {
+                int *stp = p.stamp + (size_t)(rpar * p.nb + n) * p.W + i;
                 if (det) {
                     // stamps of one buffer only grow, so the test for the round needs no clearing
                     if (sync) {
                         const long long rs = r_now - 1;
-                        const int shift = (int)(1 + round_hash(p.seed, rs) % (uint64_t)(p.W - 1));
-                        const int sender = (i - shift + p.W) % p.W;
-                        if (!message_dropped(p.seed, rs, sender, p.drop_thr) && !mf_wait_flag(stp, (int)rs, false))
+                        const int sender = (i - shift_deterministic(p.seed, rs, p.W, n) + p.W) % p.W;
+                        if (!message_dropped(p.seed, rs, sender, p.drop_thr, n) && !mf_wait_flag(stp, (int)rs, false))
                             atomicOr(p.error_flag, 1);
                     }
-                    has = __hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)(r_now - 1);
+                    if (__hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)(r_now - 1)) has |= 1 << n;
                 } else {
-                    has = *stp >= 0;
+                    if (*stp >= 0) has |= 1 << n;
                     *stp = -1;
                 }
             }
@@ -742,11 +741,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __threadfence_block();
         __syncthreads();
 
-        const bool has_ext = s_has_ext != 0;
-        const float *ext = p.slot + ((size_t)rpar * p.W + i) * kd;
-        // ---- Parzen sums (Eq. 4) over the whole state, fp64 ----
-        int delta = 0;
-        if (has_ext) {       // uniform over the workgroup
+        const int has_mask = s_has_ext;      // uniform over the workgroup
+        const float *ext0 = p.slot + ((size_t)(rpar * p.nb) * p.W + i) * kd;          // buffer n: + n * W * kd
+        const size_t ext_stride = (size_t)p.W * kd;
+        // ---- Parzen sums (Eq. 4) over the whole state, fp64, every buffer on its own (Eq. 6) ----
+        int delta_mask = 0;
+        for (int n = 0; n < p.nb; ++n) {
+            if (!(has_mask >> n & 1)) continue;
+            const float *ext = ext0 + n * ext_stride;
             double lhs = 0.0, rhs = 0.0, nrm = 0.0;
             for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
                 float w[RB][NJ], sm[RB][NJ], we[RB][NJ];
@@ -786,7 +788,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
             for (int v = 0; v < MF_WAVES; ++v) { lhs += red_d[0][v]; rhs += red_d[1][v]; nrm += red_d[2][v]; }
             if (nrm > 0.0) {                          // lambda of Eq. 3
-                delta = p.parzen ? (lhs < rhs) : 1;   // Eq. 4
+                const int delta = p.parzen ? (lhs < rhs) : 1;   // Eq. 4
+                delta_mask |= delta << n;
                 if (tid == 0) {
                     long long *cn = p.counters + (size_t)i * CNT_STRIDE;
                     cn[CNT_RECEIVED] += 1;
@@ -794,10 +797,15 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) cn[CNT_PARZEN_NEAR] += 1;
                 }
             }
+            __syncthreads();                          // red_d is written again for the next buffer
         }
-        // ---- update: Eq. 7, Alg. 5 line 8; new offsets h_c and max |w_c|^2 ----
+        // ---- update: Eq. 6 (one buffer: Eq. 7), Alg. 5 line 8; new offsets h_c and max |w_c|^2 ----
         {
-            const float *extp = delta ? ext : wst;        // read something valid when there is nothing to merge
+            const int delta = delta_mask != 0;
+            const int first = delta ? __builtin_ctz(delta_mask) : 0;
+            const int more_mask = delta_mask & (delta_mask - 1);             // accepted buffers after the first
+            const float inv = 1.0f / (float)(__builtin_popcount(delta_mask) + 1);
+            const float *extp = delta ? ext0 + first * ext_stride : wst;    // read something valid when there is nothing to merge
             wn2max = 0.0f;
             for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
                 float w[RB][NJ], sm[RB][NJ], we[RB][NJ], s2[RB];
@@ -812,6 +820,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         const int j = lane + 64 * jq;
                         const size_t e = (size_t)c * d + (j < d ? j : 0);
                         w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = extp[e];
+                        for (int m = more_mask; m; m &= m - 1) we[q][jq] += ext0[__builtin_ctz(m) * ext_stride + e];
                     }
                 }
 #pragma unroll
@@ -823,7 +832,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         if (c0 + q < k && j < d) {
                             const float sums = cn[q] > 0 ? sm[q][jq] : 0.0f;
                             float step = ((float)cn[q] * w[q][jq] - sums) / (float)b;
-                            if (delta) step += w[q][jq] - 0.5f * (w[q][jq] + we[q][jq]);
+                            if (delta) step += w[q][jq] - inv * (w[q][jq] + we[q][jq]);
                             const float wn = w[q][jq] - p.eps * step;
                             wst[(size_t)(c0 + q) * d + j] = wn;
                             s2[q] = fmaf(wn, wn, s2[q]);
@@ -852,20 +861,21 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         // ---- send (Alg. 5 line 9) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
             const long long r = t / p.E;
-            if (!message_dropped(p.seed, r, i, p.drop_thr)) {
-                const int peer = det ? peer_deterministic(p.seed, r, i, p.W) : peer_free(p.seed, r, i, p.W);
+            for (int n = 0; n < p.nb; ++n) {
+                if (message_dropped(p.seed, r, i, p.drop_thr, n)) continue;
+                const int peer = det ? peer_deterministic(p.seed, r, i, p.W, n) : peer_free(p.seed, r, i, p.W, n);
                 const int spar = det ? (int)(r & 1) : 0;
                 if (sync && r >= 2) {
                     // the buffer still holds the message of round r - 2 until the peer has passed merge point r - 1
                     if (tid == 0 && !mf_wait_flag(p.consumed + peer, (int)(r - 1), true)) atomicOr(p.error_flag, 1);
                     __syncthreads();
                 }
-                float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)spar * p.W + peer) * kd);
+                float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd);
                 const float4 *src = reinterpret_cast<const float4 *>(wst);
                 for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
                 __threadfence();
                 __syncthreads();
-                if (tid == 0) __hip_atomic_store(p.stamp + (size_t)spar * p.W + peer, (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0) __hip_atomic_store(p.stamp + (size_t)(spar * p.nb + n) * p.W + peer, (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }

@@ -50,6 +50,9 @@ def test_schedule_agrees_with_oracle(oracle):
             for r in (0, 1, 77):
                 for i in (0, W // 2, W - 1):
                     assert binding.asgd_schedule_peer(seed, r, i, W) == oracle.peer(seed, r, i, W)
+                    for n in range(min(4, W - 1)):
+                        assert binding.asgd_schedule_peer_n(seed, r, i, W, n) == oracle.peer(seed, r, i, W, n)
+    assert binding.asgd_schedule_peer_n(1, 0, 0, 4, 3) == -1 and binding.asgd_schedule_peer_n(1, 0, 0, 4, -1) == -1
 
 
 def test_argument_checks_need_no_gpu():

@@ -43,14 +43,14 @@ def make_data(N, d, k, seed=3, centres="uniform10", weights="equal", sigma=1.0):
 
 
 def run_both(B, oracle, X, k, W, b, lr, E, steps, seed=1, parzen=True, drop_rate=0.0, lr_mode=0,
-             kernel=0, tune=0, dump=True, w0=None, check_qe=True):
+             kernel=0, tune=0, dump=True, w0=None, check_qe=True, buffers=1):
     """Run `steps` steps on the GPU and in the oracle; assert the bars; return both."""
     N, d = X.shape
     g = B.ASGD(k, d, W, b, lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate, lr_mode=lr_mode,
-               kernel=kernel, tune=tune)
+               kernel=kernel, tune=tune, buffers=buffers)
     g.load_shards(to_dev(X))
     o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate,
-                          lr_mode=lr_mode, w0=w0)
+                          lr_mode=lr_mode, w0=w0, buffers=buffers)
     if w0 is not None:
         g.set_state(-1, np.asarray(w0, dtype=np.float32))
     if dump:
@@ -258,6 +258,56 @@ def test_matrix_core_kernel_one_launch(B, oracle, tune):
         parts = B.ASGD(40, 20, 12, 100, 0.05, E=2, drop_rate=drop, kernel=3, tune=tune)
         parts.load_shards(Xg); parts.run_steps(5); parts.run_steps(1); parts.run_steps(11)
         assert np.array_equal(g.get_state(), parts.get_state())
+
+
+@pytest.mark.parametrize("kernel,tune,k,d,W,b,E,steps,buffers,parzen,drop", [
+    (1, 0, 10, 10, 6, 100, 2, 13, 2, True, 0.0),        # the small-state shape falls to the generic kernel
+    (1, 0, 7, 5, 5, 64, 1, 9, 4, True, 0.3),
+    (1, 0, 12, 9, 6, 50, 3, 14, 3, False, 0.0),
+    (3, 2, 40, 20, 12, 100, 2, 17, 2, True, 0.0),       # four waves, one launch
+    (3, 2, 40, 20, 12, 100, 2, 17, 4, True, 0.4),
+    (3, 6, 40, 20, 12, 100, 2, 17, 3, False, 0.0),      # four waves, one launch per round
+    (3, 8, 40, 20, 12, 100, 3, 17, 3, True, 0.2),       # eight waves, one launch
+    (3, 0, 70, 36, 5, 300, 2, 9, 4, True, 0.0),         # eight waves, one launch per round
+])
+def test_n_external_buffers(B, oracle, kernel, tune, k, d, W, b, E, steps, buffers, parzen, drop):
+    """Eq. 3 / Eq. 6: N buffers per worker, N recipients per message."""
+    X = make_data(W * (steps + 1) * b + 7, d, k, seed=31)
+    g, o = run_both(B, oracle, X, k, W, b, 0.05, E, steps, kernel=kernel, tune=tune, buffers=buffers, parzen=parzen,
+                    drop_rate=drop)
+    assert g.stats().kernel == kernel
+    assert o.counters[:, 1].sum() > W                          # several buffers were looked at per merge point
+    if parzen and drop == 0.0:
+        assert 0 < o.counters[:, 2].sum()
+
+
+def test_n_external_buffers_options(B, oracle):
+    X = make_data(6 * 1500, 10, 10, seed=33)
+    Xg = to_dev(X)
+    auto = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=2); auto.load_shards(Xg); auto.run_steps(5)
+    assert auto.stats().kernel == B.KERNEL_GENERIC              # the small-state kernel has one buffer
+    with pytest.raises(B.AsgdError):
+        auto.set_option(B.OPT_BUFFERS, 3)                       # not after the first step
+    with pytest.raises(B.AsgdError):
+        small = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=2, kernel=B.KERNEL_SMALL); small.load_shards(Xg); small.run_steps(1)
+    with pytest.raises(B.AsgdError):
+        many = B.ASGD(10, 10, 3, 100, 0.05, E=2, buffers=3); many.load_shards(Xg); many.run_steps(1)   # needs N < W
+    with pytest.raises(B.AsgdError):
+        B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=5)
+    # one buffer set explicitly is the default; same run twice with three buffers: bit for bit
+    a = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=1); a.load_shards(Xg); a.run_steps(9)
+    c = B.ASGD(10, 10, 6, 100, 0.05, E=2); c.load_shards(Xg); c.run_steps(9)
+    assert a.stats().kernel == B.KERNEL_SMALL and np.array_equal(a.get_state(), c.get_state())
+    e = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3); e.load_shards(Xg); e.run_steps(9)
+    f = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3); f.load_shards(Xg); f.run_steps(4); f.run_steps(5)
+    assert np.array_equal(e.get_state(), f.get_state())
+    assert e.stats().sent == 6 * 4 and e.stats().received == 6 * 4 * 3
+    # free-running mode: no element-wise parity; finite, every worker sends, some messages arrive
+    fr = B.ASGD(40, 20, 12, 100, 0.05, E=2, buffers=3, mode=B.MODE_FREE_RUNNING, kernel=3)
+    Xm = to_dev(make_data(12 * 1500, 20, 40, seed=34))
+    fr.load_shards(Xm); fr.run_steps(15)
+    st = fr.stats()
+    assert np.all(np.isfinite(fr.get_state())) and st.sent == 12 * 7 and 0 < st.received <= 3 * st.sent
 
 
 def test_stored_values_of_tiny_workload(B):
