@@ -22,6 +22,7 @@
  *   send of the new state to one other worker ............... Alg. 5 line 9, Fig. 2 stage I
  *   empty external buffer <=> zero norm ..................... Eq. 3 (lambda)
  *   merge of N external buffers, each gated on its own ...... Eq. 3 (no gate), Eq. 6 (gated)
+ *   partial messages, partitioned along the cluster centres . Sec. 4.4 (data races and sparsity)
  *   quantization error E(w) ................................. Eq. 8
  *
  * Readings taken where the paper is silent or inconsistent (each is listed with its
@@ -44,7 +45,15 @@
  *     at n = 0, which would count the local state twice and would not give Eq. 2 for N = 1);
  *     with the gate switched off every non-empty buffer takes part (Eq. 3), with the gate
  *     on every buffer is tested by Eq. 4 against the same projected local step (Eq. 6);
- *   - Eq. 4 uses whole-state norms and a strict "<".
+ *   - Eq. 4 uses whole-state norms and a strict "<";
+ *   - partial messages (P parts, P = 1: whole states, the default): Sec. 4.4 partitions "along the
+ *     individual cluster centers" and leaves the rest open.  Here part q is the set of centroid
+ *     rows c with c mod P = q; copy n of the message of round r to recipient p carries part
+ *     (r + p + n) mod P of the sender's state, so the recipient knows the part without knowing the
+ *     sender and sees every part once in P rounds.  The parts of Eq. 3/4/6 are then the rows: a
+ *     transmitted row is empty iff it is all zero (lambda), is tested by Eq. 4 over that row alone,
+ *     and the accepted rows of all buffers enter Eq. 6 row by row; rows that were not transmitted
+ *     take the plain step.
  *
  * Parity status: every function here is pinned by tests/test_oracle_pins.py.
  */
@@ -159,10 +168,13 @@ double asgd_oracle_quant_error(const float *X, int64_t n, int d, int k, const do
    w:       k*d state at the start of the step (read only)
    wnew:    k*d state after the step
    ext:     the next non-empty external buffers of this merge point (next = 0: nothing to merge)
-   returns the number of buffers accepted by Eq. 4 (or merged without the gate) in bits 0-7,
+   parts:   P; extpart[n] = which part buffer n carries (P = 1: the whole state, gated as a whole)
+   returns the number of buffers accepted by Eq. 4 (or merged without the gate; P > 1: with at
+           least one accepted row) in bits 0-7,
            bit 8 = a Parzen near-tie (|lhs-rhs|/rhs < 1e-6) in one of them                  */
 static int worker_step(const float *M, int b, int k, int d, double eps, int lr_mode, int parzen,
-                       const double *w, double *wnew, const double *const *ext, int next, int64_t *ncum,
+                       const double *w, double *wnew, const double *const *ext, int next, int parts,
+                       const int *extpart, int64_t *ncum,
                        int32_t *assign_out, double *gap_out, int64_t *argmin_near)
 {
     const size_t kd = (size_t)k * d;
@@ -206,6 +218,44 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
             }
         int delta[256];
         int ndelta = 0;
+        if (parts > 1) {
+            /* Sec. 4.4: the units of Eq. 3/4/6 are the transmitted centroid rows. */
+            for (int n = 0; n < next; ++n) delta[n] = 0;
+            for (int c = 0; c < k; ++c) {
+                int nacc = 0;
+                int accn[256];
+                for (int n = 0; n < next; ++n) {
+                    if (c % parts != extpart[n]) continue;
+                    const double *er = ext[n] + (size_t)c * d;
+                    double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+                    for (int j = 0; j < d; ++j) {
+                        size_t e = (size_t)c * d + j;
+                        double a = (w[e] - eps * G[e]) - er[j];
+                        double c2 = w[e] - er[j];
+                        lhs += a * a; rhs += c2 * c2; nrm += er[j] * er[j];
+                    }
+                    if (!(nrm > 0.0)) continue;                 /* lambda: an all-zero row is empty */
+                    if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) flags |= 256;
+                    if (parzen ? (lhs < rhs) : 1) { accn[nacc++] = n; delta[n] = 1; }
+                }
+                for (int j = 0; j < d; ++j) {
+                    size_t e = (size_t)c * d + j;
+                    double Gbar = G[e];
+                    if (nacc > 0) {
+                        double s2 = w[e];
+                        for (int q = 0; q < nacc; ++q) s2 += ext[accn[q]][e];
+                        Gbar += w[e] - s2 / (double)(nacc + 1);
+                    }
+                    wnew[e] = w[e] - eps * Gbar;
+                }
+            }
+            for (int n = 0; n < next; ++n) ndelta += delta[n];
+            flags |= ndelta;
+            free(cnt);
+            free(Ssum);
+            free(G);
+            return flags;
+        }
         for (int n = 0; n < next; ++n) {
             /* Eq. 4: compare the projected local step with the current state, both
                measured from the external state. */
@@ -245,6 +295,7 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
  * X           N x d fp32 row-major; shard i = rows [i*H, (i+1)*H), H = floor(N/W)
  * w           W*k*d fp64 states, in/out
  * nb          external buffers per worker = recipients per message (1 <= nb <= 255, nb < W or W == 1)
+ * parts       P of the partial messages (1 = whole states; 1 <= P <= k)
  * slot        nb*W*k*d fp64 external buffers, buffer n of worker i at (n*W + i)*k*d, in/out
  *             (all-zero = empty, Eq. 3)
  * slot_stamp  nb*W round numbers of the buffered messages (-1 = none), in/out
@@ -257,7 +308,7 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
  * lr_mode     0 = constant eps, 1 = per-centroid 1/count (requires E == 0)
  * returns 0, or -1 on invalid arguments
  */
-int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, double eps, int E, int nb,
+int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, double eps, int E, int nb, int parts,
                       uint64_t seed, int parzen, int lr_mode, uint32_t drop_threshold,
                       int64_t nsteps, double *w, double *slot, int64_t *slot_stamp, int64_t *ncum,
                       int64_t *t_io, int64_t *counters, int64_t *near, int32_t *assign_out,
@@ -269,6 +320,7 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
     if (H < k || S < 1) return -1;
     if (lr_mode == 1 && E != 0) return -1;
     if (nb < 1 || nb > 255 || (W > 1 && nb > W - 1)) return -1;
+    if (parts < 1 || parts > k) return -1;
     const size_t kd = (size_t)k * d;
     double *wnew = (double *)malloc((size_t)W * kd * sizeof(double));
     int *flags = (int *)malloc((size_t)W * sizeof(int));
@@ -283,19 +335,24 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
         for (int i = 0; i < W; ++i) {
             const float *M = X + ((size_t)i * H + (size_t)s * b) * d;
             const double *ext[256];
+            int extpart[256];
             int next = 0;
             for (int n = 0; merge_point && n < nb; ++n) {
                 const double *buf = slot + ((size_t)n * W + i) * kd;
                 if (slot_stamp[(size_t)n * W + i] != t / E - 1) continue;
+                const int part = (int)((t / E - 1 + i + n) % parts);    /* which rows the copy carries */
                 double nrm = 0.0;
-                for (size_t e = 0; e < kd; ++e) nrm += buf[e] * buf[e];
-                if (nrm > 0.0) ext[next++] = buf;       /* lambda of Eq. 3 */
+                for (int c = 0; c < k; ++c) {
+                    if (c % parts != part) continue;
+                    for (int j = 0; j < d; ++j) nrm += buf[(size_t)c * d + j] * buf[(size_t)c * d + j];
+                }
+                if (nrm > 0.0) { extpart[next] = part; ext[next++] = buf; }       /* lambda of Eq. 3 */
             }
             looked[i] = next;
             int32_t *ao = assign_out ? assign_out + ((size_t)n * W + i) * b : NULL;
             double *go = gap_out ? gap_out + ((size_t)n * W + i) * b : NULL;
-            flags[i] = worker_step(M, b, k, d, eps, lr_mode, parzen, w + i * kd, wnew + i * kd, ext, next,
-                                   ncum + (size_t)i * k, ao, go, &near_w[i]);
+            flags[i] = worker_step(M, b, k, d, eps, lr_mode, parzen, w + i * kd, wnew + i * kd, ext, next, parts,
+                                   extpart, ncum + (size_t)i * k, ao, go, &near_w[i]);
         }
         for (int i = 0; i < W; ++i) {
             counters[i * 3 + 1] += looked[i];
@@ -314,7 +371,11 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
                 for (int n = 0; n < nb; ++n) {
                     if (asgd_oracle_dropped_n(seed, r, i, n, drop_threshold)) continue;
                     int64_t p = asgd_oracle_peer_n(seed, r, i, W, n);
-                    memcpy(slot + ((size_t)n * W + p) * kd, w + i * kd, kd * sizeof(double));
+                    const int part = (int)((r + p + n) % parts);
+                    for (int c = 0; c < k; ++c)            /* only the rows of the part travel */
+                        if (c % parts == part)
+                            memcpy(slot + ((size_t)n * W + p) * kd + (size_t)c * d, w + i * kd + (size_t)c * d,
+                                   (size_t)d * sizeof(double));
                     slot_stamp[(size_t)n * W + p] = r;
                 }
             }

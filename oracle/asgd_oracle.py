@@ -52,7 +52,7 @@ def lib():
         L.asgd_oracle_quant_error.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, f64p]
         L.asgd_oracle_steps.restype = C.c_int
         L.asgd_oracle_steps.argtypes = [
-            C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int,
+            C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int, C.c_int,
             C.c_uint64, C.c_int, C.c_int, C.c_uint32, C.c_int64,
             f64p, f64p, i64p, i64p, i64p, i64p, i64p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -114,7 +114,7 @@ class OracleASGD:
 
     LR_CONST, LR_INV_COUNT = 0, 1
 
-    def __init__(self, X, k, W, b, lr, E=0, seed=1, parzen=True, lr_mode=0, drop_rate=0.0, w0=None, buffers=1):
+    def __init__(self, X, k, W, b, lr, E=0, seed=1, parzen=True, lr_mode=0, drop_rate=0.0, w0=None, buffers=1, parts=1):
         self.X = _f32(X)
         self.N, self.d = self.X.shape
         self.k, self.W, self.b, self.lr, self.E = int(k), int(W), int(b), float(lr), int(E)
@@ -132,6 +132,7 @@ class OracleASGD:
             self.w = np.ascontiguousarray(np.broadcast_to(w0, (self.W, self.k, self.d))).copy()
         self.w = np.ascontiguousarray(self.w)
         self.buffers = int(buffers)
+        self.parts = int(parts)
         lead = () if self.buffers == 1 else (self.buffers,)
         self.slot = np.zeros(lead + (self.W, self.k, self.d), dtype=np.float64)
         self.slot_stamp = np.full(lead + (self.W,), -1, dtype=np.int64)
@@ -145,7 +146,7 @@ class OracleASGD:
         a = np.empty((nsteps, self.W, self.b), dtype=np.int32) if dump else None
         g = np.empty((nsteps, self.W, self.b), dtype=np.float64) if dump else None
         rc = lib().asgd_oracle_steps(
-            self.X.ctypes.data, self.N, self.k, self.d, self.W, self.b, self.lr, self.E, self.buffers,
+            self.X.ctypes.data, self.N, self.k, self.d, self.W, self.b, self.lr, self.E, self.buffers, self.parts,
             self.seed, int(self.parzen), self.lr_mode, self.drop_threshold, nsteps,
             self.w.reshape(-1), self.slot.reshape(-1), self.slot_stamp.reshape(-1), self.ncum.reshape(-1),
             self.t, self.counters.reshape(-1), self.near,

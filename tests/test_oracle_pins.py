@@ -46,8 +46,9 @@ def py_peer(seed, r, i, W, n=0):
     return (i + 1 + (splitmix64_stream(seed, r + 1)[r] % (W - 1) + n) % (W - 1)) % W
 
 
-def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1):
-    """Whole lockstep ASGD (Alg. 5 + Eq. 4 + Eq. 6/7) in NumPy, vectorised differently from the oracle."""
+def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1, parts=1):
+    """Whole lockstep ASGD (Alg. 5 + Eq. 4 + Eq. 6/7, partial messages of Sec. 4.4) in NumPy, vectorised differently
+    from the oracle.  A buffer entry is (state, boolean row mask of the rows that travelled)."""
     N, d = X.shape
     H = N // W
     S = H // b
@@ -65,11 +66,12 @@ def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1):
             cnt = onehot.sum(0)
             G = (cnt[:, None] * w[i] - onehot.T @ M) / b
             step = G
-            if E > 0 and t > 0 and t % E == 0:
+            if E > 0 and t > 0 and t % E == 0 and parts == 1:
                 good = []
-                for we in buf[i]:
-                    if we is None or np.linalg.norm(we) == 0:
+                for ent in buf[i]:
+                    if ent is None or np.linalg.norm(ent[0]) == 0:
                         continue
+                    we = ent[0]
                     stats[i, 1] += 1
                     ok = np.sum(((w[i] - lr * G) - we) ** 2) < np.sum((w[i] - we) ** 2)
                     if ok or not parzen:
@@ -77,6 +79,21 @@ def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1):
                 if good:
                     stats[i, 2] += len(good)
                     step = (w[i] - np.mean(np.stack(good + [w[i]]), axis=0)) + G
+            elif E > 0 and t > 0 and t % E == 0:
+                total = w[i].copy()                      # per row: local state + accepted external rows
+                count = np.ones(k)
+                for ent in buf[i]:
+                    if ent is None or np.linalg.norm(ent[0][ent[1]]) == 0:
+                        continue
+                    we, rows = ent
+                    stats[i, 1] += 1
+                    lhs = np.sum(((w[i] - lr * G) - we) ** 2, axis=1)
+                    rhs = np.sum((w[i] - we) ** 2, axis=1)
+                    ok = rows & (np.sum(we ** 2, axis=1) > 0) & ((lhs < rhs) if parzen else True)
+                    total[ok] += we[ok]
+                    count[ok] += 1
+                    stats[i, 2] += int(ok.any())
+                step = (w[i] - total / count[:, None]) + G
             new[i] = w[i] - lr * step
         if E > 0 and t > 0 and t % E == 0:
             buf = [[None] * buffers for _ in range(W)]
@@ -86,7 +103,8 @@ def asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=True, buffers=1):
             for i in range(W):
                 stats[i, 0] += 1
                 for n in range(buffers):
-                    buf[py_peer(seed, r, i, W, n)][n] = w[i].copy()
+                    p = py_peer(seed, r, i, W, n)
+                    buf[p][n] = (w[i].copy(), np.arange(k) % parts == (r + p + n) % parts)
     return w, stats
 
 
@@ -391,16 +409,83 @@ def test_n_buffers_loss_hook_is_per_copy(oracle):
     assert o.counters[:, 0].sum() == 6 * rounds and o.counters[:, 1].sum() == expected
 
 
+# ---------------------------------------------------------------- partial messages (Sec. 4.4)
+def test_partial_messages_carry_one_part_and_rotate(oracle):
+    """After a send, buffer n of worker p holds the rows c = (r + p + n) mod P (mod P) of its sender's state and
+    nothing else; over P rounds a worker sees every part once per buffer."""
+    X = small_data(N=4000, d=3, k=6, seed=11)
+    k, W, b, E, nb, P = 6, 5, 20, 2, 2, 3
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=0.1, E=E, seed=4, buffers=nb, parts=P)
+    seen = {(p, n): set() for p in range(W) for n in range(nb)}
+    for r in range(P):
+        o.run_steps(E)                               # ends right after the send of round r
+        assert int(o.t[0]) == (r + 1) * E
+        for n in range(nb):
+            for i in range(W):
+                p = oracle.peer(4, r, i, W, n)
+                part = (r + p + n) % P
+                rows = np.arange(k) % P == part
+                assert np.array_equal(o.slot[n, p][rows], o.w[i][rows])
+                assert np.all(o.slot[n, p][~rows] == 0)
+                seen[(p, n)].add(part)
+    assert all(v == set(range(P)) for v in seen.values())
+    X2 = small_data(N=800)
+    for bad in (0, 5):
+        with pytest.raises(ValueError):
+            oracle.OracleASGD(X2, k=4, W=2, b=40, lr=0.2, E=2, parts=bad).run_steps(1)
+
+
+@pytest.mark.parametrize("parzen", [True, False])
+def test_partial_messages_gate_row_by_row(oracle, parzen):
+    """Row c of the external state at w_c - a_c G_c: Eq. 4 over that row alone accepts iff a_c > eps/2 (and
+    G_c != 0); only the rows of the part that travelled are looked at; an all-zero row is empty."""
+    X = small_data(N=1600, d=3, k=8, seed=3)
+    k, W, b, E, P, lr = 8, 2, 60, 2, 2, 0.2
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, parzen=parzen, parts=P)
+    o.t[0] = E                                   # merge point of round 1: message of round 0, part (0 + i) mod P
+    w = o.w.copy()
+    G = np.zeros_like(w)
+    for i in range(W):
+        M = X[i * o.H + (E % o.S) * b:i * o.H + (E % o.S + 1) * b].astype(np.float64)
+        a, _ = brute_assign(M, w[i])
+        for c_ in range(k):
+            G[i, c_] = ((a == c_).sum() * w[i][c_] - M[a == c_].sum(0)) / b
+    coef = np.array([0.5, 0.5, 0.05, 0.05, -1.0, 3.0, 0.11, 0.09])
+    ext = w - coef[None, :, None] * G
+    ext[:, 5] = 0.0                              # row 5 empty, whatever its part
+    o.slot[:] = ext
+    o.slot_stamp[:] = 0
+    o.run_steps(1)
+    for i in range(W):
+        in_part = np.arange(k) % P == (0 + i) % P
+        nonzero_g = np.abs(G[i]).sum(1) > 0
+        acc = in_part & (np.arange(k) != 5) & (((coef > lr / 2) & nonzero_g) if parzen else True)
+        assert acc.any() and (~acc).any()
+        expect = w[i] - lr * G[i]
+        expect[acc] -= (lr / 2) * (w[i][acc] - ext[i][acc])
+        assert np.allclose(o.w[i], expect, rtol=1e-12, atol=1e-13)
+    assert np.all(o.counters[:, 1] == 1) and np.all(o.counters[:, 2] == 1)
+
+
+def test_partial_messages_with_one_part_are_whole_messages(oracle):
+    X = small_data(N=3000, d=3, k=4, seed=5)
+    a = oracle.OracleASGD(X, k=4, W=4, b=30, lr=0.3, E=2, seed=9); a.run_steps(40)
+    c = oracle.OracleASGD(X, k=4, W=4, b=30, lr=0.3, E=2, seed=9, parts=1); c.run_steps(40)
+    assert np.array_equal(a.w, c.w) and np.array_equal(a.counters, c.counters)
+
+
 # ---------------------------------------------------------------- whole algorithm vs NumPy
-@pytest.mark.parametrize("W,E,parzen,buffers", [(4, 3, True, 1), (3, 1, True, 1), (5, 2, False, 1),
-                                                (5, 2, True, 2), (4, 1, True, 3), (6, 3, False, 4)])
-def test_full_run_matches_independent_numpy_asgd(oracle, W, E, parzen, buffers):
+@pytest.mark.parametrize("W,E,parzen,buffers,parts", [(4, 3, True, 1, 1), (3, 1, True, 1, 1), (5, 2, False, 1, 1),
+                                                      (5, 2, True, 2, 1), (4, 1, True, 3, 1), (6, 3, False, 4, 1),
+                                                      (4, 1, True, 1, 2), (5, 2, True, 1, 4), (5, 1, False, 2, 3),
+                                                      (6, 2, True, 3, 2)])
+def test_full_run_matches_independent_numpy_asgd(oracle, W, E, parzen, buffers, parts):
     X = small_data(N=3000, d=3, k=4, seed=5)
     k, b, lr, seed = 4, 30, 0.3, 42
-    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, buffers=buffers)
+    o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, buffers=buffers, parts=parts)
     steps = 2 * o.S + 5
     o.run_steps(steps)
-    ref_w, ref_stats = asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=parzen, buffers=buffers)
+    ref_w, ref_stats = asgd_numpy(X, k, W, b, lr, E, seed, steps, parzen=parzen, buffers=buffers, parts=parts)
     assert np.allclose(o.w, ref_w, rtol=1e-11, atol=1e-12)
     assert np.array_equal(o.counters, ref_stats)
     assert ref_stats[:, 2].sum() > 0                       # the merge path really ran
