@@ -66,7 +66,7 @@ enum {
                                     grids that cannot be; 0: plain launch of the same grid (for tools
                                     that cannot follow cooperative launches).  The in-kernel waits are
                                     bounded either way. */
-    ASGD_OPT_BUFFERS = 10        /* N of Eq. 3 / Eq. 6: external buffers per worker, 1 (default) .. 4.  A
+    ASGD_OPT_BUFFERS = 10,       /* N of Eq. 3 / Eq. 6: external buffers per worker, 1 (default) .. 4.  A
                                     worker then sends every message to N different workers (copy n goes
                                     into the recipient's buffer n; deterministic schedule: a cyclic shift
                                     per round and copy, so every worker receives N messages per round from
@@ -78,6 +78,16 @@ enum {
                                     (ASGD_ESTATE after); reallocates the exchange buffers (2 * N * W states).
                                     N > 1 is not available in the small-state kernel (ASGD_KERNEL_AUTO then
                                     picks another one). */
+    ASGD_OPT_PARTS = 11          /* partial messages (Sec. 4.4, partitioned along the cluster centres):
+                                    P in 1 .. k, default 1 = whole states.  With P > 1 part q is the set of
+                                    centroid rows c with c mod P = q, and copy n of the message of round r
+                                    to worker p carries part (r + p + n) mod P only (1/P of the bytes); the
+                                    recipient treats every transmitted row as a unit of its own: empty iff
+                                    all zero, tested by Eq. 4 over that row, merged by Eq. 6 with the other
+                                    buffers' accepted copies of the same row; rows that did not travel take
+                                    the plain step.  "received" then counts buffers with a non-empty row,
+                                    "accepted" buffers with an accepted row.  May only be set before the
+                                    first step (ASGD_ESTATE after); not available in the small-state kernel. */
 };
 enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
 enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };

@@ -14,7 +14,7 @@ import numpy as np
 from . import build as _build
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, ESYNC = 0, -1, -2, -3, -4, -5
-OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE, OPT_BUFFERS = range(1, 11)
+OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE, OPT_BUFFERS, OPT_PARTS = range(1, 12)
 MODE_DETERMINISTIC, MODE_FREE_RUNNING = 0, 1
 LR_CONST, LR_INV_COUNT = 0, 1
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_SMALL, KERNEL_MFMA = 0, 1, 2, 3
@@ -174,13 +174,13 @@ def asgd_destroy(h):
 # ---- convenience wrapper: owns a handle, keeps the borrowed tensors alive -----------------
 class ASGD:
     def __init__(self, k, d, W, b, lr, E=0, seed=1, mode=MODE_DETERMINISTIC, parzen=True,
-                 lr_mode=LR_CONST, drop_rate=0.0, kernel=KERNEL_AUTO, tune=0, cooperative=True, buffers=1):
+                 lr_mode=LR_CONST, drop_rate=0.0, kernel=KERNEL_AUTO, tune=0, cooperative=True, buffers=1, parts=1):
         self.k, self.d, self.W, self.b = k, d, W, b
         self.h = asgd_create(k, d, W, b, lr)
         for key, val in ((OPT_EXCHANGE_EVERY, E), (OPT_SEED, seed), (OPT_MODE, mode),
                          (OPT_PARZEN, int(parzen)), (OPT_LR_MODE, lr_mode),
                          (OPT_DROP_RATE, drop_rate), (OPT_KERNEL, kernel), (OPT_TUNE, tune),
-                         (OPT_COOPERATIVE, int(cooperative)), (OPT_BUFFERS, buffers)):
+                         (OPT_COOPERATIVE, int(cooperative)), (OPT_BUFFERS, buffers), (OPT_PARTS, parts)):
             asgd_set_option(self.h, key, val)
         self._x = None
         self._dump = None

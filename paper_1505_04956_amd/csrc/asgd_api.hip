@@ -21,6 +21,7 @@ struct asgd_ctx {
     int kernel_opt = ASGD_KERNEL_AUTO;
     int tune = 0;
     int nb = 1;                 // external buffers per worker
+    int parts = 1;              // partial messages: parts of a state (1 = whole states)
     size_t slot_bytes_one = 0;  // bytes of both parities of ONE buffer per worker
     int cooperative = 1;
 
@@ -80,7 +81,7 @@ StepParams make_params(const asgd_ctx *c)
     p.counters = c->counters; p.acc = c->acc; p.cnt = c->cnt; p.assign_tmp = c->assign_tmp;
     p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->error_flag;
     p.H = c->H; p.S = c->S; p.t_dump0 = c->t; p.seed = c->seed;
-    p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr; p.nb = c->nb;
+    p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr; p.nb = c->nb; p.parts = c->parts;
     p.parzen = c->parzen; p.lr_mode = c->lr_mode; p.mode = c->mode;
     p.drop_thr = (uint32_t)llround(c->drop_rate * (double)(1u << 24));
     p.tune = c->tune;
@@ -91,8 +92,10 @@ StepParams make_params(const asgd_ctx *c)
 int clear_exchange(asgd_ctx *c)
 {
     // all bits set: empty in both message formats (stamp -1 inside the small-state kernel's pairs; the other
-    // kernels look at `stamp` before they read a buffer)
-    HIP_TRY(c, hipMemsetAsync(c->slot, 0xFF, c->slot_bytes, c->stream));
+    // kernels look at `stamp` before they read a buffer).  Partial messages leave rows of a buffer unwritten, which a
+    // free-running recipient may look at: those start as zeros (an empty row), and the small-state kernel is not
+    // used with them.
+    HIP_TRY(c, hipMemsetAsync(c->slot, c->parts > 1 ? 0 : 0xFF, c->slot_bytes, c->stream));
     HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->nb * c->W * sizeof(int), c->stream));   // -1
     return ASGD_OK;
 }
@@ -248,6 +251,15 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
             ctx->nb = nb;
             return clear_exchange(ctx);
         }
+        case ASGD_OPT_PARTS:
+            if (value < 1 || value > ctx->k || value != floor(value)) return ASGD_EINVAL;
+            if (ctx->t != 0) return ASGD_ESTATE;
+            ctx->parts = (int)value;
+            if (ctx->loaded) {
+                HIP_TRY(ctx, hipSetDevice(ctx->device));
+                return clear_exchange(ctx);
+            }
+            return ASGD_OK;
         case ASGD_OPT_TUNE:
             if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
             ctx->tune = (int)value;
@@ -332,7 +344,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 
     int kernel = ctx->kernel_opt;
     if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
-    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->nb == 1;
+    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->nb == 1 && ctx->parts == 1;
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
     if (kernel == ASGD_KERNEL_AUTO) {
         // the matrix-core kernel pays off once the k x d contraction dominates a step

@@ -74,6 +74,7 @@ struct StepParams {
     uint64_t seed;
     int k, d, W, b, E;
     int nb;                // external buffers per worker = recipients per message (Eq. 3), 1 .. MAX_BUFFERS
+    int parts;             // partial messages: a copy carries the centroid rows of one of `parts` parts (1: whole state)
     float eps;
     int parzen, lr_mode, mode;
     uint32_t drop_thr;

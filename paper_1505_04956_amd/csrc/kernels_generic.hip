@@ -49,6 +49,14 @@ __device__ void block_sum3(double &a, double &b, double &c, double (*red)[GEN_TH
     __syncthreads();
 }
 
+// Sum of a double over the 64 lanes of a wave, same value and same order in every lane.
+__device__ __forceinline__ double gen_wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
 __global__ void init_first_k_kernel(StepParams p)
 {
     // Worker i starts from the first k rows of its own shard.
@@ -110,6 +118,8 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
     extern __shared__ float smem[];
     __shared__ double red[3][GEN_THREADS];
     __shared__ int s_has_ext;
+    __shared__ int s_ext_round[MAX_BUFFERS];   // round of the message in buffer n (free-running mode: any earlier one)
+    __shared__ int s_rowflags[3];          // partial messages: buffers with a non-empty row, with an accepted row, near-ties
     __shared__ long long s_recheck;
     __shared__ int s_asg[GEN_ASG_LDS];
 
@@ -202,6 +212,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 int *stp = p.stamp + ((size_t)(rpar * p.nb + n) * p.W + i);
                 const int st = *stp;
                 if (det ? (st == (int)(r_now - 1)) : (st >= 0)) has |= 1 << n;
+                s_ext_round[n] = st;
                 *stp = -1;
             }
             s_has_ext = has;
@@ -215,8 +226,60 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
             const int c = (int)(e / d);
             sp[e] = ((float)cntp[c] * wp[e] - sp[e]) / (float)b;
         }
+        if (p.parts > 1) {
+            // Partial messages (Sec. 4.4): copy n for this worker carries the centroid rows c with
+            // c mod P = (round + worker + n) mod P; lambda, Eq. 4 and Eq. 6 row by row.  A wave takes a row
+            // through gate and update in one pass (no sum over the whole state is needed).
+            if (tid < 3) s_rowflags[tid] = 0;
+            __syncthreads();
+            int nz = 0, acc = 0, near = 0;
+            for (int c = wave; c < k; c += GEN_THREADS / 64) {
+                int rowmask = 0;
+                for (int n = 0; n < p.nb; ++n) {
+                    if (!(has_mask >> n & 1) || c % p.parts != (s_ext_round[n] + i + n) % p.parts) continue;
+                    double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+                    for (int j = lane; j < d; j += 64) {
+                        const size_t e = (size_t)c * d + j;
+                        const double we = (double)ext[n][e];
+                        const double a = ((double)wp[e] - (double)p.eps * (double)sp[e]) - we;
+                        const double c2 = (double)wp[e] - we;
+                        lhs += a * a; rhs += c2 * c2; nrm += we * we;
+                    }
+                    lhs = gen_wave_sum(lhs); rhs = gen_wave_sum(rhs); nrm = gen_wave_sum(nrm);
+                    if (!(nrm > 0.0)) continue;
+                    nz |= 1 << n;
+                    if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) near = 1;
+                    if (p.parzen ? (lhs < rhs) : 1) rowmask |= 1 << n;
+                }
+                acc |= rowmask;
+                const float inv = 1.0f / (float)(__builtin_popcount(rowmask) + 1);
+                for (int j = lane; j < d; j += 64) {
+                    const size_t e = (size_t)c * d + j;
+                    float step = sp[e];
+                    if (rowmask) {
+                        float sum = wp[e];
+                        for (int n = 0; n < p.nb; ++n)
+                            if (rowmask >> n & 1) sum += ext[n][e];
+                        step += wp[e] - inv * sum;
+                    }
+                    wp[e] = wp[e] - p.eps * step;
+                }
+            }
+            if (lane == 0) {
+                if (nz) atomicOr(&s_rowflags[0], nz);
+                if (acc) atomicOr(&s_rowflags[1], acc);
+                if (near) atomicOr(&s_rowflags[2], near);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                long long *cn = p.counters + (size_t)i * CNT_STRIDE;
+                cn[CNT_RECEIVED] += __builtin_popcount(s_rowflags[0]);
+                cn[CNT_ACCEPTED] += __builtin_popcount(s_rowflags[1]);
+                cn[CNT_PARZEN_NEAR] += s_rowflags[2];
+            }
+        }
         int delta_mask = 0, ndelta = 0;
-        for (int n = 0; n < p.nb; ++n) {
+        for (int n = 0; n < p.nb && p.parts == 1; ++n) {
             if (!(has_mask >> n & 1)) continue;
             double lhs = 0.0, rhs = 0.0, nrm = 0.0;
             for (size_t e = tid; e < kd; e += GEN_THREADS) {
@@ -240,7 +303,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         }
         // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
         const float inv = 1.0f / (float)(ndelta + 1);
-        for (size_t e = tid; e < kd; e += GEN_THREADS) {
+        for (size_t e = tid; p.parts == 1 && e < kd; e += GEN_THREADS) {
             float step = sp[e];
             if (ndelta) {
                 float sum = wp[e];
@@ -260,7 +323,9 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 const int peer = det ? peer_deterministic(p.seed, r, i, p.W, n) : peer_free(p.seed, r, i, p.W, n);
                 const int spar = det ? (int)(r & 1) : 0;
                 float *dst = p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd;
-                for (size_t e = tid; e < kd; e += GEN_THREADS) dst[e] = wp[e];
+                const int part = (int)((r + peer + n) % p.parts);           // only the rows of this part travel
+                for (size_t e = tid; e < kd; e += GEN_THREADS)
+                    if (p.parts == 1 || (int)(e / d) % p.parts == part) dst[e] = wp[e];
                 __threadfence();
                 __syncthreads();
                 if (tid == 0) p.stamp[(size_t)(spar * p.nb + n) * p.W + peer] = (int)r;

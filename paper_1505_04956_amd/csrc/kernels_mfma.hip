@@ -180,6 +180,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     __shared__ double red_d[3][MF_WAVES];
     __shared__ float red_f[MF_WAVES];
     __shared__ int s_has_ext;
+    __shared__ int s_ext_round[MAX_BUFFERS];   // round of the message in buffer n (free-running mode: any earlier one)
+    __shared__ int s_rowflags[3];     // partial messages: buffers with a non-empty row, with an accepted row, near-ties
     __shared__ int s_next_rows;
 
     const int i = blockIdx.x;                       // worker
@@ -618,8 +620,11 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                             atomicOr(p.error_flag, 1);
                     }
                     if (__hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)(r_now - 1)) has |= 1 << n;
+                    s_ext_round[n] = (int)(r_now - 1);
                 } else {
-                    if (*stp >= 0) has |= 1 << n;
+                    const int st = *stp;
+                    if (st >= 0) has |= 1 << n;
+                    s_ext_round[n] = st;
                     *stp = -1;
                 }
             }
@@ -744,6 +749,89 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int has_mask = s_has_ext;      // uniform over the workgroup
         const float *ext0 = p.slot + ((size_t)(rpar * p.nb) * p.W + i) * kd;          // buffer n: + n * W * kd
         const size_t ext_stride = (size_t)p.W * kd;
+        if (p.parts > 1) {
+            // ---- partial messages (Sec. 4.4): copy n for this worker carries the centroid rows c with
+            // c mod P = (round + worker + n) mod P; lambda, Eq. 4 and Eq. 6 row by row, gate and update of a row in
+            // one pass of the wave that takes it ----
+            if (tid < 3) s_rowflags[tid] = 0;
+            __syncthreads();
+            int nz = 0, acc = 0, near = 0;
+            wn2max = 0.0f;
+            for (int c = wave; c < k; c += MF_WAVES) {
+                const int sl = (c % NWV) * g.kq + c / NWV;
+                const int cn = cstart[sl + 1] - cstart[sl];
+                float w[NJ], gq[NJ], wesum[NJ];
+#pragma unroll
+                for (int jq = 0; jq < NJ; ++jq) {
+                    const int j = lane + 64 * jq;
+                    const size_t e = (size_t)c * d + (j < d ? j : 0);
+                    w[jq] = wst[e];
+                    const float sums = cn > 0 ? gsc[e] : 0.0f;
+                    gq[jq] = ((float)cn * w[jq] - sums) / (float)b;            // descent gradient of Eq. 9
+                    wesum[jq] = 0.0f;
+                }
+                int rowmask = 0;
+                for (int n = 0; n < p.nb; ++n) {
+                    if (!(has_mask >> n & 1) || c % p.parts != (s_ext_round[n] + i + n) % p.parts) continue;
+                    float we[NJ];
+                    double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+#pragma unroll
+                    for (int jq = 0; jq < NJ; ++jq) {
+                        const int j = lane + 64 * jq;
+                        we[jq] = ext0[n * ext_stride + (size_t)c * d + (j < d ? j : 0)];
+                        if (j < d) {
+                            const double wed = (double)we[jq];
+                            const double a = ((double)w[jq] - (double)p.eps * (double)gq[jq]) - wed;
+                            const double c2 = (double)w[jq] - wed;
+                            lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
+                        }
+                    }
+                    lhs = wave_sum_d(lhs); rhs = wave_sum_d(rhs); nrm = wave_sum_d(nrm);
+                    if (!(nrm > 0.0)) continue;
+                    nz |= 1 << n;
+                    if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) near = 1;
+                    if (p.parzen ? (lhs < rhs) : 1) {
+                        rowmask |= 1 << n;
+#pragma unroll
+                        for (int jq = 0; jq < NJ; ++jq) wesum[jq] += we[jq];
+                    }
+                }
+                acc |= rowmask;
+                const float inv = 1.0f / (float)(__builtin_popcount(rowmask) + 1);
+                float s2 = 0.0f;
+#pragma unroll
+                for (int jq = 0; jq < NJ; ++jq) {
+                    const int j = lane + 64 * jq;
+                    if (j < d) {
+                        float step = gq[jq];
+                        if (rowmask) step += w[jq] - inv * (w[jq] + wesum[jq]);
+                        const float wn = w[jq] - p.eps * step;
+                        wst[(size_t)c * d + j] = wn;
+                        s2 = fmaf(wn, wn, s2);
+                    }
+                }
+                const float sq = wave_sum_f(s2);
+                if (lane == 0) hs[c] = -0.5f * sq;
+                wn2max = fmaxf(wn2max, sq);
+            }
+            if (lane == 0) {
+                red_f[wave] = wn2max;
+                if (nz) atomicOr(&s_rowflags[0], nz);
+                if (acc) atomicOr(&s_rowflags[1], acc);
+                if (near) atomicOr(&s_rowflags[2], near);
+            }
+            __threadfence_block();
+            __syncthreads();
+            wn2max = 0.0f;
+#pragma unroll
+            for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
+            if (tid == 0) {
+                long long *cnp = p.counters + (size_t)i * CNT_STRIDE;
+                cnp[CNT_RECEIVED] += __builtin_popcount(s_rowflags[0]);
+                cnp[CNT_ACCEPTED] += __builtin_popcount(s_rowflags[1]);
+                cnp[CNT_PARZEN_NEAR] += s_rowflags[2];
+            }
+        } else {
         // ---- Parzen sums (Eq. 4) over the whole state, fp64, every buffer on its own (Eq. 6) ----
         int delta_mask = 0;
         for (int n = 0; n < p.nb; ++n) {
@@ -854,6 +942,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
         }
 
+        }
         // every wave has read the external state for the last time (barrier above): its buffer may be written again
         if (sync && merge_point && tid == 0)
             __hip_atomic_store(p.consumed + i, (int)r_now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -872,7 +961,17 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd);
                 const float4 *src = reinterpret_cast<const float4 *>(wst);
-                for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
+                if (p.parts == 1) {
+                    for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
+                } else {
+                    // only the rows of the part travel: row c = part + P * m, float4 column q4 (d is a multiple of 4)
+                    const int part = (int)((r + peer + n) % p.parts), row4 = d / 4;
+                    const int nrows = (k - part + p.parts - 1) / p.parts;
+                    for (int e = tid; e < nrows * row4; e += MF_THREADS) {
+                        const size_t o = (size_t)(part + p.parts * (e / row4)) * row4 + e % row4;
+                        dst[o] = src[o];
+                    }
+                }
                 __threadfence();
                 __syncthreads();
                 if (tid == 0) __hip_atomic_store(p.stamp + (size_t)(spar * p.nb + n) * p.W + peer, (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -43,14 +43,14 @@ def make_data(N, d, k, seed=3, centres="uniform10", weights="equal", sigma=1.0):
 
 
 def run_both(B, oracle, X, k, W, b, lr, E, steps, seed=1, parzen=True, drop_rate=0.0, lr_mode=0,
-             kernel=0, tune=0, dump=True, w0=None, check_qe=True, buffers=1):
+             kernel=0, tune=0, dump=True, w0=None, check_qe=True, buffers=1, parts=1):
     """Run `steps` steps on the GPU and in the oracle; assert the bars; return both."""
     N, d = X.shape
     g = B.ASGD(k, d, W, b, lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate, lr_mode=lr_mode,
-               kernel=kernel, tune=tune, buffers=buffers)
+               kernel=kernel, tune=tune, buffers=buffers, parts=parts)
     g.load_shards(to_dev(X))
     o = oracle.OracleASGD(X, k=k, W=W, b=b, lr=lr, E=E, seed=seed, parzen=parzen, drop_rate=drop_rate,
-                          lr_mode=lr_mode, w0=w0, buffers=buffers)
+                          lr_mode=lr_mode, w0=w0, buffers=buffers, parts=parts)
     if w0 is not None:
         g.set_state(-1, np.asarray(w0, dtype=np.float32))
     if dump:
@@ -279,6 +279,53 @@ def test_n_external_buffers(B, oracle, kernel, tune, k, d, W, b, E, steps, buffe
     assert o.counters[:, 1].sum() > W                          # several buffers were looked at per merge point
     if parzen and drop == 0.0:
         assert 0 < o.counters[:, 2].sum()
+
+
+@pytest.mark.parametrize("kernel,tune,k,d,W,b,E,steps,buffers,parts,parzen,drop", [
+    (1, 0, 10, 10, 6, 100, 2, 13, 1, 2, True, 0.0),
+    (1, 0, 7, 5, 5, 64, 1, 9, 3, 7, True, 0.3),          # one row per message
+    (1, 0, 12, 9, 6, 50, 3, 14, 2, 5, False, 0.0),
+    (3, 2, 40, 20, 12, 100, 2, 17, 1, 4, True, 0.0),     # four waves, one launch
+    (3, 2, 40, 20, 12, 100, 1, 12, 3, 3, True, 0.4),
+    (3, 6, 40, 20, 12, 100, 2, 17, 2, 8, False, 0.0),    # four waves, one launch per round
+    (3, 8, 40, 20, 12, 100, 3, 17, 2, 40, True, 0.0),    # eight waves, one launch
+    (3, 0, 70, 36, 5, 300, 2, 9, 4, 6, True, 0.0),       # eight waves, one launch per round
+    (3, 0, 100, 100, 4, 2000, 2, 7, 1, 3, True, 0.0),    # two columns of lanes per row
+])
+def test_partial_messages(B, oracle, kernel, tune, k, d, W, b, E, steps, buffers, parts, parzen, drop):
+    """Sec. 4.4: a copy carries the centroid rows of one part; lambda, Eq. 4 and Eq. 6 row by row."""
+    X = make_data(W * (steps + 1) * b + 7, d, k, seed=37)
+    g, o = run_both(B, oracle, X, k, W, b, 0.05, E, steps, kernel=kernel, tune=tune, buffers=buffers, parts=parts,
+                    parzen=parzen, drop_rate=drop)
+    assert g.stats().kernel == kernel
+    assert o.counters[:, 1].sum() > 0 and o.counters[:, 2].sum() > 0
+
+
+def test_partial_messages_options(B):
+    X = make_data(6 * 1500, 10, 10, seed=33)
+    Xg = to_dev(X)
+    auto = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=2); auto.load_shards(Xg); auto.run_steps(5)
+    assert auto.stats().kernel == B.KERNEL_GENERIC              # the small-state kernel sends whole states
+    with pytest.raises(B.AsgdError):
+        auto.set_option(B.OPT_PARTS, 5)                         # not after the first step
+    for bad in (0, 11, 2.5):
+        with pytest.raises(B.AsgdError):
+            B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=bad)
+    with pytest.raises(B.AsgdError):
+        small = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=2, kernel=B.KERNEL_SMALL); small.load_shards(Xg); small.run_steps(1)
+    # one part set explicitly is the default
+    a = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=1); a.load_shards(Xg); a.run_steps(9)
+    c = B.ASGD(10, 10, 6, 100, 0.05, E=2); c.load_shards(Xg); c.run_steps(9)
+    assert a.stats().kernel == B.KERNEL_SMALL and np.array_equal(a.get_state(), c.get_state())
+    # continued in the middle of a round: bit for bit; free-running mode: finite, messages arrive
+    Xm = to_dev(make_data(12 * 1500, 20, 40, seed=34))
+    e = B.ASGD(40, 20, 12, 100, 0.05, E=2, buffers=2, parts=4, kernel=3); e.load_shards(Xm); e.run_steps(9)
+    f = B.ASGD(40, 20, 12, 100, 0.05, E=2, buffers=2, parts=4, kernel=3); f.load_shards(Xm); f.run_steps(4); f.run_steps(5)
+    assert np.array_equal(e.get_state(), f.get_state())
+    fr = B.ASGD(40, 20, 12, 100, 0.05, E=2, buffers=2, parts=4, mode=B.MODE_FREE_RUNNING, kernel=3)
+    fr.load_shards(Xm); fr.run_steps(15)
+    st = fr.stats()
+    assert np.all(np.isfinite(fr.get_state())) and st.sent == 12 * 7 and 0 < st.received <= 2 * st.sent
 
 
 def test_n_external_buffers_options(B, oracle):
