@@ -83,6 +83,8 @@ def main():
                          "the paper's races; silent: no exchange at all (E = 0), for the merge-overhead column")
     ap.add_argument("--buffers", type=int, default=1,
                     help="external buffers per worker = recipients per message (Eq. 3 / Eq. 6); 1 is the metric's")
+    ap.add_argument("--parts", type=int, default=1,
+                    help="partial messages: a copy carries one of P parts of the centroid rows (Sec. 4.4); 1 is the metric's")
     ap.add_argument("--quant-error", action="store_true", help="also report Eq. 8 of worker 0 after the timed epochs")
     ap.add_argument("--plain-launch", action="store_true",
                     help="start the single-launch kernel with a plain launch instead of a cooperative one "
@@ -113,7 +115,7 @@ def main():
         del Y
     g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=(0 if args.mode == "silent" else wl.E), seed=wl.schedule_seed,
                mode=(B.MODE_FREE_RUNNING if args.mode == "free" else B.MODE_DETERMINISTIC), tune=args.tune,
-               cooperative=not args.plain_launch, buffers=args.buffers)
+               cooperative=not args.plain_launch, buffers=args.buffers, parts=args.parts)
     g.load_shards(X)
     for _ in range(args.warmup):
         g.run_epochs(1)
@@ -151,7 +153,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "k": wl.k, "W": wl.W, "b": wl.b, "lr": wl.lr,
                    "exchange_every": (0 if args.mode == "silent" else wl.E), "epochs_per_step": 1, "mode": args.mode,
-                   "buffers": args.buffers,
+                   "buffers": args.buffers, "parts": args.parts,
                    "samples_per_step": samples, "kernel": int(st.kernel), "launches_per_step": int(st.launches)},
         "roofline": roofline,
         "stats": {"messages_sent": int(st.sent), "messages_received": int(st.received),
