@@ -36,9 +36,11 @@ class asgd_stats(C.Structure):
 
 
 class AsgdError(RuntimeError):
-    def __init__(self, code, what):
+    def __init__(self, code, what, hip_error=0):
         self.code = code
-        super().__init__("%s failed: %s (code %d)" % (what, strerror(code), code))
+        self.hip_error = hip_error
+        extra = ", hipError_t %d" % hip_error if hip_error else ""
+        super().__init__("%s failed: %s (code %d%s)" % (what, strerror(code), code, extra))
 
 
 _lib = None
@@ -84,9 +86,10 @@ def strerror(code: int) -> str:
     return lib().asgd_strerror(int(code)).decode()
 
 
-def _check(code, what):
+def _check(code, what, h=None):
     if code != OK:
-        raise AsgdError(code, what)
+        hip_error = int(lib().asgd_last_hip_error(h)) if (h is not None and code == EHIP) else 0
+        raise AsgdError(code, what, hip_error)
 
 
 # ---- one function per C entry point ---------------------------------------------------
@@ -97,16 +100,16 @@ def asgd_create(k, d, W, b, lr):
 
 
 def asgd_set_option(h, key, value):
-    _check(lib().asgd_set_option(h, key, float(value)), "asgd_set_option")
+    _check(lib().asgd_set_option(h, key, float(value)), "asgd_set_option", h)
 
 
 def asgd_load_shards(h, x_dev_ptr, N, stream=0):
-    _check(lib().asgd_load_shards(h, x_dev_ptr, N, stream), "asgd_load_shards")
+    _check(lib().asgd_load_shards(h, x_dev_ptr, N, stream), "asgd_load_shards", h)
 
 
 def asgd_set_state(h, worker, w_host: np.ndarray):
     w_host = np.ascontiguousarray(w_host, dtype=np.float32)
-    _check(lib().asgd_set_state(h, worker, w_host.ctypes.data), "asgd_set_state")
+    _check(lib().asgd_set_state(h, worker, w_host.ctypes.data), "asgd_set_state", h)
 
 
 def asgd_set_step(h, t):
@@ -114,11 +117,11 @@ def asgd_set_step(h, t):
 
 
 def asgd_run_epochs(h, epochs):
-    _check(lib().asgd_run_epochs(h, epochs), "asgd_run_epochs")
+    _check(lib().asgd_run_epochs(h, epochs), "asgd_run_epochs", h)
 
 
 def asgd_run_steps(h, steps):
-    _check(lib().asgd_run_steps(h, steps), "asgd_run_steps")
+    _check(lib().asgd_run_steps(h, steps), "asgd_run_steps", h)
 
 
 def asgd_set_assign_dump(h, dev_ptr, capacity):
@@ -127,17 +130,17 @@ def asgd_set_assign_dump(h, dev_ptr, capacity):
 
 def asgd_get_state(h, worker, out: np.ndarray):
     assert out.dtype == np.float32 and out.flags.c_contiguous
-    _check(lib().asgd_get_state(h, worker, out.ctypes.data, out.nbytes), "asgd_get_state")
+    _check(lib().asgd_get_state(h, worker, out.ctypes.data, out.nbytes), "asgd_get_state", h)
 
 
 def asgd_get_mean_state(h, out: np.ndarray):
     assert out.dtype == np.float32 and out.flags.c_contiguous
-    _check(lib().asgd_get_mean_state(h, out.ctypes.data, out.nbytes), "asgd_get_mean_state")
+    _check(lib().asgd_get_mean_state(h, out.ctypes.data, out.nbytes), "asgd_get_mean_state", h)
 
 
 def asgd_quant_error(h, worker) -> float:
     v = C.c_double()
-    _check(lib().asgd_quant_error(h, worker, C.byref(v)), "asgd_quant_error")
+    _check(lib().asgd_quant_error(h, worker, C.byref(v)), "asgd_quant_error", h)
     return v.value
 
 
