@@ -1173,7 +1173,8 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const
 template <int NCH>
 hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
-    // tune bit 0 forces 8 waves, bit 1 forces 4 waves (resident variant only)
+    // tune bit 0 forces 8 waves, bit 1 forces 4 waves (resident variant only); bit 2 (host side) forces one launch per
+    // round, bit 3 one launch with waits also for 8 waves
     const size_t half_cu = 78 * 1024;      // two workgroups per CU must fit 160 KB, a little is reserved
     if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2)))
         return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);
