@@ -39,6 +39,7 @@ struct asgd_ctx {
     long long shift_cap = 0;
     bool xnorm2max_valid = false;
     int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
+    int *flag_host = nullptr;   // pinned: the error flag is copied here behind the kernels of a run, one wait covers both
     long long *ncum = nullptr, *counters = nullptr;
     double *qpart = nullptr, *qout = nullptr;
     int32_t *dump = nullptr;
@@ -69,6 +70,7 @@ void free_all(asgd_ctx *c)
                     c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max, c->shift_tab};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
+    if (c->flag_host) (void)hipHostFree(c->flag_host);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
 }
@@ -169,6 +171,7 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
         e = hipMalloc(a.p, a.bytes);
         if (e != hipSuccess) { fail(e); break; }
     }
+    if (rc == ASGD_OK && (e = hipHostMalloc((void **)&c->flag_host, sizeof(int), hipHostMallocDefault)) != hipSuccess) fail(e);
     if (rc == ASGD_OK && (e = hipEventCreate(&c->ev0)) != hipSuccess) fail(e);
     if (rc == ASGD_OK && (e = hipEventCreate(&c->ev1)) != hipSuccess) fail(e);
     if (rc != ASGD_OK) {
@@ -426,6 +429,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         ta = tb;
     }
     HIP_TRY(ctx, hipEventRecord(ctx->ev1, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->flag_host, ctx->error_flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     float ms = 0.f;
     HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev0, ctx->ev1));
@@ -433,9 +437,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     ctx->last_kernel = kernel;
     ctx->last_launches = launches;
     ctx->t = t_end;
-    int flag = 0;
-    HIP_TRY(ctx, hipMemcpy(&flag, ctx->error_flag, sizeof(int), hipMemcpyDeviceToHost));
-    if (flag) return ASGD_ESYNC;
+    if (*ctx->flag_host) return ASGD_ESYNC;
     return ASGD_OK;
 }
 
