@@ -72,11 +72,20 @@ __device__ __forceinline__ void top3_insert(Top3 &t, float s, int c)
 
 // Value-only insert into a sorted triple (v1 >= v2 >= v3): three instructions.  Used on scores whose low five
 // mantissa bits were replaced by the number of the accumulator register they came from.
-__device__ __forceinline__ void top3_insert_value(Top3 &t, float s)
+// `big` is +infinity in a register the compiler cannot see through: med3(v1, s, +inf) = max(v1, s) stays ONE
+// instruction (folded to a maximum it would be preceded by an instruction that quiets a signalling NaN, which a
+// tagged score can look like).  Every vector instruction between two matrix instructions costs matrix-pipe time.
+__device__ __forceinline__ void top3_insert_value(Top3 &t, float s, float big)
 {
     t.v3 = __builtin_amdgcn_fmed3f(t.v2, t.v3, s);
     t.v2 = __builtin_amdgcn_fmed3f(t.v1, t.v2, s);
-    t.v1 = __builtin_amdgcn_fmed3f(t.v1, s, INFINITY);
+    t.v1 = __builtin_amdgcn_fmed3f(t.v1, s, big);
+}
+__device__ __forceinline__ float opaque_infinity()
+{
+    float big = INFINITY;
+    asm volatile("" : "+s"(big));
+    return big;
 }
 __device__ __forceinline__ float tag_low5(float v, int r)
 {
@@ -304,6 +313,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 store_block(st, Ws);
             }
             Top3 top;
+            const float big = opaque_infinity();
             top.v1 = top.v2 = top.v3 = -INFINITY;
             top.i1 = top.i2 = 0;
             // The 64 rows of a block are done as two half-blocks of 32 rows (one 32x32 accumulator each), and the running
@@ -344,7 +354,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if constexpr (INS) {
 #pragma unroll
                         for (int r = ch * 16 / NCH; r < (ch + 1) * 16 / NCH; ++r)
-                            top3_insert_value(top, tag_low5(prev[r], r));
+                            top3_insert_value(top, tag_low5(prev[r], r), big);
                     }
                     if constexpr (MODE == 1) {
                         if (ch == 0) fetch_block(st, cb + 1);   // not before the first chunk: it waits for all loads
@@ -400,7 +410,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 // the last half-block's scores
                 const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], r));
+                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], r), big);
                 const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2), tg = 2 * g.nblocks - 1;
                 const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : tg);
                 top.i1 = (n1 != o1) ? tg : top.i1;

@@ -285,6 +285,7 @@ def test_n_external_buffers(B, oracle, kernel, tune, k, d, W, b, E, steps, buffe
     (1, 0, 10, 10, 6, 100, 2, 13, 1, 2, True, 0.0),
     (1, 0, 7, 5, 5, 64, 1, 9, 3, 7, True, 0.3),          # one row per message
     (1, 0, 12, 9, 6, 50, 3, 14, 2, 5, False, 0.0),
+    (1, 0, 6, 70, 4, 50, 2, 7, 2, 3, True, 0.0),         # rows longer than a wave
     (3, 2, 40, 20, 12, 100, 2, 17, 1, 4, True, 0.0),     # four waves, one launch
     (3, 2, 40, 20, 12, 100, 1, 12, 3, 3, True, 0.4),
     (3, 6, 40, 20, 12, 100, 2, 17, 2, 8, False, 0.0),    # four waves, one launch per round
