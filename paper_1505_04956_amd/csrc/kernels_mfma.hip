@@ -38,7 +38,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Waves per workgroup is a template parameter NWV (8 or 4): a tile has 32 samples per wave.
 constexpr int WB = 64;           // centroid rows per block (2 matrix tiles of 32)
-constexpr int RB = 4;            // rows per wave and iteration in the row passes (loads in flight)
+constexpr int RB = 8;            // rows per wave and iteration in the row passes (loads in flight)
 constexpr int GS = 16;           // sample rows in flight per wave in the gather (small clusters)
 constexpr int GU = 16;           // sample rows in flight per half-wave in the gather (large clusters)
 constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the nearest
