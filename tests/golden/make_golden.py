@@ -1,6 +1,7 @@
 #!/usr/bin/env python3
 """Writes tests/golden/cfg0_oracle.json: what the CPU oracle computes on the tiny workload
-(N = 1e5, d = 10, k = 10, W = 4, b = 500, E = 4, 5 epochs, deterministic mode, seeds 1234 / 1).
+(N = 1e5, d = 10, k = 10, W = 4, b = 500, E = 4, 5 epochs, deterministic mode, seeds 1234 / 1; and three epochs
+with N external buffers and / or partial messages).
 Calls only the oracle and the seeded input generator.  The paper prints no worked numbers for the
 method (Sec. 5.4 reports curves on its own data), so these stored values are a regression pin of
 the oracle itself and expected values for the GPU path; run from the repository root:
@@ -28,8 +29,19 @@ def compute():
     for _ in range(wl.epochs):
         o.run_epochs(1)
         qe.append(o.quant_error(0))
+    variants = {}
+    for name, kw in (("buffers2", dict(buffers=2)), ("parts2", dict(parts=2)), ("buffers3_parts5", dict(buffers=3, parts=5))):
+        v = asgd_oracle.OracleASGD(X, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed, **kw)
+        v.run_epochs(3)
+        variants[name] = {
+            "options": kw,
+            "quant_error_worker0": v.quant_error(0),
+            "counters_sent_received_accepted": v.counters.sum(0).tolist(),
+            "state_sum_by_worker": v.w.reshape(wl.W, -1).sum(1).tolist(),
+        }
     return {
         "workload": wl.name,
+        "variants_after_3_epochs": variants,
         "quant_error_worker0_by_epoch": qe,
         "quant_error_mean_state": asgd_oracle.quant_error(X, o.w.mean(0)),
         "counters_sent_received_accepted": o.counters.sum(0).tolist(),

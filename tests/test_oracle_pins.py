@@ -615,6 +615,12 @@ def test_stored_values_of_tiny_workload(oracle):
     assert abs(now["quant_error_mean_state"] - stored["quant_error_mean_state"]) <= 1e-12 * stored["quant_error_mean_state"]
     qe = stored["quant_error_worker0_by_epoch"]
     assert all(b < a for a, b in zip(qe, qe[1:]))          # Eq. 8 falls epoch by epoch on this workload
+    assert set(now["variants_after_3_epochs"]) == set(stored["variants_after_3_epochs"])
+    for name, sv in stored["variants_after_3_epochs"].items():
+        nv = now["variants_after_3_epochs"][name]
+        assert nv["counters_sent_received_accepted"] == sv["counters_sent_received_accepted"], name
+        assert np.allclose(nv["state_sum_by_worker"], sv["state_sum_by_worker"], rtol=1e-12, atol=0), name
+        assert abs(nv["quant_error_worker0"] - sv["quant_error_worker0"]) <= 1e-12 * sv["quant_error_worker0"], name
 
 
 def test_centre_error_convergence_of_tiny_workload(oracle):

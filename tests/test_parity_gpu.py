@@ -380,6 +380,14 @@ def test_stored_values_of_tiny_workload(B):
         assert np.allclose(w.reshape(wl.W, -1).sum(1), stored["state_sum_by_worker"], rtol=TOL)
         assert abs(g.quant_error(-1) - stored["quant_error_mean_state"]) <= TOL * stored["quant_error_mean_state"]
         assert [B.asgd_schedule_peer(wl.schedule_seed, 0, i, wl.W) for i in range(wl.W)] == stored["peers_round0"]
+    for name, sv in stored["variants_after_3_epochs"].items():       # N external buffers, partial messages
+        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, **sv["options"])
+        g.load_shards(to_dev(X))
+        g.run_epochs(3)
+        st = g.stats()
+        assert [st.sent, st.received, st.accepted] == sv["counters_sent_received_accepted"], name
+        assert np.allclose(g.get_state().reshape(wl.W, -1).sum(1), sv["state_sum_by_worker"], rtol=TOL), name
+        assert abs(g.quant_error(0) - sv["quant_error_worker0"]) <= TOL * sv["quant_error_worker0"], name
 
 
 @pytest.mark.parametrize("kernel,k,d,W,b,E", [
