@@ -76,8 +76,7 @@ enum {
                                     non-empty buffer takes part (Eq. 3).  Needs N < W at run time
                                     (ASGD_EINVAL otherwise); may only be set before the first step
                                     (ASGD_ESTATE after); reallocates the exchange buffers (2 * N * W states).
-                                    N > 1 is not available in the small-state kernel (ASGD_KERNEL_AUTO then
-                                    picks another one). */
+                                    Available in all three kernels. */
     ASGD_OPT_PARTS = 11          /* partial messages (Sec. 4.4, partitioned along the cluster centres):
                                     P in 1 .. k, default 1 = whole states.  With P > 1 part q is the set of
                                     centroid rows c with c mod P = q, and copy n of the message of round r

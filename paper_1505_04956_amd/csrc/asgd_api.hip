@@ -347,7 +347,8 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 
     int kernel = ctx->kernel_opt;
     if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
-    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->nb == 1 && ctx->parts == 1;
+    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->parts == 1 &&
+                          (ctx->nb == 1 || ((ctx->tune >> 2) & 3) != 1);      // several buffers: not in the private-rows shape
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
     if (kernel == ASGD_KERNEL_AUTO) {
         // the matrix-core kernel pays off once the k x d contraction dominates a step

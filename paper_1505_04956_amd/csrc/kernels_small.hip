@@ -175,7 +175,8 @@ __device__ __forceinline__ bool wait_flag(const int *flag, int want, bool at_lea
 // State layout in registers ("task layout"): lane l < NT = K*NQ holds the four elements
 // (c, 4q .. 4q+3) of the state with c = l / NQ, q = l % NQ (elements past d do not exist and stay 0);
 // the same lane sums float4 column (c, q) of the accumulator rows once per step.
-template <int K, int D, int PF, int NW, int RS>
+//   NB   external buffers per worker = recipients per message (Eq. 3 / Eq. 6); NB = p.nb
+template <int K, int D, int PF, int NW, int RS, int NB>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(RS, RS)))
 void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 {
@@ -359,22 +360,36 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && te == 0);
             const bool send_point = (p.E > 0 && p.W > 1 && te + 1 == p.E);
             const int rpar = det ? (int)((round - 1) & 1) : 0;
-            const unsigned long long *mslot =
-                reinterpret_cast<const unsigned long long *>(p.slot) + (((size_t)rpar * p.W + i) * NT + (has_task ? lane : 0)) * 4;
-            unsigned long long mp[4] = {0ull, 0ull, 0ull, 0ull};
-            if (merge_point) {
+            // buffer n of this worker (parity rpar): NT lanes x 4 pairs each; copy n of a message goes to buffer n
+            const unsigned long long *mslot[NB];
+            unsigned long long mp[NB][4];
 #pragma unroll
-                for (int c4 = 0; c4 < 4; ++c4) mp[c4] = load_pair(mslot + c4);
+            for (int n = 0; n < NB; ++n) {
+                mslot[n] = reinterpret_cast<const unsigned long long *>(p.slot) +
+                           (((size_t)(rpar * NB + n) * p.W + i) * NT + (has_task ? lane : 0)) * 4;
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4) mp[n][c4] = merge_point ? load_pair(mslot[n] + c4) : 0ull;
             }
-            int peer = 0, ackv = 0;
-            if (send_point && wave == 0) {
-                if (det) {
-                    // (the shifts of the rounds of this launch come from a table: no 64-bit division in here)
-                    peer = i + p.shift_tab[round - p.shift_r0];
-                    if (peer >= p.W) peer -= p.W;
-                    if (sync && round >= 2) ackv = __hip_atomic_load(p.consumed + peer, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } else {
-                    peer = peer_free(p.seed, round, i, p.W);
+            // cyclic shift of copy n in round r: 1 + (shift of copy 0 - 1 + n) mod (W - 1)
+            auto shift_of = [&](long long r, int n) -> int {
+                int sh = p.shift_tab[r - p.shift_r0] + n;
+                if (sh > p.W - 1) sh -= p.W - 1;
+                return sh;
+            };
+            int peer[NB], ackv[NB];
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                peer[n] = 0; ackv[n] = 0;
+                if (send_point && wave == 0) {
+                    if (det) {
+                        // (the shifts of the rounds of this launch come from a table: no 64-bit division in here)
+                        peer[n] = i + shift_of(round, n);
+                        if (peer[n] >= p.W) peer[n] -= p.W;
+                        if (sync && round >= 2)
+                            ackv[n] = __hip_atomic_load(p.consumed + peer[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        peer[n] = peer_free(p.seed, round, i, p.W, n);
+                    }
                 }
             }
 
@@ -563,94 +578,117 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             parity ^= 1;
 
             // ---- merge point? (a buffer is looked at once, at the first step of a round) ----
-            bool has_ext = false;
-            if (merge_point) {
-                // complete = every pair of every task lane carries the stamp of round-1 (free-running: any stamp)
-                auto complete = [&]() -> bool {
-                    bool ok = true;
+            bool has_ext[NB];
 #pragma unroll
-                    for (int c4 = 0; c4 < 4; ++c4) {
-                        const int st = (int)(mp[c4] >> 32);
-                        ok = ok && (det ? st == (int)(round - 1) : st >= 0);
-                    }
-                    return __ballot(has_task && !ok) == 0ull;
-                };
-                has_ext = complete();
-                if (!has_ext && sync && det && !wait_failed) {
-                    // not there yet: wait for the sender of round-1 under the cyclic-shift schedule, unless its
-                    // message is one of those the loss hook drops
-                    int sender = i - p.shift_tab[round - 1 - p.shift_r0];
-                    if (sender < 0) sender += p.W;
-                    if (!(p.drop_thr != 0 && message_dropped(p.seed, round - 1, sender, p.drop_thr))) {
-                        for (int spin = 0; spin < (1 << 18) && !has_ext; ++spin) {
-                            __builtin_amdgcn_s_sleep(4);
+            for (int n = 0; n < NB; ++n) {
+                has_ext[n] = false;
+                if (merge_point) {
+                    // complete = every pair of every task lane carries the stamp of round-1 (free-running: any stamp)
+                    auto complete = [&]() -> bool {
+                        bool ok = true;
 #pragma unroll
-                            for (int c4 = 0; c4 < 4; ++c4) mp[c4] = load_pair(mslot + c4);
-                            has_ext = complete();
+                        for (int c4 = 0; c4 < 4; ++c4) {
+                            const int st = (int)(mp[n][c4] >> 32);
+                            ok = ok && (det ? st == (int)(round - 1) : st >= 0);
                         }
-                        if (!has_ext) wait_failed = 1;
+                        return __ballot(has_task && !ok) == 0ull;
+                    };
+                    has_ext[n] = complete();
+                    if (!has_ext[n] && sync && det && !wait_failed) {
+                        // not there yet: wait for the sender of round-1 under the cyclic-shift schedule, unless its
+                        // message is one of those the loss hook drops
+                        int sender = i - shift_of(round - 1, n);
+                        if (sender < 0) sender += p.W;
+                        if (!(p.drop_thr != 0 && message_dropped(p.seed, round - 1, sender, p.drop_thr, n))) {
+                            for (int spin = 0; spin < (1 << 18) && !has_ext[n]; ++spin) {
+                                __builtin_amdgcn_s_sleep(4);
+#pragma unroll
+                                for (int c4 = 0; c4 < 4; ++c4) mp[n][c4] = load_pair(mslot[n] + c4);
+                                has_ext[n] = complete();
+                            }
+                            if (!has_ext[n]) wait_failed = 1;
+                        }
                     }
                 }
             }
-            float G[4], we[4];
-            double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+            float G[4], wesum[4];
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 G[c4] = tv[c4] ? (cnt * w4[c4] - S4[c4]) * inv_b : 0.0f;      // descent gradient of Eq. 9
-                we[c4] = 0.0f;
-                if (has_ext && tv[c4]) {
-                    we[c4] = __uint_as_float((unsigned)(mp[c4] & 0xFFFFFFFFull));
-                    const double wed = (double)we[c4];
-                    const double a = ((double)w4[c4] - (double)p.eps * (double)G[c4]) - wed;
-                    const double c2 = (double)w4[c4] - wed;
-                    lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
-                }
+                wesum[c4] = 0.0f;
             }
-            int delta = 0;
-            if (has_ext) {           // uniform over the workgroup
-                lhs = wave_sum(lhs); rhs = wave_sum(rhs); nrm = wave_sum(nrm);
-                if (nrm > 0.0) {     // lambda of Eq. 3: an all-zero buffer is empty
-                    delta = p.parzen ? (lhs < rhs) : 1;       // Eq. 4
-                    if (threadIdx.x == 0) {
-                        long long *cn = p.counters + (size_t)i * CNT_STRIDE;
-                        cn[CNT_RECEIVED] += 1;
-                        cn[CNT_ACCEPTED] += delta;
-                        if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) cn[CNT_PARZEN_NEAR] += 1;
+            int ndelta = 0;
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                if (has_ext[n]) {           // uniform over the workgroup
+                    float we[4];
+                    double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        we[c4] = 0.0f;
+                        if (tv[c4]) {
+                            we[c4] = __uint_as_float((unsigned)(mp[n][c4] & 0xFFFFFFFFull));
+                            const double wed = (double)we[c4];
+                            const double a = ((double)w4[c4] - (double)p.eps * (double)G[c4]) - wed;
+                            const double c2 = (double)w4[c4] - wed;
+                            lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
+                        }
+                    }
+                    lhs = wave_sum(lhs); rhs = wave_sum(rhs); nrm = wave_sum(nrm);
+                    if (nrm > 0.0) {     // lambda of Eq. 3: an all-zero buffer is empty
+                        const int delta = p.parzen ? (lhs < rhs) : 1;       // Eq. 4, every buffer on its own (Eq. 6)
+                        if (delta) {
+                            ndelta += 1;
+#pragma unroll
+                            for (int c4 = 0; c4 < 4; ++c4) wesum[c4] += we[c4];
+                        }
+                        if (threadIdx.x == 0) {
+                            long long *cn = p.counters + (size_t)i * CNT_STRIDE;
+                            cn[CNT_RECEIVED] += 1;
+                            cn[CNT_ACCEPTED] += delta;
+                            if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) cn[CNT_PARZEN_NEAR] += 1;
+                        }
                     }
                 }
             }
-            // Eq. 7 and Alg. 5 line 8
+            // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
+            const float inv_n = NB == 1 ? 0.5f : 1.0f / (float)(ndelta + 1);
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 float step = G[c4];
-                if (delta) step += w4[c4] - 0.5f * (w4[c4] + we[c4]);
+                if (ndelta) step += w4[c4] - inv_n * (w4[c4] + wesum[c4]);
                 w4[c4] = w4[c4] - p.eps * step;
             }
             if (merge_point) {
-                // every wave has read the buffer (the values were used above): tell senders of later rounds so.
-                // Deterministic mode: the stamps in the buffer never match again, which empties it.  Free-running
+                // every wave has read the buffers (the values were used above): tell senders of later rounds so.
+                // Deterministic mode: the stamps in a buffer never match again, which empties it.  Free-running
                 // mode: a message is used once, so it is marked empty.
                 if constexpr (NW > 1) __syncthreads();
                 if (threadIdx.x == 0)
                     __hip_atomic_store(p.consumed + i, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (!det && has_ext && wave == 0 && has_task) {
 #pragma unroll
-                    for (int c4 = 0; c4 < 4; ++c4)
-                        store_pair(const_cast<unsigned long long *>(mslot) + c4, ~0ull);
+                for (int n = 0; n < NB; ++n) {
+                    if (!det && has_ext[n] && wave == 0 && has_task) {
+#pragma unroll
+                        for (int c4 = 0; c4 < 4; ++c4)
+                            store_pair(const_cast<unsigned long long *>(mslot[n]) + c4, ~0ull);
+                    }
                 }
             }
 
             // ---- send (Alg. 5 line 9): the first wave writes ----
             if (send_point && wave == 0) {
-                if (!(p.drop_thr != 0 && message_dropped(p.seed, round, i, p.drop_thr))) {
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    if (p.drop_thr != 0 && message_dropped(p.seed, round, i, p.drop_thr, n)) continue;
                     const int spar = det ? (int)(round & 1) : 0;
-                    if (sync && det && round >= 2 && !wait_failed && ackv < (int)(round - 1)) {
+                    if (sync && det && round >= 2 && !wait_failed && ackv[n] < (int)(round - 1)) {
                         // the buffer still holds the message of round-2 until the recipient has passed
                         // the merge point of round-1 (it had not when this step began: look again)
-                        if (!wait_flag(p.consumed + peer, (int)(round - 1), true)) wait_failed = 1;
+                        if (!wait_flag(p.consumed + peer[n], (int)(round - 1), true)) wait_failed = 1;
                     }
-                    unsigned long long *dst =
-                        reinterpret_cast<unsigned long long *>(p.slot) + (((size_t)spar * p.W + peer) * NT + (has_task ? lane : 0)) * 4;
+                    unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.slot) +
+                                              (((size_t)(spar * NB + n) * p.W + peer[n]) * NT + (has_task ? lane : 0)) * 4;
                     if (has_task) {
 #pragma unroll
                         for (int c4 = 0; c4 < 4; ++c4) store_pair(dst + c4, pack_pair(w4[c4], (int)round));
@@ -687,10 +725,10 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     if (lane == 0 && wait_failed) atomicOr(p.error_flag, 1);
 }
 
-template <int K, int D, int PF, int NW, int RS>
-hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
+template <int K, int D, int PF, int NW, int RS, int NB>
+hipError_t launch_variant_nb(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
-    auto kern = small_steps_kernel<K, D, PF, NW, RS>;
+    auto kern = small_steps_kernel<K, D, PF, NW, RS, NB>;
     if (!persistent) {
         hipLaunchKernelGGL(kern, dim3(p.W), dim3(64 * NW), 0, s, p, t0, t1, 0);
         return hipGetLastError();
@@ -719,6 +757,24 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipSt
     if (p.cooperative) return hipLaunchCooperativeKernel((const void *)kern, dim3(grid), dim3(64 * NW), args, 0, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), 0, s, pp, a0, a1, sync);
     return hipGetLastError();
+}
+
+// Several buffers: the message pairs of all buffers sit in registers during a step, so the ring depth is at most 4, and
+// 2 for four buffers (measured on the streaming workload: 1.22 ms against 1.38 ms with depth 4 and register spills;
+// three buffers: 1.10 ms with depth 4 and a few spills against 1.15 ms with depth 2); the caller limits it.  Only the
+// shapes with shared rows are built.
+template <int K, int D, int PF, int NW, int RS>
+hipError_t launch_variant(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
+{
+    if (p.nb == 1) return launch_variant_nb<K, D, PF, NW, RS, 1>(p, t0, t1, s, persistent);
+    if constexpr (PF <= 4 && RS == 2) {
+        if (p.nb == 2) return launch_variant_nb<K, D, PF, NW, RS, 2>(p, t0, t1, s, persistent);
+        if (p.nb == 3) return launch_variant_nb<K, D, PF, NW, RS, 3>(p, t0, t1, s, persistent);
+    }
+    if constexpr (PF == 2 && RS == 2) {
+        if (p.nb == 4) return launch_variant_nb<K, D, PF, NW, RS, 4>(p, t0, t1, s, persistent);
+    }
+    return hipErrorInvalidValue;
 }
 
 template <int NW, int RS>
@@ -833,6 +889,7 @@ hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, h
     int pf = (ngw % 8 == 0) ? 8 : (ngw % 4 == 0) ? 4 : 2;
     if ((p.tune & 3) == 1 && pf > 4) pf = 4;
     if ((p.tune & 3) == 2 && pf > 2) pf = 2;
+    if (p.nb >= 4 && pf > 2) pf = 2;        // registers: see launch_variant
     switch (shape) {
         case 1: return launch_shape<1, 1>(p, t0, t1, s, persistent, pf);
         case 2: return launch_shape<1, 2>(p, t0, t1, s, persistent, pf);

@@ -261,7 +261,12 @@ def test_matrix_core_kernel_one_launch(B, oracle, tune):
 
 
 @pytest.mark.parametrize("kernel,tune,k,d,W,b,E,steps,buffers,parzen,drop", [
-    (1, 0, 10, 10, 6, 100, 2, 13, 2, True, 0.0),        # the small-state shape falls to the generic kernel
+    (1, 0, 10, 10, 6, 100, 2, 13, 2, True, 0.0),        # generic kernel
+    (2, 0, 10, 10, 6, 100, 2, 13, 2, True, 0.0),        # small-state kernel, two waves per worker, one launch
+    (2, 0, 10, 10, 9, 500, 1, 12, 4, True, 0.3),
+    (2, 0, 10, 10, 7, 130, 3, 14, 3, False, 0.0),
+    (2, 8, 10, 10, 6, 100, 2, 13, 2, True, 0.2),        # one wave per worker, shared rows
+    (2, 3, 10, 10, 6, 256, 2, 13, 4, True, 0.0),        # one launch per round
     (1, 0, 7, 5, 5, 64, 1, 9, 4, True, 0.3),
     (1, 0, 12, 9, 6, 50, 3, 14, 3, False, 0.0),
     (3, 2, 40, 20, 12, 100, 2, 17, 2, True, 0.0),       # four waves, one launch
@@ -333,11 +338,9 @@ def test_n_external_buffers_options(B, oracle):
     X = make_data(6 * 1500, 10, 10, seed=33)
     Xg = to_dev(X)
     auto = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=2); auto.load_shards(Xg); auto.run_steps(5)
-    assert auto.stats().kernel == B.KERNEL_GENERIC              # the small-state kernel has one buffer
+    assert auto.stats().kernel == B.KERNEL_SMALL and auto.stats().launches == 1
     with pytest.raises(B.AsgdError):
         auto.set_option(B.OPT_BUFFERS, 3)                       # not after the first step
-    with pytest.raises(B.AsgdError):
-        small = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=2, kernel=B.KERNEL_SMALL); small.load_shards(Xg); small.run_steps(1)
     with pytest.raises(B.AsgdError):
         many = B.ASGD(10, 10, 3, 100, 0.05, E=2, buffers=3); many.load_shards(Xg); many.run_steps(1)   # needs N < W
     with pytest.raises(B.AsgdError):
@@ -349,7 +352,10 @@ def test_n_external_buffers_options(B, oracle):
     e = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3); e.load_shards(Xg); e.run_steps(9)
     f = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3); f.load_shards(Xg); f.run_steps(4); f.run_steps(5)
     assert np.array_equal(e.get_state(), f.get_state())
-    assert e.stats().sent == 6 * 4 and e.stats().received == 6 * 4 * 3
+    assert e.stats().sent == 6 * 4 and e.stats().received == 6 * 4 * 3 and e.stats().kernel == B.KERNEL_SMALL
+    # free-running mode of the small-state kernel with three buffers
+    fs = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3, mode=B.MODE_FREE_RUNNING); fs.load_shards(Xg); fs.run_steps(15)
+    assert np.all(np.isfinite(fs.get_state())) and fs.stats().sent == 6 * 7 and 0 < fs.stats().received <= 3 * fs.stats().sent
     # free-running mode: no element-wise parity; finite, every worker sends, some messages arrive
     fr = B.ASGD(40, 20, 12, 100, 0.05, E=2, buffers=3, mode=B.MODE_FREE_RUNNING, kernel=3)
     Xm = to_dev(make_data(12 * 1500, 20, 40, seed=34))
