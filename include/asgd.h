@@ -86,7 +86,7 @@ enum {
                                     buffers' accepted copies of the same row; rows that did not travel take
                                     the plain step.  "received" then counts buffers with a non-empty row,
                                     "accepted" buffers with an accepted row.  May only be set before the
-                                    first step (ASGD_ESTATE after); not available in the small-state kernel. */
+                                    first step (ASGD_ESTATE after).  Available in all three kernels. */
 };
 enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
 enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };

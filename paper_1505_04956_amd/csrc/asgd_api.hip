@@ -48,6 +48,7 @@ struct asgd_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     double last_ms = 0.0;
     int last_kernel = 0, last_launches = 0;
+    int fill_kernel = 0;        // kernel whose message format the exchange buffers were last emptied for
     int hip_err = 0;
 };
 
@@ -91,14 +92,15 @@ StepParams make_params(const asgd_ctx *c)
     return p;
 }
 
-int clear_exchange(asgd_ctx *c)
+// Empties the exchange buffers for the kernel that is going to use them.  Small-state kernel: all bits set = stamp -1
+// inside its (value, stamp) pairs.  The other kernels look at `stamp` before they read a buffer; with partial messages
+// rows of a buffer stay unwritten, which a free-running recipient may look at: those start as zeros = empty rows.
+int clear_exchange(asgd_ctx *c, int kernel)
 {
-    // all bits set: empty in both message formats (stamp -1 inside the small-state kernel's pairs; the other
-    // kernels look at `stamp` before they read a buffer).  Partial messages leave rows of a buffer unwritten, which a
-    // free-running recipient may look at: those start as zeros (an empty row), and the small-state kernel is not
-    // used with them.
-    HIP_TRY(c, hipMemsetAsync(c->slot, c->parts > 1 ? 0 : 0xFF, c->slot_bytes, c->stream));
+    const int fill = (c->parts > 1 && kernel != ASGD_KERNEL_SMALL) ? 0 : 0xFF;
+    HIP_TRY(c, hipMemsetAsync(c->slot, fill, c->slot_bytes, c->stream));
     HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->nb * c->W * sizeof(int), c->stream));   // -1
+    c->fill_kernel = kernel;
     return ASGD_OK;
 }
 
@@ -252,16 +254,13 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
             ctx->stamp = stamp;
             ctx->slot_bytes = (size_t)nb * ctx->slot_bytes_one;
             ctx->nb = nb;
-            return clear_exchange(ctx);
+            return clear_exchange(ctx, ASGD_KERNEL_SMALL);
         }
         case ASGD_OPT_PARTS:
             if (value < 1 || value > ctx->k || value != floor(value)) return ASGD_EINVAL;
             if (ctx->t != 0) return ASGD_ESTATE;
             ctx->parts = (int)value;
-            if (ctx->loaded) {
-                HIP_TRY(ctx, hipSetDevice(ctx->device));
-                return clear_exchange(ctx);
-            }
+            ctx->fill_kernel = 0;          // the first run empties the buffers for its kernel
             return ASGD_OK;
         case ASGD_OPT_TUNE:
             if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
@@ -286,8 +285,9 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->xnorm2max_valid = false;
     StepParams p = make_params(ctx);
     HIP_TRY(ctx, launch_init_first_k(p, ctx->stream));
-    int rc = clear_exchange(ctx);
+    int rc = clear_exchange(ctx, ASGD_KERNEL_SMALL);
     if (rc != ASGD_OK) return rc;
+    ctx->fill_kernel = 0;
     HIP_TRY(ctx, hipMemsetAsync(ctx->ncum, 0, (size_t)ctx->W * ctx->k * sizeof(long long), ctx->stream));
     HIP_TRY(ctx, hipMemsetAsync(ctx->counters, 0, (size_t)ctx->W * CNT_STRIDE * sizeof(long long), ctx->stream));
     HIP_TRY(ctx, hipMemsetAsync(ctx->error_flag, 0, sizeof(int), ctx->stream));
@@ -323,8 +323,9 @@ int asgd_set_step(asgd_ctx *ctx, int64_t t)
     if (!ctx->loaded) return ASGD_ESTATE;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     ctx->t = t;
-    int rc = clear_exchange(ctx);
+    int rc = clear_exchange(ctx, ASGD_KERNEL_SMALL);
     if (rc != ASGD_OK) return rc;
+    ctx->fill_kernel = 0;
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return ASGD_OK;
 }
@@ -347,7 +348,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 
     int kernel = ctx->kernel_opt;
     if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
-    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST && ctx->parts == 1 &&
+    const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST &&
                           (ctx->nb == 1 || ((ctx->tune >> 2) & 3) != 1);      // several buffers: not in the private-rows shape
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
     if (kernel == ASGD_KERNEL_AUTO) {
@@ -369,6 +370,13 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     if (ctx->last_kernel != 0 && kernel != ctx->last_kernel && ctx->E > 0 && ctx->W > 1 && ctx->t > 0 &&
         ctx->t % ctx->E == 0)
         return ASGD_ESTATE;
+
+    // Partial messages: the fill of the never-written rows of the exchange buffers depends on the kernel's message
+    // format.  (No message is in flight here: the check above, and the first run after load / set_step.)
+    if (ctx->parts > 1 && ctx->fill_kernel != kernel) {
+        const int rc = clear_exchange(ctx, kernel);
+        if (rc != ASGD_OK) return rc;
+    }
 
     StepParams p = make_params(ctx);
     const long long t_end = ctx->t + steps;

@@ -578,18 +578,27 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             parity ^= 1;
 
             // ---- merge point? (a buffer is looked at once, at the first step of a round) ----
-            bool has_ext[NB];
+            bool has_ext[NB], in_part[NB];
 #pragma unroll
             for (int n = 0; n < NB; ++n) {
                 has_ext[n] = false;
+                in_part[n] = has_task;
                 if (merge_point) {
-                    // complete = every pair of every task lane carries the stamp of round-1 (free-running: any stamp)
+                    // complete = every pair of every task lane carries the stamp of round-1 (free-running: any stamp).
+                    // Partial messages: only the lanes whose centroid row belongs to the part that this copy carries
+                    // (free-running mode: the part follows from the round in the lane's own first stamp).
                     auto complete = [&]() -> bool {
                         bool ok = true;
 #pragma unroll
                         for (int c4 = 0; c4 < 4; ++c4) {
                             const int st = (int)(mp[n][c4] >> 32);
                             ok = ok && (det ? st == (int)(round - 1) : st >= 0);
+                        }
+                        if (p.parts > 1) {
+                            const int mr = det ? (int)(round - 1) : (int)(mp[n][0] >> 32);
+                            in_part[n] = has_task && mr >= 0 && tc % p.parts == (mr + i + n) % p.parts;
+                            if (!det) return __ballot(in_part[n] && ok) != 0ull;      // some row is there
+                            return __ballot(in_part[n] && !ok) == 0ull;
                         }
                         return __ballot(has_task && !ok) == 0ull;
                     };
@@ -618,9 +627,61 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 wesum[c4] = 0.0f;
             }
             int ndelta = 0;
+            if (p.parts > 1) {
+                // Partial messages (Sec. 4.4): lambda, Eq. 4 and Eq. 6 per centroid row.  A row is spread over the NQ
+                // task lanes NQ*c .. NQ*c + NQ - 1; their partial sums are added with lane reads.  ndelta counts,
+                // per lane, the accepted copies of ITS row.
+                int nz = 0, accb = 0, near = 0;
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    if (!has_ext[n]) continue;          // uniform
+                    float we[4];
+                    double lhs = 0.0, rhs = 0.0, nrm = 0.0;
+                    bool okl = in_part[n];
+                    if (!det) {
+#pragma unroll
+                        for (int c4 = 0; c4 < 4; ++c4) okl = okl && (int)(mp[n][c4] >> 32) >= 0;
+                    }
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        we[c4] = 0.0f;
+                        if (okl && tv[c4]) {
+                            we[c4] = __uint_as_float((unsigned)(mp[n][c4] & 0xFFFFFFFFull));
+                            const double wed = (double)we[c4];
+                            const double a = ((double)w4[c4] - (double)p.eps * (double)G[c4]) - wed;
+                            const double c2 = (double)w4[c4] - wed;
+                            lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
+                        }
+                    }
+                    double l3 = 0.0, r3 = 0.0, n3 = 0.0;
+                    int all3 = 1;
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) {
+                        const int src = tc * NQ + q;
+                        l3 += __shfl(lhs, src, 64); r3 += __shfl(rhs, src, 64); n3 += __shfl(nrm, src, 64);
+                        all3 &= __shfl((int)okl, src, 64);
+                    }
+                    const bool rowok = has_task && all3 && n3 > 0.0;       // every lane of the row is there; lambda
+                    const bool acc = rowok && (p.parzen ? (l3 < r3) : true);
+                    if (acc) {
+                        ndelta += 1;
+#pragma unroll
+                        for (int c4 = 0; c4 < 4; ++c4) wesum[c4] += we[c4];
+                    }
+                    if (__ballot(rowok) != 0ull) nz |= 1 << n;
+                    if (__ballot(acc) != 0ull) accb |= 1 << n;
+                    if (__ballot(rowok && r3 > 0.0 && fabs(l3 - r3) / r3 < 1e-6) != 0ull) near = 1;
+                }
+                if (threadIdx.x == 0 && nz) {
+                    long long *cn = p.counters + (size_t)i * CNT_STRIDE;
+                    cn[CNT_RECEIVED] += __builtin_popcount(nz);
+                    cn[CNT_ACCEPTED] += __builtin_popcount(accb);
+                    cn[CNT_PARZEN_NEAR] += near;
+                }
+            }
 #pragma unroll
             for (int n = 0; n < NB; ++n) {
-                if (has_ext[n]) {           // uniform over the workgroup
+                if (has_ext[n] && p.parts == 1) {           // uniform over the workgroup
                     float we[4];
                     double lhs = 0.0, rhs = 0.0, nrm = 0.0;
 #pragma unroll
@@ -652,7 +713,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 }
             }
             // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
-            const float inv_n = NB == 1 ? 0.5f : 1.0f / (float)(ndelta + 1);
+            const float inv_n = (NB == 1 && p.parts == 1) ? 0.5f : 1.0f / (float)(ndelta + 1);
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 float step = G[c4];
@@ -668,7 +729,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     __hip_atomic_store(p.consumed + i, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
-                    if (!det && has_ext[n] && wave == 0 && has_task) {
+                    if (!det && has_ext[n] && wave == 0 && has_task && in_part[n]) {
 #pragma unroll
                         for (int c4 = 0; c4 < 4; ++c4)
                             store_pair(const_cast<unsigned long long *>(mslot[n]) + c4, ~0ull);
@@ -689,7 +750,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     }
                     unsigned long long *dst = reinterpret_cast<unsigned long long *>(p.slot) +
                                               (((size_t)(spar * NB + n) * p.W + peer[n]) * NT + (has_task ? lane : 0)) * 4;
-                    if (has_task) {
+                    if (has_task && (p.parts == 1 || tc % p.parts == (int)((round + peer[n] + n) % p.parts))) {
 #pragma unroll
                         for (int c4 = 0; c4 < 4; ++c4) store_pair(dst + c4, pack_pair(w4[c4], (int)round));
                     }

@@ -288,6 +288,11 @@ def test_n_external_buffers(B, oracle, kernel, tune, k, d, W, b, E, steps, buffe
 
 @pytest.mark.parametrize("kernel,tune,k,d,W,b,E,steps,buffers,parts,parzen,drop", [
     (1, 0, 10, 10, 6, 100, 2, 13, 1, 2, True, 0.0),
+    (2, 0, 10, 10, 6, 100, 2, 13, 1, 2, True, 0.0),      # small-state kernel, two waves per worker, one launch
+    (2, 0, 10, 10, 9, 500, 1, 12, 3, 10, True, 0.3),     # one row per message
+    (2, 0, 10, 10, 7, 130, 3, 14, 2, 3, False, 0.0),
+    (2, 8, 10, 10, 6, 100, 2, 13, 4, 5, True, 0.2),      # one wave per worker, shared rows
+    (2, 3, 10, 10, 6, 256, 2, 13, 2, 4, True, 0.0),      # one launch per round
     (1, 0, 7, 5, 5, 64, 1, 9, 3, 7, True, 0.3),          # one row per message
     (1, 0, 12, 9, 6, 50, 3, 14, 2, 5, False, 0.0),
     (1, 0, 6, 70, 4, 50, 2, 7, 2, 3, True, 0.0),         # rows longer than a wave
@@ -311,14 +316,15 @@ def test_partial_messages_options(B):
     X = make_data(6 * 1500, 10, 10, seed=33)
     Xg = to_dev(X)
     auto = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=2); auto.load_shards(Xg); auto.run_steps(5)
-    assert auto.stats().kernel == B.KERNEL_GENERIC              # the small-state kernel sends whole states
+    assert auto.stats().kernel == B.KERNEL_SMALL and auto.stats().launches == 1
     with pytest.raises(B.AsgdError):
         auto.set_option(B.OPT_PARTS, 5)                         # not after the first step
     for bad in (0, 11, 2.5):
         with pytest.raises(B.AsgdError):
             B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=bad)
-    with pytest.raises(B.AsgdError):
-        small = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=2, kernel=B.KERNEL_SMALL); small.load_shards(Xg); small.run_steps(1)
+    # free-running mode of the small-state kernel with partial messages: finite, every worker sends, rows arrive
+    fs = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=2, parts=5, mode=B.MODE_FREE_RUNNING); fs.load_shards(Xg); fs.run_steps(15)
+    assert np.all(np.isfinite(fs.get_state())) and fs.stats().sent == 6 * 7 and 0 < fs.stats().received <= 2 * fs.stats().sent
     # one part set explicitly is the default
     a = B.ASGD(10, 10, 6, 100, 0.05, E=2, parts=1); a.load_shards(Xg); a.run_steps(9)
     c = B.ASGD(10, 10, 6, 100, 0.05, E=2); c.load_shards(Xg); c.run_steps(9)
