@@ -37,6 +37,9 @@ struct asgd_ctx {
     size_t slot_bytes = 0;         // size of the exchange buffers (both parities, all workers)
     int *shift_tab = nullptr;      // schedule table of the small-state kernel, grown on demand
     long long shift_cap = 0;
+    long long tab_r0 = 0, tab_n = 0;   // rounds [tab_r0, tab_r0 + tab_n) the table holds, for tab_seed and tab_W
+    uint64_t tab_seed = 0;
+    int tab_W = 0;
     bool xnorm2max_valid = false;
     int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
     int *flag_host = nullptr;   // pinned: the error flag is copied here behind the kernels of a run, one wait covers both
@@ -384,18 +387,26 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         // cyclic shifts of the rounds this call touches: the round before the first step up to the last step's
         const long long r_lo = ctx->t / ctx->E > 0 ? ctx->t / ctx->E - 1 : 0;
         const long long r_hi = (t_end - 1) / ctx->E;
-        const long long n = r_hi - r_lo + 1;
-        if (n > (long long)1 << 30) return ASGD_EINVAL;
-        if (n > ctx->shift_cap) {
-            if (ctx->shift_tab) (void)hipFree(ctx->shift_tab);
-            ctx->shift_tab = nullptr;
-            ctx->shift_cap = 0;
-            HIP_TRY(ctx, hipMalloc((void **)&ctx->shift_tab, (size_t)n * sizeof(int)));
-            ctx->shift_cap = n;
+        if (r_hi - r_lo + 1 > (long long)1 << 30) return ASGD_EINVAL;
+        const bool held = ctx->tab_n > 0 && ctx->tab_seed == ctx->seed && ctx->tab_W == ctx->W && r_lo >= ctx->tab_r0 &&
+                          r_hi < ctx->tab_r0 + ctx->tab_n;
+        if (!held) {
+            // some rounds ahead as well, so that a run of many short calls computes the table once in a while
+            long long n = r_hi - r_lo + 1;
+            if (n < 4096) n = 4096;
+            if (n > ctx->shift_cap) {
+                if (ctx->shift_tab) (void)hipFree(ctx->shift_tab);
+                ctx->shift_tab = nullptr;
+                ctx->shift_cap = 0;
+                ctx->tab_n = 0;
+                HIP_TRY(ctx, hipMalloc((void **)&ctx->shift_tab, (size_t)n * sizeof(int)));
+                ctx->shift_cap = n;
+            }
+            HIP_TRY(ctx, launch_schedule_table(ctx->seed, r_lo, (int)n, ctx->W, ctx->shift_tab, ctx->stream));
+            ctx->tab_r0 = r_lo; ctx->tab_n = n; ctx->tab_seed = ctx->seed; ctx->tab_W = ctx->W;
         }
-        HIP_TRY(ctx, launch_schedule_table(ctx->seed, r_lo, (int)n, ctx->W, ctx->shift_tab, ctx->stream));
         p.shift_tab = ctx->shift_tab;
-        p.shift_r0 = r_lo;
+        p.shift_r0 = ctx->tab_r0;
     }
     // Deterministic mode: a worker may only read the message of round r-1 once its sender has
     // finished that round.  Either the whole run is one launch of co-resident workgroups that wait
