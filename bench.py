@@ -85,6 +85,8 @@ def main():
                     help="external buffers per worker = recipients per message (Eq. 3 / Eq. 6); 1 is the metric's")
     ap.add_argument("--parts", type=int, default=1,
                     help="partial messages: a copy carries one of P parts of the centroid rows (Sec. 4.4); 1 is the metric's")
+    ap.add_argument("--mini-batch", type=int, default=0,
+                    help="override the workload's mini-batch size b (sensitivity runs; the workload name gets a suffix)")
     ap.add_argument("--quant-error", action="store_true", help="also report Eq. 8 of worker 0 after the timed epochs")
     ap.add_argument("--plain-launch", action="store_true",
                     help="start the single-launch kernel with a plain launch instead of a cooperative one "
@@ -104,6 +106,8 @@ def main():
     from paper_1505_04956_amd import workloads
 
     wl = workloads.CONFIGS[args.config]
+    if args.mini_batch > 0 and args.mini_batch != wl.b:
+        wl = wl.scaled(b=args.mini_batch, name="%s_b%d" % (wl.name, args.mini_batch))
     torch.cuda.set_device(0)
     X = workloads.generate_device(wl, device="cuda:0")
     torch.cuda.synchronize()
