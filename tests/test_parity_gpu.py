@@ -480,10 +480,12 @@ def test_two_contexts_and_a_side_stream(B, oracle):
     assert a.stats().steps == 15
 
 
-def test_kernel_switch_between_runs(B, oracle):
+@pytest.mark.parametrize("buffers,parts", [(1, 1), (2, 1), (1, 5), (3, 2)])
+def test_kernel_switch_between_runs(B, oracle, buffers, parts):
     # Kernels keep the message in flight in their own format; one is in flight exactly at a merge point.
+    # (With partial messages the never-written rows of the buffers are filled per format: refilled at the switch.)
     X = make_data(24_000, 10, 10, seed=2)
-    g = B.ASGD(10, 10, 6, 200, 0.1, E=2, kernel=2)
+    g = B.ASGD(10, 10, 6, 200, 0.1, E=2, kernel=2, buffers=buffers, parts=parts)
     g.load_shards(to_dev(X))
     g.run_steps(2)                                    # t = 2: the messages of round 0 wait to be merged
     g.set_option(B.OPT_KERNEL, 1)
@@ -494,10 +496,13 @@ def test_kernel_switch_between_runs(B, oracle):
     g.run_steps(1)                                    # t = 3: nothing in flight
     g.set_option(B.OPT_KERNEL, 1)
     g.run_steps(4)                                    # the generic kernel takes over, sends and merges in its format
-    o = oracle.OracleASGD(X, k=10, W=6, b=200, lr=0.1, E=2)
-    o.run_steps(7)
+    g.set_option(B.OPT_KERNEL, 2)
+    g.run_steps(2)                                    # and back (t = 9)
+    o = oracle.OracleASGD(X, k=10, W=6, b=200, lr=0.1, E=2, buffers=buffers, parts=parts)
+    o.run_steps(9)
     assert rel_fro(g.get_state(), o.w).max() <= TOL
-    assert np.array_equal(g.worker_counters(), o.counters)
+    if o.near[1] == 0:
+        assert np.array_equal(g.worker_counters(), o.counters)
 
 
 def test_schedule_matches_oracle(B, oracle):
