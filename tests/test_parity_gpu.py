@@ -351,6 +351,11 @@ def test_n_external_buffers_options(B, oracle):
         many = B.ASGD(10, 10, 3, 100, 0.05, E=2, buffers=3); many.load_shards(Xg); many.run_steps(1)   # needs N < W
     with pytest.raises(B.AsgdError):
         B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=5)
+    # set after load_shards but before the first step: same as set at creation
+    late = B.ASGD(10, 10, 6, 100, 0.05, E=2); late.load_shards(Xg)
+    late.set_option(B.OPT_BUFFERS, 3); late.set_option(B.OPT_PARTS, 2); late.run_steps(9)
+    early = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=3, parts=2); early.load_shards(Xg); early.run_steps(9)
+    assert np.array_equal(late.get_state(), early.get_state()) and late.stats().received == early.stats().received > 0
     # one buffer set explicitly is the default; same run twice with three buffers: bit for bit
     a = B.ASGD(10, 10, 6, 100, 0.05, E=2, buffers=1); a.load_shards(Xg); a.run_steps(9)
     c = B.ASGD(10, 10, 6, 100, 0.05, E=2); c.load_shards(Xg); c.run_steps(9)
