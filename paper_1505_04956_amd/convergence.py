@@ -18,6 +18,7 @@ def main() -> None:
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--epochs", type=int, default=8)
     ap.add_argument("--buffers", type=int, default=1)
+    ap.add_argument("--parts", type=int, default=1)
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -31,11 +32,12 @@ def main() -> None:
              ("silent", dict(E=0)))
     runs = {}
     for name, kw in modes:
-        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, seed=wl.schedule_seed, buffers=(args.buffers if kw["E"] else 1), **kw)
+        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, seed=wl.schedule_seed, buffers=(args.buffers if kw["E"] else 1),
+                   parts=(args.parts if kw["E"] else 1), **kw)
         g.load_shards(X)
         runs[name] = g
-    print("workload %s: N=%d d=%d k=%d W=%d b=%d E=%d, buffers=%d; per sample: E(w)/N" %
-          (wl.name, wl.N, wl.d, wl.k, wl.W, wl.b, wl.E, args.buffers), flush=True)
+    print("workload %s: N=%d d=%d k=%d W=%d b=%d E=%d, buffers=%d, parts=%d; per sample: E(w)/N" %
+          (wl.name, wl.N, wl.d, wl.k, wl.W, wl.b, wl.E, args.buffers, args.parts), flush=True)
     print("%5s %-14s %14s %14s %12s %12s" % ("epoch", "mode", "E(w_0)/N", "E(mean w)/N", "centres w_0", "centres mean"))
     for ep in range(1, args.epochs + 1):
         for name, _ in modes:
