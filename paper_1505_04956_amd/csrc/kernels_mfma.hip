@@ -124,7 +124,7 @@ __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool reside
     size_t o = (size_t)(resident ? g.kpad : 2 * WB) * DP * sizeof(float);
     g.off_h = o;            o += (size_t)g.kpad * sizeof(float);
     g.off_cstart = o;       o += ((size_t)g.ns + 4) / 4 * 4 * sizeof(int);
-    g.off_cursor = o;       o += ((size_t)g.ns + 3) / 4 * 4 * sizeof(int);
+    g.off_cursor = o;       o += ((size_t)g.ns * nwv + 3) / 4 * 4 * sizeof(int);
     g.off_idx = o;          o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
@@ -195,6 +195,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     __shared__ int s_ext_round[MAX_BUFFERS];   // round of the message in buffer n (free-running mode: any earlier one)
     __shared__ int s_rowflags[3];     // partial messages: buffers with a non-empty row, with an accepted row, near-ties
     __shared__ int s_next_rows;
+    __shared__ int s_tot[MF_WAVES];   // samples in the slots of a wave (counting sort)
 
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     float *Ws = reinterpret_cast<float *>(smem_raw);                                  // (RES ? kpad : 2 x WB) x DP
     float *hs = reinterpret_cast<float *>(smem_raw + g.off_h);                        // kpad offsets h_c
     int *cstart = reinterpret_cast<int *>(smem_raw + g.off_cstart);                   // ns + 1 list starts
-    int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns counts, then cursors
+    int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns x nwv counts (slot-major: one per slot and wave), then cursors
     unsigned short *idx = reinterpret_cast<unsigned short *>(smem_raw + g.off_idx);   // b assignments
     unsigned short *perm = reinterpret_cast<unsigned short *>(smem_raw + g.off_perm); // b samples sorted by centroid
     unsigned short *flist = reinterpret_cast<unsigned short *>(smem_raw + g.off_flist);
@@ -594,29 +595,47 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         asm volatile("" : "+v"(lane_p2));
         const int lane = lane_p2, tid = wave * 64 + lane;
         // ---- stable counting sort of the samples by centroid slot ----
-        for (int s = tid; s < g.ns; s += MF_THREADS) cursor[s] = 0;
+        // Wave w takes the samples [w, w + 1) * spw of the mini-batch: it counts them per slot, and later places them,
+        // behind those of the waves before it.  Entry slot * NWV + w of `cursor` first holds that count, then the
+        // position of the wave's next sample of the slot.  (Every vector instruction of this part competes with the
+        // matrix work of the other workgroup on the CU, so each wave looks at its share of the samples only.)
+        const int spw = ((b + 63) / 64 + NWV - 1) / NWV * 64;          // samples per wave, whole groups of 64
+        const int n_lo = wave * spw, n_hi = min(b, n_lo + spw);
+        for (int s = tid; s < g.ns * NWV; s += MF_THREADS) cursor[s] = 0;
         __syncthreads();                                   // also: idx complete
-        for (int n = tid; n < b; n += MF_THREADS) {
+        for (int n = n_lo + lane; n < n_hi; n += 64) {
             const int c = idx[n];
-            atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);
+            atomicAdd(&cursor[((c % NWV) * g.kq + c / NWV) * NWV + wave], 1);
         }
         __syncthreads();
-        if (wave == 0) {
+        {
+            // exclusive prefix over the ns * NWV entries: wave w scans those of its own slots (they are contiguous),
+            // the totals of the waves give the offsets
+            int *mine = cursor + wave * g.ns;              // kq slots x NWV entries = ns entries
             int running = 0;
             for (int base = 0; base < g.ns; base += 64) {
-                const int s = base + lane;
-                const int v = s < g.ns ? cursor[s] : 0;
+                const int e = base + lane;
+                const int v = e < g.ns ? mine[e] : 0;
                 int incl = v;
 #pragma unroll
                 for (int off = 1; off < 64; off <<= 1) {
                     const int o = __shfl_up(incl, off, 64);
                     if (lane >= off) incl += o;
                 }
-                const int excl = incl - v + running;
-                if (s < g.ns) { cstart[s] = excl; cursor[s] = excl; }
+                if (e < g.ns) mine[e] = incl - v + running;
                 running += __shfl(incl, 63, 64);
             }
-            if (lane == 0) cstart[g.ns] = running;
+            if (lane == 0) s_tot[wave] = running;
+            __syncthreads();
+            int woff = 0;
+#pragma unroll
+            for (int v = 0; v < MF_WAVES; ++v) woff += v < wave ? s_tot[v] : 0;
+            for (int e = lane; e < g.ns; e += 64) {
+                const int pos = mine[e] + woff;
+                mine[e] = pos;
+                if (e % NWV == 0) cstart[wave * g.kq + e / NWV] = pos;
+            }
+            if (wave == MF_WAVES - 1 && lane == 0) cstart[g.ns] = woff + running;
         }
         const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && (t % p.E) == 0);
         const long long r_now = p.E > 0 ? t / p.E : 0;
@@ -650,29 +669,30 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __syncthreads();
         // the message was written by another workgroup, maybe on another XCD, during this launch
         if (sync && merge_point) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        // placement: every wave walks all samples in order and places those of its own centroids
+        // placement: a wave walks its samples in order
         int nbits = 1;
         while ((1 << nbits) < k) ++nbits;
-        for (int n0 = 0; n0 < b; n0 += 64) {
+        for (int n0 = n_lo; n0 < n_hi; n0 += 64) {
             const int n = n0 + lane;
-            const int c = n < b ? (int)idx[n] : -1;
-            const bool own = n < b && (c % NWV) == wave;
-            // lanes of this chunk with the same centroid as this lane: intersect, bit by bit of the index, the
+            const bool valid = n < n_hi;
+            const int c = valid ? (int)idx[n] : -1;
+            // lanes of this group with the same centroid as this lane: intersect, bit by bit of the index, the
             // ballot of the lanes that agree with this lane in that bit (no loop over distinct values)
-            unsigned long long same = __ballot(own);
+            unsigned long long same = __ballot(valid);
             for (int bit = 0; bit < nbits; ++bit) {
                 const unsigned long long set = __ballot(((c >> bit) & 1) != 0);
                 same &= ((c >> bit) & 1) ? set : ~set;
             }
             const int rank = __popcll(same & ((1ull << lane) - 1ull));
             const bool last = (same >> lane) == 1ull;
-            if (own) {
-                const int s = (c % NWV) * g.kq + c / NWV;
-                const int base = cursor[s];
+            if (valid) {
+                const int e = ((c % NWV) * g.kq + c / NWV) * NWV + wave;
+                const int base = cursor[e];
                 perm[base + rank] = (unsigned short)n;
-                if (last) cursor[s] = base + rank + 1;
+                if (last) cursor[e] = base + rank + 1;
             }
         }
+        __syncthreads();        // the lists of a wave's centroids were written by all waves
         // gather, large clusters: the wave's 64 lanes are two half-waves of 32 float4 columns; each half-wave sums
         // the sample rows of one of the wave's centroids, in sample order, GU rows in flight per half-wave
         if (b >= 8 * k) {
