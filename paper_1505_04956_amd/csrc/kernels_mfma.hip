@@ -98,11 +98,19 @@ __device__ __forceinline__ double wave_sum_d(double v)
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
+// Sum over the wave without LDS traffic: butterfly inside rows of 16 lanes with DPP (lane ^ 1, lane ^ 2, mirror inside 8,
+// mirror inside 16), then the four rows through scalar reads.  The order of the additions is fixed.
 __device__ __forceinline__ float wave_sum_f(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x141, 0xF, 0xF, true));   // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x140, 0xF, 0xF, true));   // row_mirror
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
 }
 
 // LDS layout, shared by host and device
@@ -784,6 +792,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __syncthreads();
 
         const int has_mask = s_has_ext;      // uniform over the workgroup
+        const float inv_b = 1.0f / (float)b;
         const float *ext0 = p.slot + ((size_t)(rpar * p.nb) * p.W + i) * kd;          // buffer n: + n * W * kd
         const size_t ext_stride = (size_t)p.W * kd;
         if (p.parts > 1) {
@@ -801,10 +810,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                 for (int jq = 0; jq < NJ; ++jq) {
                     const int j = lane + 64 * jq;
-                    const size_t e = (size_t)c * d + (j < d ? j : 0);
+                    const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
                     w[jq] = wst[e];
                     const float sums = cn > 0 ? gsc[e] : 0.0f;
-                    gq[jq] = ((float)cn * w[jq] - sums) / (float)b;            // descent gradient of Eq. 9
+                    gq[jq] = ((float)cn * w[jq] - sums) * inv_b;            // descent gradient of Eq. 9
                     wesum[jq] = 0.0f;
                 }
                 int rowmask = 0;
@@ -886,7 +895,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
                         const int j = lane + 64 * jq;
-                        const size_t e = (size_t)c * d + (j < d ? j : 0);
+                        const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
                         w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = ext[e];
                     }
                 }
@@ -897,7 +906,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         const int j = lane + 64 * jq;
                         if (c0 + q < k && j < d) {
                             const float sums = cn[q] > 0 ? sm[q][jq] : 0.0f;
-                            const float gq = ((float)cn[q] * w[q][jq] - sums) / (float)b;     // descent gradient of Eq. 9
+                            const float gq = ((float)cn[q] * w[q][jq] - sums) * inv_b;     // descent gradient of Eq. 9
                             const double wed = (double)we[q][jq];
                             const double a = ((double)w[q][jq] - (double)p.eps * (double)gq) - wed;
                             const double c2 = (double)w[q][jq] - wed;
@@ -943,7 +952,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
                         const int j = lane + 64 * jq;
-                        const size_t e = (size_t)c * d + (j < d ? j : 0);
+                        const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
                         w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = extp[e];
                         for (int m = more_mask; m; m &= m - 1) we[q][jq] += ext0[__builtin_ctz(m) * ext_stride + e];
                     }
@@ -956,7 +965,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         const int j = lane + 64 * jq;
                         if (c0 + q < k && j < d) {
                             const float sums = cn[q] > 0 ? sm[q][jq] : 0.0f;
-                            float step = ((float)cn[q] * w[q][jq] - sums) / (float)b;
+                            float step = ((float)cn[q] * w[q][jq] - sums) * inv_b;
                             if (delta) step += w[q][jq] - inv * (w[q][jq] + we[q][jq]);
                             const float wn = w[q][jq] - p.eps * step;
                             wst[(size_t)(c0 + q) * d + j] = wn;
