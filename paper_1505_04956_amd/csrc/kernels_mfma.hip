@@ -203,6 +203,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     __shared__ int s_ext_round[MAX_BUFFERS];   // round of the message in buffer n (free-running mode: any earlier one)
     __shared__ int s_rowflags[3];     // partial messages: buffers with a non-empty row, with an accepted row, near-ties
     __shared__ int s_next_rows;
+    __shared__ int s_next_item;       // gather: next ticket (slot, first or second round)
     __shared__ int s_tot[MF_WAVES];   // samples in the slots of a wave (counting sort)
 
     const int i = blockIdx.x;                       // worker
@@ -610,6 +611,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int spw = ((b + 63) / 64 + NWV - 1) / NWV * 64;          // samples per wave, whole groups of 64
         const int n_lo = wave * spw, n_hi = min(b, n_lo + spw);
         for (int s = tid; s < g.ns * NWV; s += MF_THREADS) cursor[s] = 0;
+        if (tid == 0) s_next_item = 0;
         __syncthreads();                                   // also: idx complete
         for (int n = n_lo + lane; n < n_hi; n += 64) {
             const int c = idx[n];
@@ -701,39 +703,60 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         }
         __syncthreads();        // the lists of a wave's centroids were written by all waves
-        // gather, large clusters: the wave's 64 lanes are two half-waves of 32 float4 columns; each half-wave sums
-        // the sample rows of one of the wave's centroids, in sample order, GU rows in flight per half-wave
+        // gather, large clusters: the wave's 64 lanes are two half-waves of 32 float4 columns; a half-wave sums the
+        // sample rows of one centroid at a time, in sample order, GU rows in flight, and takes its next centroid from a
+        // counter when it is through: first the centroids with many samples, then the others, so that skewed cluster
+        // sizes (the workload with Zipf weights) still spread evenly over the half-waves.  Which half-wave sums a
+        // centroid does not change its sum.
         if (b >= 8 * k) {
             const int hw = lane >> 5, q4 = lane & 31;
             const bool colok = 4 * q4 < d;
             const int col = colok ? 4 * q4 : 0;
-            const int *cs = cstart + wave * g.kq;
-            for (int mp = 0; mp < g.kq; mp += 2) {
-                const int m = mp + hw;
-                const int c = wave + NWV * m;
-                const bool cok = m < g.kq && c < k;
-                const int a = cok ? (int)cs[m] : 0;
-                const int nrow = cok ? (int)cs[m + 1] - a : 0;
-                const int nmax = max(__builtin_amdgcn_readlane(nrow, 0), __builtin_amdgcn_readlane(nrow, 32));
-                float4 S = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                for (int it0 = 0; it0 < nmax; it0 += GU) {
-                    // past the end of its list a half-wave re-reads a valid row and adds 0 instead, so the loop
-                    // has no divergent branch
-                    float4 v[GU];
-                    int id[GU];
-#pragma unroll
-                    for (int u = 0; u < GU; ++u) id[u] = perm[it0 + u < nrow ? a + it0 + u : 0];
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < GU; ++u) v[u] = *reinterpret_cast<const float4 *>(xb + (id[u] * d + col));
-#pragma unroll
-                    for (int u = 0; u < GU; ++u) {
-                        const bool ok = it0 + u < nrow;
-                        S.x += ok ? v[u].x : 0.0f; S.y += ok ? v[u].y : 0.0f;
-                        S.z += ok ? v[u].z : 0.0f; S.w += ok ? v[u].w : 0.0f;
+            const int big = max(b / (8 * NWV), GU);       // a quarter of a half-wave's share of the mini-batch
+            int a = 0, nrow = 0, it = 0, c_cur = 0;
+            bool done = false;
+            float4 S = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            for (;;) {
+                bool need = !done && it >= nrow;
+                while (__ballot(need) != 0ull) {
+                    // ticket v: slot v in the first round (taken if it is a big one), slot v - ns in the second
+                    int v = 0;
+                    if (need && q4 == 0) v = atomicAdd(&s_next_item, 1);
+                    v = __shfl(v, hw * 32, 64);
+                    if (need) {
+                        if (v < 2 * g.ns) {
+                            const int sl = v < g.ns ? v : v - g.ns;
+                            const int a2 = cstart[sl], n2 = cstart[sl + 1] - a2;
+                            if (v < g.ns ? (n2 >= big) : (n2 > 0 && n2 < big)) {
+                                a = a2; nrow = n2; it = 0;
+                                c_cur = (sl % g.kq) * NWV + sl / g.kq;
+                                S = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                                need = false;
+                            }
+                        } else {
+                            done = true;
+                            need = false;
+                        }
                     }
                 }
-                if (colok && cok) *reinterpret_cast<float4 *>(gsc + (size_t)c * d + 4 * q4) = S;
+                if (__ballot(!done) == 0ull) break;
+                // past the end of its list a half-wave re-reads a valid row and adds 0 instead, so the loop
+                // has no divergent branch
+                float4 v[GU];
+                int id[GU];
+#pragma unroll
+                for (int u = 0; u < GU; ++u) id[u] = perm[(!done && it + u < nrow) ? a + it + u : 0];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < GU; ++u) v[u] = *reinterpret_cast<const float4 *>(xb + (id[u] * d + col));
+#pragma unroll
+                for (int u = 0; u < GU; ++u) {
+                    const bool ok = !done && it + u < nrow;
+                    S.x += ok ? v[u].x : 0.0f; S.y += ok ? v[u].y : 0.0f;
+                    S.z += ok ? v[u].z : 0.0f; S.w += ok ? v[u].w : 0.0f;
+                }
+                it += GU;
+                if (!done && it >= nrow && colok) *reinterpret_cast<float4 *>(gsc + (size_t)c_cur * d + 4 * q4) = S;
             }
         }
         // gather, small clusters: this wave's samples in (centroid, sample) order, GS rows in flight whatever the
