@@ -195,6 +195,8 @@ def test_wider_shapes_generic(B, oracle):
     (33, 36, 5, 300, 3, 8, 5 * 1000 + 3, "uniform10", "equal"),         # ragged last tile, odd row length of W'
     (2, 4, 2, 129, 1, 6, 2 * 400, "uniform10", "equal"),                # smallest k and d
     (128, 64, 2, 256, 1, 5, 2 * 1024, "uniform10", "equal"),            # exact multiples of all tile sizes
+    (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "uniform10", "zipf1.1"),  # skewed cluster sizes, big and small ones in one gather
+    (3, 16, 2, 500, 2, 5, 2 * 1000, "uniform10", "zipf1.1"),            # fewer centroids than half-waves
 ])
 def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights):
     X = make_data(N, d, k, seed=21, centres=centres, weights=weights)
@@ -206,6 +208,7 @@ def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights
     (100, 100, 4, 2000, 2, 7, 4 * 2000 * 3),
     (33, 36, 5, 300, 3, 8, 5 * 1000 + 3),
     (70, 8, 3, 100, 2, 9, 3 * 450 + 2),
+    (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5),
 ])
 def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N):
     # the variant with four waves per worker (two workers per CU), which large W selects by itself
