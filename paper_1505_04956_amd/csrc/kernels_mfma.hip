@@ -119,6 +119,7 @@ struct MfmaGeom {
     int nblocks;   // kpad / WB
     int kq;        // centroids per owner wave (c % nwv), rounded up
     int ns;        // nwv * kq sort slots: slot(c) = (c % nwv) * kq + c / nwv
+    int nr;        // shares of the mini-batch in the counting sort (waves that count and place): a power of two <= nwv
     size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, bytes;
 };
 __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv)
@@ -129,10 +130,12 @@ __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool reside
     g.nblocks = g.kpad / WB;
     g.kq = (k + nwv - 1) / nwv;
     g.ns = nwv * g.kq;
+    g.nr = nwv;
+    while (g.nr > 1 && (size_t)g.ns * g.nr * sizeof(int) > 32768) g.nr /= 2;     // the counters stay within 32 KB
     size_t o = (size_t)(resident ? g.kpad : 2 * WB) * DP * sizeof(float);
     g.off_h = o;            o += (size_t)g.kpad * sizeof(float);
     g.off_cstart = o;       o += ((size_t)g.ns + 4) / 4 * 4 * sizeof(int);
-    g.off_cursor = o;       o += ((size_t)g.ns * nwv + 3) / 4 * 4 * sizeof(int);
+    g.off_cursor = o;       o += ((size_t)g.ns * g.nr + 3) / 4 * 4 * sizeof(int);
     g.off_idx = o;          o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     float *Ws = reinterpret_cast<float *>(smem_raw);                                  // (RES ? kpad : 2 x WB) x DP
     float *hs = reinterpret_cast<float *>(smem_raw + g.off_h);                        // kpad offsets h_c
     int *cstart = reinterpret_cast<int *>(smem_raw + g.off_cstart);                   // ns + 1 list starts
-    int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns x nwv counts (slot-major: one per slot and wave), then cursors
+    int *cursor = reinterpret_cast<int *>(smem_raw + g.off_cursor);                   // ns x nr counts (slot-major: one per slot and share), then cursors
     unsigned short *idx = reinterpret_cast<unsigned short *>(smem_raw + g.off_idx);   // b assignments
     unsigned short *perm = reinterpret_cast<unsigned short *>(smem_raw + g.off_perm); // b samples sorted by centroid
     unsigned short *flist = reinterpret_cast<unsigned short *>(smem_raw + g.off_flist);
@@ -604,35 +607,38 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         asm volatile("" : "+v"(lane_p2));
         const int lane = lane_p2, tid = wave * 64 + lane;
         // ---- stable counting sort of the samples by centroid slot ----
-        // Wave w takes the samples [w, w + 1) * spw of the mini-batch: it counts them per slot, and later places them,
-        // behind those of the waves before it.  Entry slot * NWV + w of `cursor` first holds that count, then the
-        // position of the wave's next sample of the slot.  (Every vector instruction of this part competes with the
-        // matrix work of the other workgroup on the CU, so each wave looks at its share of the samples only.)
-        const int spw = ((b + 63) / 64 + NWV - 1) / NWV * 64;          // samples per wave, whole groups of 64
-        const int n_lo = wave * spw, n_hi = min(b, n_lo + spw);
-        for (int s = tid; s < g.ns * NWV; s += MF_THREADS) cursor[s] = 0;
+        // The mini-batch is cut into nr shares of whole groups of 64 samples (nr = number of waves unless the
+        // counters would not fit).  Wave w < nr counts the samples of share w per slot and later places them, behind
+        // those of the shares before it.  Entry slot * nr + w of `cursor` first holds that count, then the position of
+        // the share's next sample of the slot.  (Every vector instruction of this part competes with the matrix work
+        // of the other workgroup on the CU, so each wave looks at its share of the samples only.)
+        const int NR = g.nr;
+        const int spw = ((b + 63) / 64 + NR - 1) / NR * 64;
+        const int n_lo = min(b, wave * spw), n_hi = wave < NR ? min(b, n_lo + spw) : n_lo;
+        for (int s = tid; s < g.ns * NR; s += MF_THREADS) cursor[s] = 0;
         if (tid == 0) s_next_item = 0;
         __syncthreads();                                   // also: idx complete
         for (int n = n_lo + lane; n < n_hi; n += 64) {
             const int c = idx[n];
-            atomicAdd(&cursor[((c % NWV) * g.kq + c / NWV) * NWV + wave], 1);
+            atomicAdd(&cursor[((c % NWV) * g.kq + c / NWV) * NR + wave], 1);
         }
         __syncthreads();
         {
-            // exclusive prefix over the ns * NWV entries: wave w scans those of its own slots (they are contiguous),
+            // exclusive prefix over the ns * nr entries: wave w scans those of its own slots (they are contiguous),
             // the totals of the waves give the offsets
-            int *mine = cursor + wave * g.ns;              // kq slots x NWV entries = ns entries
+            const int ne = g.kq * NR;
+            int *mine = cursor + wave * ne;
             int running = 0;
-            for (int base = 0; base < g.ns; base += 64) {
+            for (int base = 0; base < ne; base += 64) {
                 const int e = base + lane;
-                const int v = e < g.ns ? mine[e] : 0;
+                const int v = e < ne ? mine[e] : 0;
                 int incl = v;
 #pragma unroll
                 for (int off = 1; off < 64; off <<= 1) {
                     const int o = __shfl_up(incl, off, 64);
                     if (lane >= off) incl += o;
                 }
-                if (e < g.ns) mine[e] = incl - v + running;
+                if (e < ne) mine[e] = incl - v + running;
                 running += __shfl(incl, 63, 64);
             }
             if (lane == 0) s_tot[wave] = running;
@@ -640,10 +646,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             int woff = 0;
 #pragma unroll
             for (int v = 0; v < MF_WAVES; ++v) woff += v < wave ? s_tot[v] : 0;
-            for (int e = lane; e < g.ns; e += 64) {
+            for (int e = lane; e < ne; e += 64) {
                 const int pos = mine[e] + woff;
                 mine[e] = pos;
-                if (e % NWV == 0) cstart[wave * g.kq + e / NWV] = pos;
+                if (e % NR == 0) cstart[wave * g.kq + e / NR] = pos;
             }
             if (wave == MF_WAVES - 1 && lane == 0) cstart[g.ns] = woff + running;
         }
@@ -696,7 +702,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int rank = __popcll(same & ((1ull << lane) - 1ull));
             const bool last = (same >> lane) == 1ull;
             if (valid) {
-                const int e = ((c % NWV) * g.kq + c / NWV) * NWV + wave;
+                const int e = ((c % NWV) * g.kq + c / NWV) * NR + wave;
                 const int base = cursor[e];
                 perm[base + rank] = (unsigned short)n;
                 if (last) cursor[e] = base + rank + 1;

@@ -197,6 +197,7 @@ def test_wider_shapes_generic(B, oracle):
     (128, 64, 2, 256, 1, 5, 2 * 1024, "uniform10", "equal"),            # exact multiples of all tile sizes
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "uniform10", "zipf1.1"),  # skewed cluster sizes, big and small ones in one gather
     (3, 16, 2, 500, 2, 5, 2 * 1000, "uniform10", "zipf1.1"),            # fewer centroids than half-waves
+    (2048, 16, 2, 2304, 1, 3, 2 * 2304 * 2, "uniform10", "equal"),      # many centroids: the sort uses fewer shares than waves
 ])
 def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights):
     X = make_data(N, d, k, seed=21, centres=centres, weights=weights)
