@@ -388,11 +388,17 @@ __global__ __launch_bounds__(QE_THREADS) void quant_error_kernel(const float *__
 
 __global__ void quant_error_final_kernel(const double *partials, int n, double *out)
 {
-    // one thread, fixed order: the result does not depend on scheduling
+    // One wave, fixed order: lane l adds the partials l, l + 64, ... in that order, then the 64 sums are added in lane
+    // order.  The result does not depend on scheduling.
+    __shared__ double red[64];
+    double s = 0.0;
+    for (int q = threadIdx.x; q < n; q += 64) s += partials[q];
+    red[threadIdx.x] = s;
+    __syncthreads();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        double s = 0.0;
-        for (int q = 0; q < n; ++q) s += partials[q];
-        *out = s;
+        double t = 0.0;
+        for (int l = 0; l < 64; ++l) t += red[l];
+        *out = t;
     }
 }
 
