@@ -145,15 +145,26 @@ __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool reside
 }
 inline int mfma_chunks(int d) { return d <= 32 ? 4 : d <= 64 ? 8 : d <= 104 ? 13 : 16; }
 
-// max over rows of |x|^2 (one value), used by the rounding-error bound
+// max over rows of |x|^2 (one value), used by the rounding-error bound.  A half-wave takes a row (32 lanes x float4
+// cover d <= 128 floats, d a multiple of 4, rows 16-byte aligned: what the matrix-core kernel requires anyway), so
+// the reads are contiguous; the squares of a row are added in a fixed order (lane-local, then a butterfly).
 __global__ void rownorm2_partial_kernel(const float *__restrict__ x, long long rows, int d, float *partial)
 {
     __shared__ float red[256];
+    const int lane = threadIdx.x & 63, q4 = lane & 31;
+    const long long hw = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 5;      // half-wave number
+    const long long nhw = ((long long)gridDim.x * blockDim.x) >> 5;
+    const bool colok = 4 * q4 < d;
     float m = 0.0f;
-    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (long long)gridDim.x * blockDim.x) {
-        const float *xr = x + (size_t)r * d;
+    for (long long r0 = 0; r0 < rows; r0 += nhw) {          // uniform trip count: the shuffles below need every lane
+        const long long r = r0 + hw;
         float s = 0.0f;
-        for (int j = 0; j < d; ++j) s = fmaf(xr[j], xr[j], s);
+        if (r < rows && colok) {
+            const float4 v = *reinterpret_cast<const float4 *>(x + (size_t)r * d + 4 * q4);
+            s = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
+        }
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);         // stays inside the half-wave
         m = fmaxf(m, s);
     }
     red[threadIdx.x] = m;
