@@ -51,6 +51,7 @@ struct asgd_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     double last_ms = 0.0;
     int last_kernel = 0, last_launches = 0;
+    long long passed_t = -1;    // step up to which `consumed` holds what a one-launch run needs (-1: unknown)
     int fill_kernel = 0;        // kernel whose message format the exchange buffers were last emptied for
     int hip_err = 0;
 };
@@ -201,6 +202,7 @@ int asgd_last_hip_error(asgd_ctx *ctx) { return ctx ? ctx->hip_err : 0; }
 int asgd_set_option(asgd_ctx *ctx, int key, double value)
 {
     if (!ctx || !isfinite(value)) return ASGD_EINVAL;
+    ctx->passed_t = -1;
     switch (key) {
         case ASGD_OPT_EXCHANGE_EVERY:
             if (value < 0 || value > 2e9 || value != floor(value)) return ASGD_EINVAL;
@@ -284,6 +286,7 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->x = x_dev; ctx->N = N; ctx->H = H; ctx->S = H / ctx->b;
     ctx->stream = (hipStream_t)hip_stream;
     ctx->t = 0;
+    ctx->passed_t = -1;
     ctx->loaded = false;
     ctx->xnorm2max_valid = false;
     StepParams p = make_params(ctx);
@@ -326,6 +329,7 @@ int asgd_set_step(asgd_ctx *ctx, int64_t t)
     if (!ctx->loaded) return ASGD_ESTATE;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     ctx->t = t;
+    ctx->passed_t = -1;
     int rc = clear_exchange(ctx, ASGD_KERNEL_SMALL);
     if (rc != ASGD_OK) return rc;
     ctx->fill_kernel = 0;
@@ -422,12 +426,15 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         // every worker has passed the merge points before the first step of this run
         const long long r0 = ctx->t / ctx->E;
         const int passed = (int)((ctx->t % ctx->E) != 0 ? r0 : (r0 > 0 ? r0 - 1 : 0));
-        HIP_TRY(ctx, hipMemsetD32Async((hipDeviceptr_t)ctx->consumed, passed, (size_t)ctx->W, ctx->stream));
+        // (a one-launch run leaves exactly these values behind: no need to write them again for the run that follows it)
+        if (ctx->passed_t != ctx->t)
+            HIP_TRY(ctx, hipMemsetD32Async((hipDeviceptr_t)ctx->consumed, passed, (size_t)ctx->W, ctx->stream));
         hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ctx->t, t_end, ctx->stream, true)
                                                      : launch_mfma_steps(p, ctx->t, t_end, ctx->xnorm2max, ctx->stream, true);
         if (e == hipSuccess) {
             done = true;
             launches = 1;
+            ctx->passed_t = t_end;
         } else if (e == hipErrorCooperativeLaunchTooLarge || e == hipErrorNotSupported) {
             (void)hipGetLastError();     // fall back to one launch per round
         } else {
@@ -447,6 +454,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         HIP_TRY(ctx, e);
         ++launches;
         ta = tb;
+        ctx->passed_t = -1;
     }
     HIP_TRY(ctx, hipEventRecord(ctx->ev1, ctx->stream));
     HIP_TRY(ctx, hipMemcpyAsync(ctx->flag_host, ctx->error_flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
