@@ -38,7 +38,12 @@ enum {
     ASGD_ENOMEM = -2,   /* device or host allocation failed */
     ASGD_ESTATE = -3,   /* call out of order (e.g. run before load_shards) */
     ASGD_EHIP = -4,     /* a HIP runtime call failed; asgd_last_hip_error() has its code */
-    ASGD_ESYNC = -5     /* a bounded wait inside a kernel expired (persistent kernels) */
+    ASGD_ESYNC = -5     /* a bounded wait inside a kernel expired (runs that are one launch of workgroups
+                           which wait for each other's messages; all the waits of a workgroup draw on one
+                           budget of polls, so such a launch ends within about a second of waiting whatever
+                           its length).  The run is lost: the step counter is not advanced and later runs
+                           fail with ASGD_ESTATE until asgd_load_shards(), or asgd_set_state() followed by
+                           asgd_set_step(), have put the context back on a known footing. */
 };
 
 /* Keys of asgd_set_option().  Values are passed as double and rounded to integers

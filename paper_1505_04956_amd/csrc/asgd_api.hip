@@ -53,6 +53,7 @@ struct asgd_ctx {
     int last_kernel = 0, last_launches = 0;
     long long passed_t = -1;    // step up to which `consumed` holds what a one-launch run needs (-1: unknown)
     int fill_kernel = 0;        // kernel whose message format the exchange buffers were last emptied for
+    bool desynced = false;      // a bounded wait expired in the last run: states and buffers are not those of any step
     int hip_err = 0;
 };
 
@@ -287,6 +288,7 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->stream = (hipStream_t)hip_stream;
     ctx->t = 0;
     ctx->passed_t = -1;
+    ctx->desynced = false;
     ctx->loaded = false;
     ctx->xnorm2max_valid = false;
     StepParams p = make_params(ctx);
@@ -330,6 +332,7 @@ int asgd_set_step(asgd_ctx *ctx, int64_t t)
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     ctx->t = t;
     ctx->passed_t = -1;
+    ctx->desynced = false;
     int rc = clear_exchange(ctx, ASGD_KERNEL_SMALL);
     if (rc != ASGD_OK) return rc;
     ctx->fill_kernel = 0;
@@ -348,7 +351,7 @@ int asgd_set_assign_dump(asgd_ctx *ctx, int32_t *assign_dev, size_t capacity)
 int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
 {
     if (!ctx || steps < 0) return ASGD_EINVAL;
-    if (!ctx->loaded) return ASGD_ESTATE;
+    if (!ctx->loaded || ctx->desynced) return ASGD_ESTATE;
     if (ctx->lr_mode == ASGD_LR_INV_COUNT && ctx->E != 0) return ASGD_EINVAL;
     if (ctx->dump && (double)steps * ctx->W * ctx->b > (double)ctx->dump_cap) return ASGD_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
@@ -356,7 +359,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     int kernel = ctx->kernel_opt;
     if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
     const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST &&
-                          (ctx->nb == 1 || ((ctx->tune >> 2) & 3) != 1);      // several buffers: not in the private-rows shape
+                          ((ctx->nb == 1 && ctx->parts == 1) || ((ctx->tune >> 2) & 3) != 1);   // several buffers, partial messages: not in the private-rows shape
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
     if (kernel == ASGD_KERNEL_AUTO) {
         // the matrix-core kernel pays off once the k x d contraction dominates a step
@@ -419,6 +422,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     // earlier launch on the same stream.
     const bool rounds = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
     int launches = 0;
+    HIP_TRY(ctx, hipMemsetAsync(ctx->error_flag, 0, sizeof(int), ctx->stream));
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
     bool done = false;
     const bool one_launch = (kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3) || (kernel == ASGD_KERNEL_MFMA && !(ctx->tune & 4));
@@ -464,8 +468,15 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     ctx->last_ms = ms;
     ctx->last_kernel = kernel;
     ctx->last_launches = launches;
+    if (*ctx->flag_host) {
+        // A bounded wait inside a kernel expired: some worker went on without a message it was owed, so the states are
+        // not those of any step of the deterministic run.  The step counter stays where it was and the context refuses
+        // further runs until asgd_load_shards() or asgd_set_state() + asgd_set_step() put it back on a known footing.
+        ctx->passed_t = -1;
+        ctx->desynced = true;
+        return ASGD_ESYNC;
+    }
     ctx->t = t_end;
-    if (*ctx->flag_host) return ASGD_ESYNC;
     return ASGD_OK;
 }
 

@@ -43,17 +43,24 @@ constexpr int GS = 16;           // sample rows in flight per wave in the gather
 constexpr int GU = 16;           // sample rows in flight per half-wave in the gather (large clusters)
 constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the nearest
 
-// Bounded wait for a flag that another workgroup writes: false when the bound (about 0.2 s; the waits of a healthy
-// run last microseconds to a few milliseconds) expires.  A workgroup whose wait has failed once waits for nothing
-// any more (s_wait_failed), so a launch outlasts its normal duration by one bound at most.
-__device__ __forceinline__ bool mf_wait_flag(const int *flag, int want, bool at_least)
+// Bounded wait for a flag that another workgroup writes.  All the waits of a workgroup draw on ONE budget of polls
+// (*budget, in LDS, used by the one thread that waits; a poll is ~0.5 us of sleep plus an uncached load, the waits of
+// a healthy run last microseconds to a few milliseconds): false when it is used up.  A workgroup whose wait has failed
+// waits for nothing any more (s_wait_failed), so a launch outlasts its normal duration by about a quarter of a second
+// at most, however many rounds it covers.
+constexpr int MF_WAIT_BUDGET = 1 << 18;
+__device__ __forceinline__ bool mf_wait_flag(const int *flag, int want, bool at_least, int *budget)
 {
-    for (int spin = 0; spin < (1 << 17); ++spin) {
+    int left = *budget;
+    bool ok = false;
+    while (left > 0) {
         const int v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (at_least ? (v >= want) : (v == want)) return true;
+        if (at_least ? (v >= want) : (v == want)) { ok = true; break; }
         __builtin_amdgcn_s_sleep(8);
+        --left;
     }
-    return false;
+    *budget = left;
+    return ok;
 }
 
 struct Top3 {
@@ -214,6 +221,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     __shared__ float red_f[MF_WAVES];
     __shared__ int s_has_ext;
     __shared__ int s_wait_failed;
+    __shared__ int s_wait_budget;
     __shared__ int s_ext_round[MAX_BUFFERS];   // round of the message in buffer n (free-running mode: any earlier one)
     __shared__ int s_rowflags[3];     // partial messages: buffers with a non-empty row, with an accepted row, near-ties
     __shared__ int s_next_rows;
@@ -239,7 +247,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
     const float xn2 = *xnorm2max_ptr;
 
-    if (threadIdx.x == 0) s_wait_failed = 0;        // read after the barriers below
+    if (threadIdx.x == 0) { s_wait_failed = 0; s_wait_budget = MF_WAIT_BUDGET; }       // read after the barriers below
     // ---- h_c = -|w_c|^2/2 and max_c |w_c|^2 ----
     float wn2max = 0.0f;
     for (int c0 = wave * RB; c0 < g.kpad; c0 += MF_WAVES * RB) {
@@ -677,7 +685,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         const long long rs = r_now - 1;
                         const int sender = (i - shift_deterministic(p.seed, rs, p.W, n) + p.W) % p.W;
                         if (!message_dropped(p.seed, rs, sender, p.drop_thr, n) && !s_wait_failed &&
-                            !mf_wait_flag(stp, (int)rs, false)) {
+                            !mf_wait_flag(stp, (int)rs, false, &s_wait_budget)) {
                             s_wait_failed = 1;
                             atomicOr(p.error_flag, 1);
                         }
@@ -1042,7 +1050,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 const int spar = det ? (int)(r & 1) : 0;
                 if (sync && r >= 2) {
                     // the buffer still holds the message of round r - 2 until the peer has passed merge point r - 1
-                    if (tid == 0 && !s_wait_failed && !mf_wait_flag(p.consumed + peer, (int)(r - 1), true)) {
+                    if (tid == 0 && !s_wait_failed && !mf_wait_flag(p.consumed + peer, (int)(r - 1), true, &s_wait_budget)) {
                         s_wait_failed = 1;
                         atomicOr(p.error_flag, 1);
                     }
