@@ -193,6 +193,24 @@ int asgd_get_mean_state(asgd_ctx *ctx, float *out_host, size_t out_bytes);
  */
 int asgd_quant_error(asgd_ctx *ctx, int worker, double *out);
 
+/*
+ * Eq. 8 without a context and without any allocation, for callers that cannot call hipMalloc: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same kernels and the same result as
+ * asgd_quant_error(); the partial sums of the reduction live in a static device array of the library (16 KB on every
+ * GPU the library runs on, held until the process ends) instead of a context's scratch.
+ *   x_dev    device pointer, N x d fp32 row-major, at least 8-byte aligned (BORROWED for the duration of the work)
+ *   w_dev    device pointer, k x d fp32 state
+ *   out_dev  device pointer to ONE double, 8-byte aligned: receives E(w) when the work enqueued on `hip_stream`
+ *            (a hipStream_t, 0 = default stream) has finished; the call itself does not wait
+ * Limits: N <= 2^40, d <= 65536, k*d <= 2^24; anything larger, a null pointer or a misaligned one gives ASGD_EINVAL
+ * and nothing is enqueued.  Calls neither hipMalloc/hipFree nor any routine that allocates (the first call on a
+ * device looks up the address of the static array, nothing more).  All calls on one GPU share that array: calls that
+ * overlap in time on one GPU (different streams or threads) race on it; calls on one stream are ordered and safe.
+ * The array keeps the last call's partial sums; every call overwrites all it reads, so nothing is cleared.
+ */
+int asgd_quant_error_noalloc(const float *x_dev, int64_t N, int k, int d, const float *w_dev, double *out_dev,
+                             void *hip_stream);
+
 /* Device time in milliseconds of the last asgd_run_* call, measured with HIP events recorded on
    the context's stream around its kernel launches.  No device access. */
 int asgd_last_run_ms(asgd_ctx *ctx, double *out);

@@ -25,6 +25,7 @@ SYMBOLS = (
     "asgd_run_epochs", "asgd_run_steps", "asgd_set_assign_dump", "asgd_get_state",
     "asgd_get_mean_state", "asgd_quant_error", "asgd_last_run_ms", "asgd_get_stats", "asgd_get_worker_counters",
     "asgd_schedule_peer", "asgd_schedule_peer_n", "asgd_last_hip_error", "asgd_destroy", "asgd_strerror",
+    "asgd_quant_error_noalloc",
 )
 
 
@@ -74,6 +75,7 @@ def lib():
             "asgd_last_hip_error": (C.c_int, [vp]),
             "asgd_destroy": (None, [vp]),
             "asgd_strerror": (C.c_char_p, [C.c_int]),
+            "asgd_quant_error_noalloc": (C.c_int, [vp, i64, C.c_int, C.c_int, vp, vp, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -142,6 +144,10 @@ def asgd_quant_error(h, worker) -> float:
     v = C.c_double()
     _check(lib().asgd_quant_error(h, worker, C.byref(v)), "asgd_quant_error", h)
     return v.value
+
+
+def asgd_quant_error_noalloc(x_dev_ptr, N, k, d, w_dev_ptr, out_dev_ptr, stream=0):
+    _check(lib().asgd_quant_error_noalloc(x_dev_ptr, N, k, d, w_dev_ptr, out_dev_ptr, stream), "asgd_quant_error_noalloc")
 
 
 def asgd_last_run_ms(h) -> float:
