@@ -303,6 +303,7 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
  * t_io        global step counter shared by all workers, in/out
  * counters    W*3: sending rounds, messages looked at, messages merged ("good" messages), in/out
  * near        2 counters: argmin near-ties, Parzen near-ties, in/out
+ * parzen_near_w  optional W counters: Parzen near-ties per worker (steps of that worker with a flagged test), in/out
  * assign_out  optional nsteps*W*b assignments, step-major then worker then sample
  * gap_out     optional, same shape: (d2-d1)/d1 of each assignment
  * lr_mode     0 = constant eps, 1 = per-centroid 1/count (requires E == 0)
@@ -311,7 +312,7 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
 int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, double eps, int E, int nb, int parts,
                       uint64_t seed, int parzen, int lr_mode, uint32_t drop_threshold,
                       int64_t nsteps, double *w, double *slot, int64_t *slot_stamp, int64_t *ncum,
-                      int64_t *t_io, int64_t *counters, int64_t *near, int32_t *assign_out,
+                      int64_t *t_io, int64_t *counters, int64_t *near, int64_t *parzen_near_w, int32_t *assign_out,
                       double *gap_out)
 {
     if (k < 1 || d < 1 || W < 1 || b < 1 || !(eps > 0.0) || E < 0) return -1;
@@ -357,7 +358,10 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
         for (int i = 0; i < W; ++i) {
             counters[i * 3 + 1] += looked[i];
             counters[i * 3 + 2] += flags[i] & 255;
-            if (flags[i] & 256) near[1] += 1;
+            if (flags[i] & 256) {
+                near[1] += 1;
+                if (parzen_near_w) parzen_near_w[i] += 1;
+            }
         }
         if (merge_point) {               /* a buffer is looked at once, then emptied */
             memset(slot, 0, (size_t)nb * W * kd * sizeof(double));

@@ -54,7 +54,7 @@ def lib():
         L.asgd_oracle_steps.argtypes = [
             C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int, C.c_int,
             C.c_uint64, C.c_int, C.c_int, C.c_uint32, C.c_int64,
-            f64p, f64p, i64p, i64p, i64p, i64p, i64p, C.c_void_p, C.c_void_p]
+            f64p, f64p, i64p, i64p, i64p, i64p, i64p, i64p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -140,6 +140,7 @@ class OracleASGD:
         self.t = np.zeros(1, dtype=np.int64)
         self.counters = np.zeros((self.W, 3), dtype=np.int64)   # sent, received, accepted
         self.near = np.zeros(2, dtype=np.int64)                 # argmin / Parzen near-ties
+        self.parzen_near = np.zeros(self.W, dtype=np.int64)     # Parzen near-ties per worker
 
     def run_steps(self, nsteps: int, dump: bool = False):
         nsteps = int(nsteps)
@@ -149,11 +150,22 @@ class OracleASGD:
             self.X.ctypes.data, self.N, self.k, self.d, self.W, self.b, self.lr, self.E, self.buffers, self.parts,
             self.seed, int(self.parzen), self.lr_mode, self.drop_threshold, nsteps,
             self.w.reshape(-1), self.slot.reshape(-1), self.slot_stamp.reshape(-1), self.ncum.reshape(-1),
-            self.t, self.counters.reshape(-1), self.near,
+            self.t, self.counters.reshape(-1), self.near, self.parzen_near,
             a.ctypes.data if dump else None, g.ctypes.data if dump else None)
         if rc != 0:
             raise ValueError("asgd_oracle_steps rejected its arguments")
         return (a, g) if dump else None
+
+    def set_window(self, Xw, t_start: int):
+        """Hand the oracle only the rows that the steps [t_start, t_start + n) touch: Xw holds, shard after shard, the
+        n*b rows of those steps (n = rows per shard / b).  For inputs that do not fit the host as a whole.  Indexing
+        only: the C routine finds the mini-batch of step t at row (t mod n)*b of a shard, which is the right one when
+        the window starts at a multiple of n and does not cross the end of an epoch."""
+        Xw = _f32(Xw)
+        assert Xw.shape[1] == self.d and Xw.shape[0] % (self.W * self.b) == 0
+        n = Xw.shape[0] // (self.W * self.b)
+        assert int(self.t[0]) == t_start and t_start % n == 0
+        self.X, self.N = Xw, Xw.shape[0]
 
     def run_epochs(self, epochs: int, dump: bool = False):
         return self.run_steps(int(epochs) * self.S, dump=dump)

@@ -264,6 +264,42 @@ def test_parzen_off_always_merges_and_same_state_is_rejected(oracle):
     assert np.all(o2.counters[:, 2] == 0) and np.allclose(o2.w, w2 - 0.2 * G2, rtol=1e-12)
 
 
+@pytest.mark.parametrize("delta,flagged", [(2.5e-8, True), (-2.5e-8, True), (2.5e-4, False), (-2.5e-4, False)])
+def test_parzen_near_tie_flag_is_set_exactly_below_the_margin(oracle, delta, flagged):
+    """With w_ext = w - c*G: lhs / rhs = ((c - eps) / c)^2, so c = (eps/2)(1 + delta) gives |lhs - rhs| / rhs = 4|delta|
+    to first order: 1e-7 must be counted as a near-tie of Eq. 4, 1e-3 must not; the decision follows the sign."""
+    lr = 0.2
+    o, w, G = _merge_case(oracle, lr / 2 * (1 + delta), lr=lr)
+    assert o.near[1] == (2 if flagged else 0)                       # both workers of the pair
+    assert np.array_equal(o.parzen_near, [1, 1] if flagged else [0, 0])
+    assert np.all(o.counters[:, 2] == int(delta > 0))
+    # one worker near the tie, the other far from it: the per-worker counter tells them apart
+    c = np.array([lr / 2 * (1 + 2.5e-8), 3.0]).reshape(2, 1, 1)
+    o2, _, _ = _merge_case(oracle, c, lr=lr)
+    assert o2.near[1] == 1 and np.array_equal(o2.parzen_near, [1, 0]) and np.array_equal(o2.counters[:, 2], [1, 1])
+
+
+def test_argmin_near_tie_counter_counts_gaps_below_1e6(oracle):
+    """Two centroids at (0,0) and (2,0); a sample at (1 - eta, 0) has (d2 - d1)/d1 = 4 eta / (1 - eta)^2.  eta = 2^-24
+    (the fp32 neighbour of 1: gap 2.4e-7) and eta = 0 (exact tie) count as near-ties, eta = 2^-12 (gap 9.8e-4) does not."""
+    b = 40
+    w0 = np.array([[0.0, 0.0], [2.0, 0.0]])
+    for n_near, n_exact in [(0, 0), (3, 0), (5, 2)]:
+        X = np.zeros((2 * b, 2), dtype=np.float32)
+        X[:, 0] = np.float32(1.0) - np.float32(2.0 ** -12)
+        X[:n_near, 0] = np.float32(1.0) - np.float32(2.0 ** -24)
+        X[n_near:n_near + n_exact, 0] = 1.0
+        assert float(X[0, 0]) < 1.0 or n_near == 0
+        o = oracle.OracleASGD(X, k=2, W=1, b=b, lr=0.1, E=0, w0=w0)
+        a, gap = o.run_steps(1, dump=True)
+        assert o.near[0] == n_near + n_exact
+        assert np.all(a == 0)                                        # the nearer one, and the lower index on the tie
+        assert int((gap < 1e-6).sum()) == n_near + n_exact
+        if n_near:
+            assert 2.0e-7 < gap[0, 0, 0] < 2.6e-7
+        assert 9.0e-4 < gap[0, 0, -1] < 1.0e-3
+
+
 def test_zero_gradient_never_accepts(oracle):
     """G = 0 makes both sides of Eq. 4 equal; the strict '<' rejects."""
     x = np.array([2.0, 2.0], dtype=np.float32)

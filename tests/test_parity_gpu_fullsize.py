@@ -5,47 +5,34 @@
   - wider workload (k = d = 100, W = 512, b = 2000, E = 8): one epoch, all assignments and states;
   - contraction workload (k = 1024, d = 128, W = 256, b = 4096, E = 4): one epoch plus the first
     merge step, all assignments and states;
-  - HBM-scale workload (N = 2.5e9, W = 4096, E = 16; 100 GB of samples): the first two
-    communication rounds element by element (the oracle runs them on a compacted copy of the rows
-    those steps touch), then the whole epoch on properties that hold at any size.
+  - HBM-scale workload (N = 2.5e9, W = 4096, E = 16; 100 GB of samples): the whole epoch, round by
+    round (the oracle is fed the rows of one communication round at a time), every assignment,
+    every state at every round boundary, counters, Eq. 8 at the end; then the free-running mode.
 """
 import numpy as np
 import pytest
 
 from paper_1505_04956_amd import workloads
+from tests.parity_rules import NEAR_TIE, check_assignments, check_counters, follow_on_bound, mismatch_shift, rel_fro
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
 
-def compare(tag, g, o, ag, ao, gap, state_tol=1e-4):
-    """Bar: assignments are identical except at near-ties (oracle relative gap < 1e-6).  A near-tie that is
-    resolved the other way moves one sample between two centroids, after which that worker's state differs
-    from the oracle's by a few 1e-5 (relative) and later samples of the SAME worker whose gap is below that
-    perturbation may follow; those must stay below 1e-3 and are listed."""
+def compare(tag, g, o, ag, ao, gap, q_per_sample, state_tol=1e-4):
+    """The rules of tests/parity_rules.py at full size; mismatches are listed and counted by kind."""
     st = g.stats()
     W = o.w.shape[0]
-    wg = g.get_state().astype(np.float64).reshape(W, -1)
-    wo = o.w.reshape(W, -1)
-    err = np.linalg.norm(wg - wo, axis=1) / np.linalg.norm(wo, axis=1)
-    diff = ag != ao
-    print("\n[%s] %d assignments: mismatches %d, oracle near-ties %d, Parzen near-ties %d; max state err %.3g; "
+    err = rel_fro(g.get_state(), o.w)
+    print("\n[%s] %d assignments, oracle near-ties %d, Parzen near-ties %d; max state err %.3g; "
           "exact rechecks %d; messages sent/received/good %d/%d/%d (oracle %d/%d/%d); kernel %d, launches %d, %.3f ms"
-          % (tag, ag.size, diff.sum(), (gap < 1e-6).sum(), o.near[1], err.max(), st.exact_rechecks, st.sent,
+          % (tag, ag.size, (gap < NEAR_TIE).sum(), o.near[1], err.max(), st.exact_rechecks, st.sent,
              st.received, st.accepted, *o.counters.sum(0), st.kernel, st.launches, st.last_run_ms))
-    first_seen = {}
-    for t, i, n in zip(*np.nonzero(diff)):
-        print("   mismatch step %d worker %d sample %d: gpu %d oracle %d gap %.3g"
-              % (t, i, n, ag[t, i, n], ao[t, i, n], gap[t, i, n]))
-        if i not in first_seen:
-            first_seen[i] = t
-        if t == first_seen[i]:
-            assert gap[t, i, n] < 1e-6, "first mismatch of worker %d is not a near-tie" % i
-        else:
-            assert gap[t, i, n] < 1e-3, "mismatch of worker %d after a near-tie flip has a large gap" % i
-    assert np.all(np.isfinite(wg))
+    n_tie, n_round, n_follow = check_assignments(ag, ao, gap, follow_on_bound(err, o.w, q_per_sample))
+    print("[%s] mismatches: %d at near-ties of the oracle, %d from state rounding, %d follow-on" % (tag, n_tie, n_round, n_follow))
+    assert n_round <= 1 + ag.size // 10_000_000
+    assert np.all(np.isfinite(g.get_state()))
     assert err.max() <= state_tol
-    if o.near[1] == 0:
-        assert np.array_equal(g.worker_counters(), o.counters)
+    check_counters(g.worker_counters(), o.counters, o.parzen_near)
 
 
 def run_config(oracle, wl, steps, expect_kernel, expect_launches=None):
@@ -63,8 +50,8 @@ def run_config(oracle, wl, steps, expect_kernel, expect_launches=None):
     oracle.set_threads(16)
     o = oracle.OracleASGD(X.cpu().numpy(), k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
     ao, gap = o.run_steps(steps, dump=True)
-    compare(wl.name, g, o, ag, ao, gap)
     qg, qo = g.quant_error(0), o.quant_error(0)
+    compare(wl.name, g, o, ag, ao, gap, qo / wl.N)
     assert abs(qg - qo) <= 1e-4 * qo
     return g, o
 
@@ -90,51 +77,105 @@ def test_contraction_workload_full_size(oracle):
 
 
 def test_hbm_scale_workload(oracle):
+    """The 100 GB workload, the WHOLE epoch against the oracle: the samples stay on the device, the oracle is fed one
+    communication round at a time (the rows those 16 steps touch, copied shard by shard), and after every round all
+    assignments of the round, all worker states and the message counters are compared; Eq. 8 of the final state is
+    summed by the oracle over chunks of the samples.  Then the same epoch as ONE launch (what the benchmark times) must
+    give the same states bit for bit, and the free-running mode (the workload names both) is checked on properties."""
+    import time
     import torch
     from paper_1505_04956_amd import binding as B
     wl = workloads.CONFIGS[3]
     free, total = torch.cuda.mem_get_info()
     if free < 115e9:
         pytest.skip("needs 115 GB of free device memory, have %.0f GB" % (free / 1e9))
+    t_begin = time.time()
     X = workloads.generate_device(wl, device="cuda:0")                   # 100 GB
+    shards = X[:wl.W * wl.H].view(wl.W, wl.H, wl.d)
     g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed)
     g.load_shards(X)
-    # --- the first two rounds, element by element ---
-    steps = 2 * wl.E + 1                                                  # ends one step after the second merge point
-    g.enable_assign_dump(steps)
-    g.run_steps(steps)
-    assert g.stats().kernel == B.KERNEL_SMALL and g.stats().launches == 1
-    ag = g.assign_dump(steps)
-    g.disable_assign_dump()
-    rows = steps * wl.b
-    Xc = X[:wl.W * wl.H].view(wl.W, wl.H, wl.d)[:, :rows, :].contiguous().cpu().numpy().reshape(wl.W * rows, wl.d)
     oracle.set_threads(16)
-    o = oracle.OracleASGD(Xc, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
-    ao, gap = o.run_steps(steps, dump=True)
-    compare(wl.name + " first rounds", g, o, ag, ao, gap)
-    assert o.counters[:, 1].sum() == 2 * wl.W                             # every worker has merged twice
-    # --- the rest of the epoch: properties ---
-    w_before = g.get_state()
-    q_before = g.quant_error(0)
-    g.run_steps(wl.S - steps)
+    o = None
+    err_max = q_typ = None
+    flipped = set()
+    n_round = over = 0
+    shift = np.zeros(wl.W)
+    n_tie = n_follow = near = 0
+    worst = 0.0
+    t = 0
+    g.enable_assign_dump(wl.E)
+    while t < wl.S:
+        n = min(wl.E, wl.S - t)                                           # 38 rounds of 16 steps, then 2 steps
+        g.run_steps(n)
+        assert g.stats().kernel == B.KERNEL_SMALL and g.stats().launches == 1
+        ag = g.assign_dump(n)
+        Xw = shards[:, t * wl.b:(t + n) * wl.b, :].contiguous().cpu().numpy().reshape(wl.W * n * wl.b, wl.d)
+        if o is None:
+            o = oracle.OracleASGD(Xw, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+        else:
+            o.set_window(Xw, t)
+        ao, gap = o.run_steps(n, dump=True)
+        err = rel_fro(g.get_state(), o.w)
+        err_max = err if err_max is None else np.maximum(err_max, err)
+        if q_typ is None:
+            q_typ = oracle.quant_error(Xw, o.w[0]) / Xw.shape[0]           # Eq. 8 per sample, from the rows of the first round
+        a, r_, f_ = check_assignments(ag, ao, gap, follow_on_bound(err_max, o.w, q_typ), verbose=False, flipped=flipped)
+        n_round += r_
+        n_tie += a; n_follow += f_; near += int((gap < NEAR_TIE).sum())
+        worst = max(worst, float(err.max()))
+        # a worker's state may be off by 1e-4 plus what its counted assignment mismatches explain
+        shift += mismatch_shift(ag, ao, Xw.reshape(wl.W, n * wl.b, wl.d), o.w, wl.lr, wl.b)
+        allowed = 1e-4 + shift / np.linalg.norm(o.w.reshape(wl.W, -1), axis=1)
+        if not (np.all(np.isfinite(err)) and np.all(err <= allowed)):
+            for i_ in np.nonzero(~(err <= allowed))[0][:10]:
+                print("   step %d worker %d: state error %.3g > %.3g" % (t + n, i_, err[i_], allowed[i_]))
+        assert np.all(np.isfinite(err)) and np.all(err <= allowed), (t, err.max())
+        over = max(over, int((err > 1e-4).sum()))
+        check_counters(g.worker_counters(), o.counters, o.parzen_near)
+        t += n
+    g.disable_assign_dump()
     st = g.stats()
-    w_after = g.get_state()
-    q_after = g.quant_error(0)
     rounds = wl.S // wl.E
-    print("\n[%s epoch] %.3f ms for %d steps (%.3g samples/s); E(w) of worker 0 %.6g -> %.6g; "
-          "messages sent/received/good %d/%d/%d"
-          % (wl.name, st.last_run_ms, wl.S - steps, (wl.S - steps) * wl.W * wl.b / st.last_run_ms * 1e3,
-             q_before, q_after, st.sent, st.received, st.accepted))
-    assert st.steps == wl.S and st.launches == 1
-    assert np.all(np.isfinite(w_after))
-    assert st.sent == wl.W * rounds                                       # every worker sends once per round
-    assert st.received == wl.W * ((wl.S - 1) // wl.E)                     # ... and merges at every multiple of E
-    assert 0 < st.accepted <= st.received
-    assert q_after <= q_before * 1.001                                    # constant step size: no worse, up to SGD noise
-    # the states stay inside the convex hull box of the data they average
-    lo, hi = float(X[:1_000_000].min()), float(X[:1_000_000].max())
-    assert w_after.min() >= lo - 1.0 and w_after.max() <= hi + 1.0
-    assert not np.array_equal(w_before, w_after)
+    assert st.steps == wl.S and int(o.t[0]) == wl.S
+    assert st.sent == wl.W * rounds and st.received == wl.W * ((wl.S - 1) // wl.E) and 0 < st.accepted <= st.received
+    # Eq. 8 of worker 0's final state over all N rows: the oracle sums it chunk by chunk
+    qo = 0.0
+    chunk = 50_000_000
+    for lo in range(0, wl.N, chunk):
+        qo += oracle.quant_error(X[lo:lo + chunk].cpu().numpy(), o.w[0])
+    qg = g.quant_error(0)
+    print("\n[%s whole epoch] %d assignments: %d mismatches at near-ties of the oracle (%d near-ties), %d from state rounding, %d follow-on; worst "
+          "state error at a round boundary %.3g; Parzen near-ties %d; messages sent/received/good %d/%d/%d (oracle %d/%d/%d); "
+          "workers above 1e-4 at some boundary (explained by their mismatches): %d; E(w_0) gpu %.8g oracle %.8g; %.0f s"
+          % (wl.name, wl.S * wl.W * wl.b, n_tie, near, n_round, n_follow, worst, o.near[1], st.sent, st.received, st.accepted,
+             *o.counters.sum(0), over, qg, qo, time.time() - t_begin))
+    assert abs(qg - qo) <= 1e-4 * qo
+    assert n_round <= 1 + (wl.S * wl.W * wl.b) // 10_000_000
+    w_rounds = g.get_state()
+    g.close()
+    # --- the same epoch as one launch, as the benchmark runs it: bit for bit the same ---
+    one = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed)
+    one.load_shards(X)
+    one.run_epochs(1)
+    s1 = one.stats()
+    assert s1.launches == 1 and s1.steps == wl.S
+    assert np.array_equal(one.get_state(), w_rounds)
+    assert [s1.sent, s1.received, s1.accepted] == [st.sent, st.received, st.accepted]
+    print("[%s] one launch: %.3f ms (%.3g samples/s)" % (wl.name, s1.last_run_ms, wl.processed_per_epoch / s1.last_run_ms * 1e3))
+    one.close()
+    # --- free-running mode (no element-wise parity exists for it): properties, and Eq. 8 close to the deterministic run's ---
+    fr = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, mode=B.MODE_FREE_RUNNING)
+    fr.load_shards(X)
+    fr.run_epochs(1)
+    sf = fr.stats()
+    wf = fr.get_state()
+    qf = fr.quant_error(0)
+    print("[%s free-running] %.3f ms; E(w_0) %.8g (deterministic %.8g); sent/received/good %d/%d/%d"
+          % (wl.name, sf.last_run_ms, qf, qg, sf.sent, sf.received, sf.accepted))
+    assert np.all(np.isfinite(wf)) and sf.kernel == B.KERNEL_SMALL and sf.launches == 1
+    assert sf.sent == wl.W * rounds and 0 < sf.received <= sf.sent and 0 < sf.accepted <= sf.received
+    assert abs(qf - qg) <= 0.02 * qg
+    fr.close()
 
 
 def test_free_running_full_size():
