@@ -188,8 +188,11 @@ int asgd_get_mean_state(asgd_ctx *ctx, float *out_host, size_t out_bytes);
 
 /*
  * Quantization error of Eq. 8, E(w) = sum_i 1/2 * min_k |x_i - w_k|^2, over all N loaded
- * rows for the state of `worker` (>= 0) or the mean state (worker = -1).  Distances in
- * fp32 (direct form), summed in fp64.  *out is host memory.
+ * rows for the state of `worker` (>= 0) or the mean state (worker = -1).  fp32: the nearest
+ * centroid of a sample is found from expanded-form scores x.w_c - |w_c|^2/2 (any shape but the
+ * smallest ones: on the matrix cores), the distance to it is then formed directly as
+ * sum_j (x_j - w_cj)^2, so clusters far from the origin lose nothing to cancellation; the sum
+ * over the samples is fp64 in a fixed order.  *out is host memory.
  */
 int asgd_quant_error(asgd_ctx *ctx, int worker, double *out);
 

@@ -1085,8 +1085,9 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 }
 
 // Eq. 8 for the contraction shapes: the same matrix-core scores as phase 1 of the step kernel, for ONE state and
-// all N samples.  min_c |x - w_c|^2 / 2 = |x|^2 / 2 - max_c (x.w_c - |w_c|^2/2): only the running maximum per sample
-// is kept.  A workgroup (8 waves) walks tiles of 256 samples with a fixed stride, every lane pair adds its samples
+// all N samples.  The centroid with the largest score x.w_c - |w_c|^2/2 is the nearest one: only the running
+// maximum per sample is kept, with the place it came from in its low mantissa bits, and the distance to that
+// centroid is then formed directly as sum_j (x_j - w_cj)^2 (no cancellation).  A workgroup (8 waves) walks tiles of 256 samples with a fixed stride, every lane pair adds its samples
 // in fp64 in a fixed order, the partials are added in a fixed order: the result does not depend on scheduling.
 template <int NCH>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void quant_error_mfma_kernel(
@@ -1146,21 +1147,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const bool ok = n < N;
         const float *row = x + (size_t)(ok ? n : 0) * d;
         float4 xf[NCH];
-        float x2 = 0.0f;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             const int col = ch * 8 + col0;
             xf[ch] = *reinterpret_cast<const float4 *>(row + (col < collim ? col : collim));
-            if (ch * 8 + 4 * half < d) {            // a real column (clamped ones repeat data and meet zero state rows)
-                x2 = fmaf(xf[ch].x, xf[ch].x, x2); x2 = fmaf(xf[ch].y, xf[ch].y, x2);
-                x2 = fmaf(xf[ch].z, xf[ch].z, x2); x2 = fmaf(xf[ch].w, xf[ch].w, x2);
-            }
         }
         float4 st[NST];
         __syncthreads();                 // nobody still reads the stage (and hs is complete)
         fetch_block(st, 0);
         store_block(st, Ws);
-        float best = -INFINITY;
+        float best = -INFINITY;         // largest score so far, the number of its accumulator register in its low 5 bits
+        int bestcb = 0;                 // ... and the block it came from
         for (int cb = 0; cb < nblocks; ++cb) {
             __syncthreads();
             const float *Wc = Ws + (cb & 1) * WB * DP;
@@ -1200,12 +1197,40 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 a0 = n0; a1 = n1;
             }
             if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
+            float bm = -INFINITY;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) best = fmaxf(best, fmaxf(acc0[r], acc1[r]));
+            for (int r = 0; r < 16; ++r) {
+                const float t0 = __uint_as_float((__float_as_uint(acc0[r]) & 0xFFFFFFE0u) | (unsigned)r);
+                const float t1 = __uint_as_float((__float_as_uint(acc1[r]) & 0xFFFFFFE0u) | (unsigned)(16 + r));
+                bm = fmaxf(bm, fmaxf(t0, t1));
+            }
+            if (bm > best) { best = bm; bestcb = cb; }
         }
-        best = fmaxf(best, __shfl_xor(best, 32, 64));       // the other half-wave saw the other centroid rows
-        x2 += __shfl_xor(x2, 32, 64);                       // ... and holds the other half of the dimensions
-        if (half == 0 && ok) sum += (double)fmaxf(0.5f * x2 - best, 0.0f);
+        // The scores only pick the centroid; the distance to it is formed directly, sum_j (x_j - w_cj)^2, so that no
+        // |x|^2/2 - score cancellation enters the sum (tight clusters far from the origin).  Among scores that agree to
+        // the rounding error (and the 5 tag bits) any may win: their distances differ by less than that error.
+        int c;
+        {
+            const int r = (int)(__float_as_uint(best) & 31u);
+            // accumulator register r of half-wave h holds row 8*((r & 15) / 4) + 4*h + (r & 3) of the block (+32: second accumulator)
+            c = bestcb * WB + (r & 16) * 2 + 8 * ((r & 15) >> 2) + 4 * half + (r & 3);
+            const float ob = __shfl_xor(best, 32, 64);       // the other half-wave saw the other centroid rows
+            const int oc = __shfl_xor(c, 32, 64);
+            if (ob > best || (ob == best && oc < c)) c = oc;
+            c = c < k ? c : k - 1;
+        }
+        float d2 = 0.0f;
+        const float *wrow = w + (size_t)c * d;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            if (ch * 8 + 4 * half < d) {            // a real column (clamped ones repeat data)
+                const float4 wv4 = *reinterpret_cast<const float4 *>(wrow + ch * 8 + col0);
+                const float e0 = xf[ch].x - wv4.x, e1 = xf[ch].y - wv4.y, e2 = xf[ch].z - wv4.z, e3 = xf[ch].w - wv4.w;
+                d2 = fmaf(e0, e0, d2); d2 = fmaf(e1, e1, d2); d2 = fmaf(e2, e2, d2); d2 = fmaf(e3, e3, d2);
+            }
+        }
+        d2 += __shfl_xor(d2, 32, 64);                       // the other half-wave holds the other half of the dimensions
+        if (half == 0 && ok) sum += (double)(0.5f * d2);
     }
     sum = wave_sum_d(sum);
     if (lane == 0) red[wave] = sum;

@@ -516,3 +516,21 @@ def test_mean_state(B, oracle):
     qg = g.quant_error(-1)
     qo = oracle.quant_error(X, o.w.mean(0))
     assert abs(qg - qo) <= TOL * qo
+
+
+@pytest.mark.parametrize("k,d,kernel_name", [(10, 10, "streaming"), (64, 32, "matrix-core"), (7, 5, "generic")])
+def test_quant_error_of_tight_clusters_far_from_the_origin(B, oracle, k, d, kernel_name):
+    """Eq. 8 where |x|^2 is ten orders of magnitude above the distances: centres in [0, 1000]^d, sigma = 0.01.  An
+    expanded-form evaluation |x|^2/2 - max score loses everything to cancellation in fp32; the kernels form the winner's
+    distance directly."""
+    rng = np.random.default_rng(17)
+    N = 60_000 + 13
+    centres = rng.uniform(0.0, 1000.0, size=(k, d))
+    X = (centres[rng.integers(0, k, size=N)] + 0.01 * rng.standard_normal((N, d))).astype(np.float32)
+    w = (centres + 0.02 * rng.standard_normal((k, d))).astype(np.float32)
+    g = B.ASGD(k, d, 1, 64, 0.05)
+    g.load_shards(to_dev(X))
+    g.set_state(0, w)
+    qg, qo = g.quant_error(0), oracle.quant_error(X, w.astype(np.float64))
+    print("\n[Eq. 8, %s kernel] gpu %.8g oracle %.8g (per sample %.3g)" % (kernel_name, qg, qo, qo / N))
+    assert abs(qg - qo) <= TOL * qo
