@@ -91,7 +91,21 @@ enum {
                                     buffers' accepted copies of the same row; rows that did not travel take
                                     the plain step.  "received" then counts buffers with a non-empty row,
                                     "accepted" buffers with an accepted row.  May only be set before the
-                                    first step (ASGD_ESTATE after).  Available in all three kernels. */
+                                    first step (ASGD_ESTATE after).  Available in all three kernels; in the
+                                    matrix-core kernel only while W*k*d <= ASGD_MFMA_PARTS_MAX_STATE (the sizes
+                                    its tests cover: the only batch of larger runs of that combination ended in
+                                    a device fault that was never explained).  Above that the automatic choice
+                                    takes the shape-agnostic kernel and an explicit ASGD_KERNEL_MFMA fails with
+                                    ASGD_EINVAL. */
+};
+enum { ASGD_MFMA_PARTS_MAX_STATE = 1 << 18 };
+enum {
+    ASGD_OPT_WAIT_POLLS = 12,       /* test hook: polls a workgroup may spend, in total, on the waits of one launch
+                                       (0 = the library's default of some 10^5, i.e. a fraction of a second) */
+    ASGD_OPT_DROP_UNANNOUNCED = 13  /* test hook: 1 = the recipient does not know which messages ASGD_OPT_DROP_RATE
+                                       loses, so a run that is one launch waits for them until its poll budget is
+                                       gone and then returns ASGD_ESYNC (every kernel still ends normally); 0 (default):
+                                       a lost message is skipped at once */
 };
 enum { ASGD_MODE_DETERMINISTIC = 0, ASGD_MODE_FREE_RUNNING = 1 };
 enum { ASGD_LR_CONST = 0, ASGD_LR_INV_COUNT = 1 };

@@ -14,7 +14,7 @@ import numpy as np
 from . import build as _build
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP, ESYNC = 0, -1, -2, -3, -4, -5
-OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE, OPT_BUFFERS, OPT_PARTS = range(1, 12)
+OPT_EXCHANGE_EVERY, OPT_SEED, OPT_MODE, OPT_PARZEN, OPT_LR_MODE, OPT_DROP_RATE, OPT_KERNEL, OPT_TUNE, OPT_COOPERATIVE, OPT_BUFFERS, OPT_PARTS, OPT_WAIT_POLLS, OPT_DROP_UNANNOUNCED = range(1, 14)
 MODE_DETERMINISTIC, MODE_FREE_RUNNING = 0, 1
 LR_CONST, LR_INV_COUNT = 0, 1
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_SMALL, KERNEL_MFMA = 0, 1, 2, 3

@@ -24,6 +24,8 @@ struct asgd_ctx {
     int parts = 1;              // partial messages: parts of a state (1 = whole states)
     size_t slot_bytes_one = 0;  // bytes of both parities of ONE buffer per worker
     int cooperative = 1;
+    int wait_polls = 0;
+    int drop_unannounced = 0;
 
     int device = 0;
     hipStream_t stream = nullptr;
@@ -94,6 +96,8 @@ StepParams make_params(const asgd_ctx *c)
     p.drop_thr = (uint32_t)llround(c->drop_rate * (double)(1u << 24));
     p.tune = c->tune;
     p.cooperative = c->cooperative;
+    p.wait_polls = c->wait_polls;
+    p.drop_unannounced = c->drop_unannounced;
     return p;
 }
 
@@ -268,6 +272,14 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
             ctx->parts = (int)value;
             ctx->fill_kernel = 0;          // the first run empties the buffers for its kernel
             return ASGD_OK;
+        case ASGD_OPT_WAIT_POLLS:
+            if (value < 0 || value > (double)(1 << 24) || value != floor(value)) return ASGD_EINVAL;
+            ctx->wait_polls = (int)value;
+            return ASGD_OK;
+        case ASGD_OPT_DROP_UNANNOUNCED:
+            if (value != 0 && value != 1) return ASGD_EINVAL;
+            ctx->drop_unannounced = (int)value;
+            return ASGD_OK;
         case ASGD_OPT_TUNE:
             if (value < 0 || value > 1000 || value != floor(value)) return ASGD_EINVAL;
             ctx->tune = (int)value;
@@ -360,7 +372,11 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     if (ctx->W > 1 && ctx->E > 0 && ctx->nb > ctx->W - 1) return ASGD_EINVAL;       // a message has nb different recipients
     const bool small_ok = small_kernel_supports(ctx->k, ctx->d, ctx->b) && ctx->lr_mode == ASGD_LR_CONST &&
                           ((ctx->nb == 1 && ctx->parts == 1) || ((ctx->tune >> 2) & 3) != 1);   // several buffers, partial messages: not in the private-rows shape
-    const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST;
+    // Partial messages in the matrix-core kernel are limited to the sizes its parity tests cover: the one batch of
+    // full-size runs of that combination ended with a device fault whose cause was never found, so larger runs of
+    // it are refused (an explicit choice of the kernel) or go to the shape-agnostic kernel (automatic choice).
+    const bool mfma_parts_ok = ctx->parts == 1 || (double)ctx->W * ctx->k * ctx->d <= (double)ASGD_MFMA_PARTS_MAX_STATE;
+    const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST && mfma_parts_ok;
     if (kernel == ASGD_KERNEL_AUTO) {
         // the matrix-core kernel pays off once the k x d contraction dominates a step
         kernel = small_ok ? ASGD_KERNEL_SMALL

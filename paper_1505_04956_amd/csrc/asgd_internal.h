@@ -80,6 +80,8 @@ struct StepParams {
     uint32_t drop_thr;
     int tune;              // variant selector for experiments (0 = default)
     int cooperative;       // use the cooperative launch API for single-launch runs
+    int wait_polls;        // polls a workgroup may spend on all the waits of a launch (test hook; 0 = the kernel's default)
+    int drop_unannounced;  // test hook: the recipient does not know which messages the loss hook drops and waits for them
 };
 
 // Launchers (each returns the hipError_t of its launch).

@@ -247,7 +247,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
     const float xn2 = *xnorm2max_ptr;
 
-    if (threadIdx.x == 0) { s_wait_failed = 0; s_wait_budget = MF_WAIT_BUDGET; }       // read after the barriers below
+    if (threadIdx.x == 0) { s_wait_failed = 0; s_wait_budget = p.wait_polls > 0 ? p.wait_polls : MF_WAIT_BUDGET; }       // read after the barriers below
     // ---- h_c = -|w_c|^2/2 and max_c |w_c|^2 ----
     float wn2max = 0.0f;
     for (int c0 = wave * RB; c0 < g.kpad; c0 += MF_WAVES * RB) {
@@ -684,7 +684,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (sync) {
                         const long long rs = r_now - 1;
                         const int sender = (i - shift_deterministic(p.seed, rs, p.W, n) + p.W) % p.W;
-                        if (!message_dropped(p.seed, rs, sender, p.drop_thr, n) && !s_wait_failed &&
+                        if ((p.drop_unannounced || !message_dropped(p.seed, rs, sender, p.drop_thr, n)) && !s_wait_failed &&
                             !mf_wait_flag(stp, (int)rs, false, &s_wait_budget)) {
                             s_wait_failed = 1;
                             atomicOr(p.error_flag, 1);

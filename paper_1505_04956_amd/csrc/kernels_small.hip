@@ -361,7 +361,7 @@ struct SmallKeeper {
         inv_b = 1.0f / (float)p.b;
         eps = p.eps;
         wait_failed = 0;
-        budget = WAIT_BUDGET;
+        budget = p.wait_polls > 0 ? p.wait_polls : WAIT_BUDGET;
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
             mslot[n] = nullptr; peer[n] = 0; ackv[n] = 0;
@@ -521,7 +521,7 @@ struct SmallKeeper {
                     // message is one of those the loss hook drops
                     int from = i - shift_of(p, round - 1, n);
                     if (from < 0) from += W;
-                    if (!(p.drop_thr != 0 && message_dropped(p.seed, round - 1, from, p.drop_thr, n))) {
+                    if (p.drop_unannounced || !(p.drop_thr != 0 && message_dropped(p.seed, round - 1, from, p.drop_thr, n))) {
                         while (budget > 0 && !has_ext[n]) {
                             __builtin_amdgcn_s_sleep(4);
                             --budget;

@@ -76,6 +76,24 @@ def test_contraction_workload_full_size(oracle):
     assert o.counters[:, 1].sum() == wl.W
 
 
+@pytest.mark.skip(reason="partial messages (Sec. 4.4) on the matrix-core kernel at full size: the only batch of such runs "
+                         "(k = d = 100 and k = 1024, d = 128 workloads, P = 1/4/16, also with 4 buffers) ended with the GPU box "
+                         "reporting a fault or a hung queue; its log was lost with the box and no cause was found by reading "
+                         "the code, so the case is not run again and the library refuses the combination above the tested sizes")
+def test_partial_messages_matrix_core_full_size(oracle):
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[2]
+    X = workloads.generate_device(wl, device="cuda:0")
+    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, parts=4, kernel=B.KERNEL_MFMA)
+    g.load_shards(X)
+    g.enable_assign_dump(wl.S)
+    g.run_steps(wl.S)
+    ag = g.assign_dump(wl.S)
+    o = oracle.OracleASGD(X.cpu().numpy(), k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed, parts=4)
+    ao, gap = o.run_steps(wl.S, dump=True)
+    compare(wl.name + " parts=4", g, o, ag, ao, gap, o.quant_error(0) / wl.N)
+
+
 def test_hbm_scale_workload(oracle):
     """The 100 GB workload, the WHOLE epoch against the oracle: the samples stay on the device, the oracle is fed one
     communication round at a time (the rows those 16 steps touch, copied shard by shard), and after every round all
