@@ -103,6 +103,23 @@ def quant_error(X, w) -> float:
     return float(lib().asgd_oracle_quant_error(X.ctypes.data, X.shape[0], d, k, w))
 
 
+def centre_error(w, centres) -> float:
+    """Error against the centres the data was generated from, as the paper uses it for its synthetic sets (Sec. 5.3, last
+    paragraph: the distance between the generating centres and the returned ones; a relative measure).  The paper prints
+    no formula; reading: for every generating centre the Euclidean distance to the nearest returned centroid, averaged
+    over the generating centres.  Plain loops, fp64."""
+    w = np.asarray(w, dtype=np.float64)
+    centres = np.asarray(centres, dtype=np.float64)
+    total = 0.0
+    for c in centres:
+        nearest = np.inf
+        for row in w.reshape(-1, centres.shape[1]):
+            dist = float(np.sqrt(np.sum((c - row) * (c - row))))
+            nearest = min(nearest, dist)
+        total += nearest
+    return total / len(centres)
+
+
 def drop_threshold(rate: float) -> int:
     """24-bit fixed-point loss probability used by the message-loss test hook."""
     return int(round(float(rate) * (1 << 24)))

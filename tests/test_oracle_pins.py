@@ -659,6 +659,25 @@ def test_stored_values_of_tiny_workload(oracle):
         assert abs(nv["quant_error_worker0"] - sv["quant_error_worker0"]) <= 1e-12 * sv["quant_error_worker0"], name
 
 
+def test_centre_error_hand_example(oracle):
+    """Three generating centres (0,0), (4,0), (0,3) and returned centroids (1,0), (4,1), (10,10): the nearest returned
+    centroid is at distance 1, 1 and sqrt(10) (to (1,0); (4,1) is at sqrt(20)), so the error is (2 + sqrt 10) / 3.  A
+    squared distance would give 4, a maximum 3.16, a mean over the returned centroids something else again; the
+    far centroid (10,10) must not matter, nor the order."""
+    centres = np.array([[0.0, 0.0], [4.0, 0.0], [0.0, 3.0]])
+    w = np.array([[1.0, 0.0], [4.0, 1.0], [10.0, 10.0]])
+    want = (2.0 + np.sqrt(10.0)) / 3.0
+    assert abs(oracle.centre_error(w, centres) - want) < 1e-15
+    assert abs(oracle.centre_error(w[::-1], centres[[2, 0, 1]]) - want) < 1e-15
+    assert oracle.centre_error(centres, centres) == 0.0
+    # the evaluation helper of the package (NumPy, vectorised) is the same quantity
+    wl = workloads.CONFIGS[0]
+    c, _ = workloads.mixture_parameters(wl)
+    rng = np.random.default_rng(5)
+    wr = rng.uniform(0, 10, size=(wl.k, wl.d))
+    assert abs(workloads.centre_error(wr, wl) - oracle.centre_error(wr, c)) < 1e-12
+
+
 def test_centre_error_convergence_of_tiny_workload(oracle):
     """Shape of the paper's convergence figures on the synthetic generator (Sec. 5.4): the distance between
     the generator's centres and the returned ones falls with the number of samples touched; the helper is

@@ -196,28 +196,60 @@ def test_hbm_scale_workload(oracle):
     fr.close()
 
 
-def test_free_running_full_size():
-    """Free-running mode (the paper's races, Sec. 4.4) at the streaming workload's full size, against the
-    deterministic and the silent run on the same data: no element-wise parity exists for it, so properties:
-    finite states, every worker sends once per round, Eq. 8 of worker 0 and of the mean state within 2 % of
-    the deterministic run's and not worse than the silent run's by more than 2 %."""
+@pytest.mark.parametrize("config", [1, 2, 4])
+def test_free_running_full_size(config):
+    """Free-running mode (the paper's races, Sec. 4.4) at full size on the streaming, the wider and the contraction
+    workload, over three schedule seeds, against the deterministic and the silent run on the same data: no element-wise
+    parity exists for it, so properties: finite states, every worker sends once per round, nobody receives more than
+    was sent, Eq. 8 of worker 0 within 3 % of the deterministic run's and not worse than the silent run's by more
+    than 3 %.  Prints the kernel time per epoch of the three modes (the cost of the exchange)."""
     from paper_1505_04956_amd import binding as B
-    wl = workloads.CONFIGS[1]
+    wl = workloads.CONFIGS[config]
     X = workloads.generate_device(wl, device="cuda:0")
-    res = {}
-    for name, kw in (("deterministic", dict(E=wl.E)), ("free", dict(E=wl.E, mode=B.MODE_FREE_RUNNING)), ("silent", dict(E=0))):
-        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, seed=wl.schedule_seed, **kw)
-        g.load_shards(X)
-        g.run_epochs(2)
-        st = g.stats()
-        w = g.get_state()
-        assert np.all(np.isfinite(w)) and st.kernel == B.KERNEL_SMALL and st.launches == 1
-        res[name] = (g.quant_error(0), g.quant_error(-1), st.sent, st.received, st.accepted, st.last_run_ms)
-        print("[%s] E(w_0) %.6g  E(mean w) %.6g  sent/received/good %d/%d/%d  %.3f ms" % ((name,) + res[name]))
-        g.close()
+    kernel = B.KERNEL_SMALL if config == 1 else B.KERNEL_MFMA
+    silent = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=0)
+    silent.load_shards(X)
+    silent.run_epochs(2)
+    qs, ms_s = silent.quant_error(0), silent.stats().last_run_ms
+    assert silent.stats().sent == 0 and silent.stats().kernel == kernel
+    silent.close()
     rounds = (2 * wl.S) // wl.E
-    assert res["deterministic"][2] == res["free"][2] == wl.W * rounds and res["silent"][2] == 0
-    assert 0 < res["free"][3] <= res["free"][2] and 0 < res["free"][4] <= res["free"][3]
-    for q in (0, 1):
-        assert abs(res["free"][q] - res["deterministic"][q]) <= 0.02 * res["deterministic"][q]
-        assert res["free"][q] <= 1.02 * res["silent"][q]
+    for seed in (1, 2, 3):
+        res = {}
+        for name, mode in (("deterministic", B.MODE_DETERMINISTIC), ("free", B.MODE_FREE_RUNNING)):
+            g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=seed, mode=mode)
+            g.load_shards(X)
+            g.run_epochs(2)
+            st = g.stats()
+            assert np.all(np.isfinite(g.get_state())) and st.kernel == kernel
+            res[name] = (g.quant_error(0), st.sent, st.received, st.accepted, st.last_run_ms)
+            g.close()
+        qd, qf = res["deterministic"][0], res["free"][0]
+        print("[%s seed %d] E(w_0): deterministic %.6g free %.6g silent %.6g; free sent/received/good %d/%d/%d; "
+              "ms per 2 epochs: deterministic %.3f free %.3f silent %.3f"
+              % (wl.name, seed, qd, qf, qs, *res["free"][1:4], res["deterministic"][4], res["free"][4], ms_s))
+        assert res["deterministic"][1] == res["free"][1] == wl.W * rounds
+        assert res["deterministic"][2] == wl.W * ((2 * wl.S - 1) // wl.E)
+        assert 0 < res["free"][2] <= res["free"][1] and 0 < res["free"][3] <= res["free"][2]
+        assert abs(qf - qd) <= 0.03 * qd
+        assert qf <= 1.03 * qs
+
+
+def test_convergence_curves_match_the_oracle(oracle):
+    """The convergence table of the tiny workload (Eq. 8 per sample and the error against the generating centres
+    after every epoch: the shape of the paper's convergence figures, Sec. 5.4) from the HIP path and from the oracle."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[0]
+    X = workloads.generate_host(wl)
+    centres, _ = workloads.mixture_parameters(wl)
+    import torch
+    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed)
+    g.load_shards(torch.from_numpy(X).to("cuda:0"))
+    o = oracle.OracleASGD(X, k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+    for ep in range(1, wl.epochs + 1):
+        g.run_epochs(1)
+        o.run_epochs(1)
+        qg, qo = g.quant_error(0) / wl.N, o.quant_error(0) / wl.N
+        cg, co = workloads.centre_error(g.get_state(0), wl), oracle.centre_error(o.w[0], centres)
+        print("epoch %d: E(w_0)/N gpu %.7f oracle %.7f; centre error gpu %.6f oracle %.6f" % (ep, qg, qo, cg, co))
+        assert abs(qg - qo) <= 1e-4 * qo and abs(cg - co) <= 1e-4 * co
