@@ -65,7 +65,7 @@ def cpu_baseline(wl, X):
         o.run_steps(steps)
         dt += time.perf_counter() - t0
     n = reps * steps * wl.W * wl.b
-    return {"value": n / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
+    return {"value": n / dt, "unit": "samples/s", "cores": cores, "nproc": os.cpu_count(), "kind": "oracle",
             "sample": "%d x the first %d steps (an epoch has %d) of the same workload, all %d workers: %d samples in "
                       "%.1f s, fp64, %d OpenMP threads over workers" % (reps, steps, wl.S, wl.W, n, dt, cores)}
 
@@ -92,6 +92,12 @@ def main():
                     help="start the single-launch kernel with a plain launch instead of a cooperative one "
                          "(same kernel, same grid); needed under rocprofv3, whose tool library crashes at "
                          "process exit after cooperative launches")
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="untimed device time spent on the same epochs before the warmup steps, until the clocks of a "
+                         "freshly woken device have settled (the first few dozen launches of a process run up to 10 %% "
+                         "slower); reported in the JSON line; 0 switches it off")
+    ap.add_argument("--no-exchange-overhead", action="store_true",
+                    help="skip the two extra timed runs (free-running, silent) behind the exchange_overhead object")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the sample array (known size: N*d*4 bytes read and "
                          "written), so that a counter profile of this command can be scaled")
@@ -120,20 +126,33 @@ def main():
         torch.mul(X, 1.0, out=Y)      # an elementwise kernel: reads N*d*4 bytes, writes N*d*4 bytes
         torch.cuda.synchronize()
         del Y
-    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=(0 if args.mode == "silent" else wl.E), seed=wl.schedule_seed,
-               mode=(B.MODE_FREE_RUNNING if args.mode == "free" else B.MODE_DETERMINISTIC), tune=args.tune,
-               cooperative=not args.plain_launch, buffers=args.buffers, parts=args.parts)
-    g.load_shards(X)
+    def context(mode):
+        c = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=(0 if mode == "silent" else wl.E), seed=wl.schedule_seed,
+                   mode=(B.MODE_FREE_RUNNING if mode == "free" else B.MODE_DETERMINISTIC), tune=args.tune,
+                   cooperative=not args.plain_launch, buffers=args.buffers, parts=args.parts)
+        c.load_shards(X)
+        return c
+
+    def timed(c, steps):
+        """`steps` epochs, one library call each; wall time over all of them and the kernel time of each."""
+        ms = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            c.run_epochs(1)                   # returns after the device has finished
+            ms.append(c.last_run_ms())
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ms
+
+    g = context(args.mode)
+    settle_epochs, settle_ms = 0, 0.0
+    while settle_ms < args.settle_ms and settle_epochs < 10000:
+        g.run_epochs(1)
+        settle_ms += g.last_run_ms()
+        settle_epochs += 1
     for _ in range(args.warmup):
         g.run_epochs(1)
-    torch.cuda.synchronize()
-    kernel_ms = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        g.run_epochs(1)                       # returns after the device has finished
-        kernel_ms.append(g.last_run_ms())
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed, kernel_ms = timed(g, args.steps)
     st = g.stats()
 
     samples = wl.processed_per_epoch
@@ -166,6 +185,24 @@ def main():
         "stats": {"messages_sent": int(st.sent), "messages_received": int(st.received),
                   "messages_accepted": int(st.accepted), "exact_rechecks": int(st.exact_rechecks)},
     }
+    out["settle"] = {"epochs": settle_epochs, "device_ms": settle_ms,
+                     "note": "untimed, before the warmup steps: clock transient of a freshly started process"}
+    if not args.no_exchange_overhead:
+        # the cost of the exchange (Sec. 4.4: it must stay small beside the update itself): kernel time of one epoch
+        # with the seeded deterministic schedule, free-running, and with no exchange at all, same data, same run
+        per_mode = {args.mode: avg_kernel_ms}
+        for mode in ("deterministic", "free", "silent"):
+            if mode not in per_mode:
+                c = context(mode)
+                for _ in range(args.warmup):
+                    c.run_epochs(1)
+                _, ms = timed(c, args.steps)
+                per_mode[mode] = sum(ms) / len(ms)
+                c.close()
+        out["exchange_overhead"] = {
+            "kernel_ms": per_mode, "unit": "ms per epoch",
+            "deterministic_over_silent": per_mode["deterministic"] / per_mode["silent"] - 1.0,
+            "free_over_silent": per_mode["free"] / per_mode["silent"] - 1.0}
     if args.quant_error:
         out["stats"]["quant_error_worker0"] = g.quant_error(0)
     if not args.no_cpu_baseline:

@@ -48,11 +48,20 @@ _lib = None
 
 
 def lib():
-    """The loaded library.  Builds it only if no built library is present."""
+    """The loaded library.  Builds it only if no built library is present; warns if the one present is stale."""
     global _lib
     if _lib is None:
         if not os.path.exists(_build.LIB_PATH):
             _build.build_library(verbose=False)
+        elif _build.is_stale():
+            # a source is newer than the built library: say so loudly, but run what is built (a build belongs before
+            # the run, not inside it; ASGD_REBUILD_STALE=1 asks for it here all the same)
+            if os.environ.get("ASGD_REBUILD_STALE") == "1":
+                _build.build_library(verbose=False)
+            else:
+                import warnings
+                warnings.warn("libasgd_hip.so is older than its sources: run `python -m paper_1505_04956_amd.build` "
+                              "(or __graft_entry__.build()); loading the old library", RuntimeWarning, stacklevel=2)
         L = C.CDLL(_build.LIB_PATH)
         vp, i64, u64, dbl = C.c_void_p, C.c_int64, C.c_uint64, C.c_double
         sig = {
