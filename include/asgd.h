@@ -161,9 +161,33 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
 int asgd_set_state(asgd_ctx *ctx, int worker, const float *w_host);
 
 /* Set the step counter t (>= 0) when continuing an earlier run.  Exchange buffers are
-   emptied; a run resumed at a multiple of E therefore equals the uninterrupted run only
-   if the last message of the earlier run is not needed (E = 0) or t is not a merge point. */
+   emptied: at a multiple of E the messages of the round just finished are in flight
+   (Alg. 5: sent in line 9 of one step, looked at in line 5 of the next), so a run resumed
+   there equals the uninterrupted one only if asgd_set_exchange() hands them over too. */
 int asgd_set_step(asgd_ctx *ctx, int64_t t);
+
+/*
+ * The messages in flight (Alg. 5 lines 5 and 9, Eq. 3 / Eq. 6: N external buffers per
+ * worker; Sec. 4 "Initialization": a run may start from the result of an earlier one), in
+ * a layout that does not depend on the kernel that ran:
+ *   values_host  float [buffers][W][k][d], host memory: the rows waiting in buffer n of
+ *                worker i; rows that a partial message (Sec. 4.4) does not carry, and
+ *                empty buffers, are zeros.
+ *   rounds_host  int32 [buffers][W], host memory: the round the message was sent in,
+ *                -1 = nothing waiting.
+ * Deterministic mode: messages wait exactly when t is a positive multiple of E, and all
+ * carry round t/E - 1; anywhere else every entry is -1.  Free-running mode: whatever the
+ * buffers hold at this moment (the newest message of a buffer; its rows only).
+ * asgd_get_exchange() copies them out (sizes in bytes are checked: ASGD_EINVAL if too
+ * small).  asgd_set_exchange() is called after asgd_set_state() and asgd_set_step(t) of a
+ * continued run; the library keeps a host copy until the next run, which writes it into
+ * the buffers in its kernel's format.  A deterministic run continued this way at a merge
+ * point is bit-identical to the uninterrupted run.  ASGD_EINVAL: a round that cannot wait
+ * at step t (deterministic mode: anything but -1 and t/E - 1 at a merge point).
+ * The same conversion happens by itself when ASGD_OPT_KERNEL changes between two runs.
+ */
+int asgd_get_exchange(asgd_ctx *ctx, float *values_host, size_t values_bytes, int32_t *rounds_host, size_t rounds_bytes);
+int asgd_set_exchange(asgd_ctx *ctx, const float *values_host, const int32_t *rounds_host);
 
 /*
  * Run `epochs` passes over every shard: epochs * S steps of Alg. 5 lines 6-10 per

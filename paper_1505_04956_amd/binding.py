@@ -25,7 +25,7 @@ SYMBOLS = (
     "asgd_run_epochs", "asgd_run_steps", "asgd_set_assign_dump", "asgd_get_state",
     "asgd_get_mean_state", "asgd_quant_error", "asgd_last_run_ms", "asgd_get_stats", "asgd_get_worker_counters",
     "asgd_schedule_peer", "asgd_schedule_peer_n", "asgd_last_hip_error", "asgd_destroy", "asgd_strerror",
-    "asgd_quant_error_noalloc",
+    "asgd_quant_error_noalloc", "asgd_get_exchange", "asgd_set_exchange",
 )
 
 
@@ -70,6 +70,8 @@ def lib():
             "asgd_load_shards": (C.c_int, [vp, vp, i64, vp]),
             "asgd_set_state": (C.c_int, [vp, C.c_int, vp]),
             "asgd_set_step": (C.c_int, [vp, i64]),
+            "asgd_get_exchange": (C.c_int, [vp, vp, C.c_size_t, vp, C.c_size_t]),
+            "asgd_set_exchange": (C.c_int, [vp, vp, vp]),
             "asgd_run_epochs": (C.c_int, [vp, C.c_int]),
             "asgd_run_steps": (C.c_int, [vp, i64]),
             "asgd_set_assign_dump": (C.c_int, [vp, vp, C.c_size_t]),
@@ -125,6 +127,19 @@ def asgd_set_state(h, worker, w_host: np.ndarray):
 
 def asgd_set_step(h, t):
     _check(lib().asgd_set_step(h, t), "asgd_set_step")
+
+
+def asgd_get_exchange(h, values: np.ndarray, rounds: np.ndarray):
+    assert values.dtype == np.float32 and rounds.dtype == np.int32
+    assert values.flags["C_CONTIGUOUS"] and rounds.flags["C_CONTIGUOUS"]
+    _check(lib().asgd_get_exchange(h, values.ctypes.data, values.nbytes, rounds.ctypes.data, rounds.nbytes),
+           "asgd_get_exchange", h)
+
+
+def asgd_set_exchange(h, values: np.ndarray, rounds: np.ndarray):
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    rounds = np.ascontiguousarray(rounds, dtype=np.int32)
+    _check(lib().asgd_set_exchange(h, values.ctypes.data, rounds.ctypes.data), "asgd_set_exchange", h)
 
 
 def asgd_run_epochs(h, epochs):
@@ -193,7 +208,7 @@ def asgd_destroy(h):
 class ASGD:
     def __init__(self, k, d, W, b, lr, E=0, seed=1, mode=MODE_DETERMINISTIC, parzen=True,
                  lr_mode=LR_CONST, drop_rate=0.0, kernel=KERNEL_AUTO, tune=0, cooperative=True, buffers=1, parts=1):
-        self.k, self.d, self.W, self.b = k, d, W, b
+        self.k, self.d, self.W, self.b, self.buffers = k, d, W, b, buffers
         self.h = asgd_create(k, d, W, b, lr)
         for key, val in ((OPT_EXCHANGE_EVERY, E), (OPT_SEED, seed), (OPT_MODE, mode),
                          (OPT_PARZEN, int(parzen)), (OPT_LR_MODE, lr_mode),
@@ -233,6 +248,18 @@ class ASGD:
 
     def set_step(self, t):
         asgd_set_step(self.h, t)
+
+    def get_exchange(self):
+        """(values [buffers, W, k, d] float32, rounds [buffers, W] int32): the messages in flight."""
+        values = np.empty((self.buffers, self.W, self.k, self.d), dtype=np.float32)
+        rounds = np.empty((self.buffers, self.W), dtype=np.int32)
+        asgd_get_exchange(self.h, values, rounds)
+        return values, rounds
+
+    def set_exchange(self, values, rounds):
+        values, rounds = np.asarray(values), np.asarray(rounds)
+        assert values.shape == (self.buffers, self.W, self.k, self.d) and rounds.shape == (self.buffers, self.W)
+        asgd_set_exchange(self.h, values, rounds)
 
     def run_epochs(self, epochs):
         asgd_run_epochs(self.h, epochs)

@@ -56,6 +56,10 @@ struct asgd_ctx {
     long long passed_t = -1;    // step up to which `consumed` holds what a one-launch run needs (-1: unknown)
     int fill_kernel = 0;        // kernel whose message format the exchange buffers were last emptied for
     bool desynced = false;      // a bounded wait expired in the last run: states and buffers are not those of any step
+    // messages handed over by asgd_set_exchange(), kept until the next run knows which kernel's format they take
+    std::vector<float> pending_values;
+    std::vector<int32_t> pending_rounds;
+    bool pending = false;
     int hip_err = 0;
 };
 
@@ -110,6 +114,137 @@ int clear_exchange(asgd_ctx *c, int kernel)
     HIP_TRY(c, hipMemsetAsync(c->slot, fill, c->slot_bytes, c->stream));
     HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->nb * c->W * sizeof(int), c->stream));   // -1
     c->fill_kernel = kernel;
+    return ASGD_OK;
+}
+
+// ---- messages in flight, in a format of their own -------------------------------------------------------------
+// Logical content of the exchange buffers: values[n][i] = the k x d rows waiting in buffer n of worker i (rows that a
+// partial message does not carry: zeros), rounds[n][i] = the round it was sent in, -1 = nothing waiting.  The
+// kernels hold this in two device formats: plain rows + a stamp per buffer (shape-agnostic and matrix-core kernels),
+// or (value, stamp) pairs in padded rows (small-state kernel).  Conversion runs on the host, in chunks of workers.
+
+// parity of the buffers that hold what the next merge point reads, and the round those messages carry (-1: none can)
+void inflight(const asgd_ctx *c, int *parity, long long *round)
+{
+    const bool det = c->mode == ASGD_MODE_DETERMINISTIC;
+    *parity = 0;
+    *round = -1;
+    if (c->E <= 0 || c->W < 2 || c->t <= 0) return;
+    if (!det) { *round = c->t / c->E - 1; return; }       // newest round that has sent; older stamps count too
+    if (c->t % c->E != 0) return;                           // inside a round nothing is in flight
+    *round = c->t / c->E - 1;
+    *parity = (int)(*round & 1);
+}
+
+bool row_in_part(const asgd_ctx *c, int row, long long round, int worker, int n)
+{
+    return c->parts == 1 || row % c->parts == (int)((round + worker + n) % c->parts);
+}
+
+enum { EXCHANGE_CHUNK_BYTES = 32 << 20 };
+
+int export_exchange(asgd_ctx *c, int kernel, float *values, int32_t *rounds)
+{
+    const size_t kd = kd_of(c), W = (size_t)c->W;
+    const bool det = c->mode == ASGD_MODE_DETERMINISTIC;
+    int par;
+    long long r_want;
+    inflight(c, &par, &r_want);
+    for (size_t q = 0; q < (size_t)c->nb * W; ++q) rounds[q] = -1;
+    memset(values, 0, (size_t)c->nb * W * kd * sizeof(float));
+    if (r_want < 0 || kernel == 0) return ASGD_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const bool small = kernel == ASGD_KERNEL_SMALL;
+    const size_t msg_bytes = small ? small_kernel_message_bytes(c->k, c->d) : kd * sizeof(float);
+    const size_t per_chunk = EXCHANGE_CHUNK_BYTES / msg_bytes > 0 ? EXCHANGE_CHUNK_BYTES / msg_bytes : 1;
+    std::vector<unsigned char> stage;
+    std::vector<int> stamps, row_round;
+    try {
+        stage.resize((per_chunk < W ? per_chunk : W) * msg_bytes);
+        stamps.resize(W);
+        row_round.resize((size_t)c->k);
+    } catch (...) {
+        return ASGD_ENOMEM;
+    }
+    for (int n = 0; n < c->nb; ++n) {
+        const size_t buf0 = ((size_t)par * c->nb + n) * W;             // index of (parity, buffer n, worker 0)
+        if (!small)
+            HIP_TRY(c, hipMemcpy(stamps.data(), c->stamp + buf0, W * sizeof(int), hipMemcpyDeviceToHost));
+        for (size_t i0 = 0; i0 < W; i0 += per_chunk) {
+            const size_t cnt = W - i0 < per_chunk ? W - i0 : per_chunk;
+            HIP_TRY(c, hipMemcpy(stage.data(), (const unsigned char *)c->slot + (buf0 + i0) * msg_bytes, cnt * msg_bytes,
+                                 hipMemcpyDeviceToHost));
+            for (size_t q = 0; q < cnt; ++q) {
+                const size_t i = i0 + q;
+                float *out = values + ((size_t)n * W + i) * kd;
+                long long st = -1;
+                if (small) {
+                    small_kernel_unpack_message(c->k, c->d, stage.data() + q * msg_bytes, out, row_round.data());
+                    for (int row = 0; row < c->k; ++row)
+                        if (row_round[row] > st) st = row_round[row];
+                } else {
+                    st = stamps[i];
+                    if (st >= 0) memcpy(out, stage.data() + q * msg_bytes, kd * sizeof(float));
+                }
+                const bool there = det ? st == r_want : st >= 0;
+                for (int row = 0; row < c->k; ++row) {
+                    const bool keep = there && row_in_part(c, row, st, (int)i, n) && (!small || row_round[row] == st);
+                    if (!keep) memset(out + (size_t)row * c->d, 0, (size_t)c->d * sizeof(float));
+                }
+                rounds[(size_t)n * W + i] = there ? (int32_t)st : -1;
+            }
+        }
+    }
+    return ASGD_OK;
+}
+
+// Writes the messages into the (freshly emptied) buffers in the format of `kernel`.
+int import_exchange(asgd_ctx *c, int kernel, const float *values, const int32_t *rounds)
+{
+    const size_t kd = kd_of(c), W = (size_t)c->W;
+    int par;
+    long long r_want;
+    inflight(c, &par, &r_want);
+    if (r_want < 0) return ASGD_OK;
+    const bool small = kernel == ASGD_KERNEL_SMALL;
+    const size_t msg_bytes = small ? small_kernel_message_bytes(c->k, c->d) : kd * sizeof(float);
+    const size_t per_chunk = EXCHANGE_CHUNK_BYTES / msg_bytes > 0 ? EXCHANGE_CHUNK_BYTES / msg_bytes : 1;
+    std::vector<unsigned char> stage;
+    std::vector<int> stamps, row_round;
+    try {
+        stage.resize((per_chunk < W ? per_chunk : W) * msg_bytes);
+        stamps.resize(W);
+        row_round.resize((size_t)c->k);
+    } catch (...) {
+        return ASGD_ENOMEM;
+    }
+    const int fill = (c->parts > 1 && !small) ? 0 : 0xFF;              // what clear_exchange() left in an empty buffer
+    for (int n = 0; n < c->nb; ++n) {
+        const size_t buf0 = ((size_t)par * c->nb + n) * W;
+        for (size_t i0 = 0; i0 < W; i0 += per_chunk) {
+            const size_t cnt = W - i0 < per_chunk ? W - i0 : per_chunk;
+            for (size_t q = 0; q < cnt; ++q) {
+                const size_t i = i0 + q;
+                const long long st = rounds[(size_t)n * W + i];
+                const float *in = values + ((size_t)n * W + i) * kd;
+                unsigned char *dst = stage.data() + q * msg_bytes;
+                stamps[i] = (int)st;
+                if (small) {
+                    for (int row = 0; row < c->k; ++row)
+                        row_round[row] = (st >= 0 && row_in_part(c, row, st, (int)i, n)) ? (int)st : -1;
+                    small_kernel_pack_message(c->k, c->d, in, row_round.data(), dst);
+                } else if (st >= 0) {
+                    memcpy(dst, in, kd * sizeof(float));
+                } else {
+                    memset(dst, fill, msg_bytes);
+                }
+            }
+            HIP_TRY(c, hipMemcpy((unsigned char *)c->slot + (buf0 + i0) * msg_bytes, stage.data(), cnt * msg_bytes,
+                                 hipMemcpyHostToDevice));
+        }
+        if (!small)
+            HIP_TRY(c, hipMemcpy(c->stamp + buf0, stamps.data(), W * sizeof(int), hipMemcpyHostToDevice));
+    }
     return ASGD_OK;
 }
 
@@ -301,6 +436,7 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->t = 0;
     ctx->passed_t = -1;
     ctx->desynced = false;
+    ctx->pending = false;
     ctx->loaded = false;
     ctx->xnorm2max_valid = false;
     StepParams p = make_params(ctx);
@@ -345,10 +481,51 @@ int asgd_set_step(asgd_ctx *ctx, int64_t t)
     ctx->t = t;
     ctx->passed_t = -1;
     ctx->desynced = false;
+    ctx->pending = false;
+    ctx->last_kernel = 0;       // the buffers are empty: no format to carry over
     int rc = clear_exchange(ctx, ASGD_KERNEL_SMALL);
     if (rc != ASGD_OK) return rc;
     ctx->fill_kernel = 0;
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return ASGD_OK;
+}
+
+int asgd_get_exchange(asgd_ctx *ctx, float *values_host, size_t values_bytes, int32_t *rounds_host, size_t rounds_bytes)
+{
+    if (!ctx || !values_host || !rounds_host) return ASGD_EINVAL;
+    if (!ctx->loaded || ctx->desynced) return ASGD_ESTATE;
+    const size_t nmsg = (size_t)ctx->nb * ctx->W;
+    if (values_bytes < nmsg * kd_of(ctx) * sizeof(float) || rounds_bytes < nmsg * sizeof(int32_t)) return ASGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (ctx->pending) {          // handed over and not yet used by a run: give the same messages back
+        memcpy(values_host, ctx->pending_values.data(), nmsg * kd_of(ctx) * sizeof(float));
+        memcpy(rounds_host, ctx->pending_rounds.data(), nmsg * sizeof(int32_t));
+        return ASGD_OK;
+    }
+    return export_exchange(ctx, ctx->last_kernel, values_host, rounds_host);
+}
+
+int asgd_set_exchange(asgd_ctx *ctx, const float *values_host, const int32_t *rounds_host)
+{
+    if (!ctx || !values_host || !rounds_host) return ASGD_EINVAL;
+    if (!ctx->loaded || ctx->desynced) return ASGD_ESTATE;
+    const size_t nmsg = (size_t)ctx->nb * ctx->W;
+    int par;
+    long long r_want;
+    inflight(ctx, &par, &r_want);
+    const bool det = ctx->mode == ASGD_MODE_DETERMINISTIC;
+    for (size_t q = 0; q < nmsg; ++q) {
+        const long long st = rounds_host[q];
+        if (st < -1 || st > r_want || (det && st >= 0 && st != r_want)) return ASGD_EINVAL;   // no such message can wait here
+    }
+    try {
+        ctx->pending_values.assign(values_host, values_host + nmsg * kd_of(ctx));
+        ctx->pending_rounds.assign(rounds_host, rounds_host + nmsg);
+    } catch (...) {
+        return ASGD_ENOMEM;
+    }
+    ctx->pending = true;
+    ctx->passed_t = -1;
     return ASGD_OK;
 }
 
@@ -392,14 +569,32 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         }
     }
 
-    // The kernels keep a message in flight in different formats; one is in flight exactly at a merge point.
-    if (ctx->last_kernel != 0 && kernel != ctx->last_kernel && ctx->E > 0 && ctx->W > 1 && ctx->t > 0 &&
-        ctx->t % ctx->E == 0)
-        return ASGD_ESTATE;
-
-    // Partial messages: the fill of the never-written rows of the exchange buffers depends on the kernel's message
-    // format.  (No message is in flight here: the check above, and the first run after load / set_step.)
-    if (ctx->parts > 1 && ctx->fill_kernel != kernel) {
+    // The kernels keep a message in flight in different formats.  Messages handed over by asgd_set_exchange(), and
+    // those a run of another kernel left behind, are written into the buffers in the format of this run's kernel.
+    const bool switched = ctx->last_kernel != 0 && kernel != ctx->last_kernel && ctx->E > 0 && ctx->W > 1 && ctx->t > 0;
+    if (ctx->pending || switched) {
+        if (!ctx->pending) {
+            try {
+                ctx->pending_values.resize((size_t)ctx->nb * ctx->W * kd_of(ctx));
+                ctx->pending_rounds.resize((size_t)ctx->nb * ctx->W);
+            } catch (...) {
+                return ASGD_ENOMEM;
+            }
+            const int rc = export_exchange(ctx, ctx->last_kernel, ctx->pending_values.data(), ctx->pending_rounds.data());
+            if (rc != ASGD_OK) return rc;
+        }
+        int rc = clear_exchange(ctx, kernel);
+        if (rc != ASGD_OK) return rc;
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        rc = import_exchange(ctx, kernel, ctx->pending_values.data(), ctx->pending_rounds.data());
+        if (rc != ASGD_OK) return rc;
+        ctx->pending = false;
+        std::vector<float>().swap(ctx->pending_values);
+        std::vector<int32_t>().swap(ctx->pending_rounds);
+        ctx->passed_t = -1;
+    } else if (ctx->parts > 1 && ctx->fill_kernel != kernel) {
+        // Partial messages: the fill of the never-written rows of the exchange buffers depends on the kernel's
+        // message format.  (No message is in flight here: first run after load / set_step.)
         const int rc = clear_exchange(ctx, kernel);
         if (rc != ASGD_OK) return rc;
     }

@@ -91,6 +91,9 @@ hipError_t launch_generic_steps(const StepParams &p, long long t0, long long t1,
 bool small_kernel_supports(int k, int d, int b);
 // bytes of one exchange buffer in the small-state kernel's own message format (0: kernel not applicable)
 size_t small_kernel_message_bytes(int k, int d);
+// host side of that format: rows = k x d floats, row_round[c] = round stamped on row c (-1: row empty or torn)
+void small_kernel_unpack_message(int k, int d, const void *msg, float *rows, int *row_round);
+void small_kernel_pack_message(int k, int d, const float *rows, const int *row_round, void *msg);
 // persistent = true: the whole range in one cooperative launch with in-kernel waits between rounds
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent);
 // Matrix-core kernel: needs d % 4 == 0, d <= 128, 16-byte aligned samples and its LDS budget.

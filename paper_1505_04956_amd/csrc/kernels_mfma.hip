@@ -681,7 +681,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 int *stp = p.stamp + (size_t)(rpar * p.nb + n) * p.W + i;
                 if (det) {
                     // stamps of one buffer only grow, so the test for the round needs no clearing
-                    if (sync) {
+                    if (sync && t > t0) {      // (at the first step of a launch the message, if any, was sent before it)
                         const long long rs = r_now - 1;
                         const int sender = (i - shift_deterministic(p.seed, rs, p.W, n) + p.W) % p.W;
                         if ((p.drop_unannounced || !message_dropped(p.seed, rs, sender, p.drop_thr, n)) && !s_wait_failed &&

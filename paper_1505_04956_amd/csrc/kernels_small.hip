@@ -26,6 +26,8 @@
 // bookkeeping is 32-bit and scalar, the state lives in registers in the layout the row sums come out
 // in, and the wave-uniform copies are made with one LDS write and broadcast reads.
 // Every sum is formed in one fixed order, so a run is reproducible bit for bit.
+#include <string.h>
+
 #include "asgd_internal.h"
 
 namespace asgd {
@@ -812,7 +814,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
                 const bool merge_point = wk.xchg && te == 0 && round > 0;      // t > 0 and t mod E == 0
                 const bool send_point = wk.xchg && te + 1 == E;
-                kp.fetch(p, i, round, merge_point, send_point, det, sync, wave == 0);
+                // what the first step of a launch finds in the buffers was sent before the launch: nothing to wait for
+                const int sync_now = (wk.done + ls) > 0 ? sync : 0;
+                kp.fetch(p, i, round, merge_point, send_point, det, sync_now, wave == 0);
 
                 const bool last_step = ls + 1 == wk.seg;
                 const int s_next = (s_epoch + 1 == wk.S) ? 0 : s_epoch + 1;
@@ -914,7 +918,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     }
                 }
                 parity ^= 1;
-                kp.template finish<(NW > 1)>(p, i, round, S4, merge_point, send_point, det, sync, wave == 0);
+                kp.template finish<(NW > 1)>(p, i, round, S4, merge_point, send_point, det, sync_now, wave == 0);
 
                 // advance the clock
                 xb = xbn;
@@ -1092,6 +1096,39 @@ size_t small_kernel_message_bytes(int k, int d)
 {
     if (!(k == 10 && d == 10)) return 0;
     return (size_t)k * ((d + 1 + 3) / 4) * 4 * sizeof(unsigned long long);      // NT lanes x 4 (value, stamp) pairs
+}
+
+// A message is k padded rows of RW = 4 * NQ pairs: pair c * RW + j holds element j of row c (j < d), zero beyond.
+void small_kernel_unpack_message(int k, int d, const void *msg, float *rows, int *row_round)
+{
+    const unsigned long long *pairs = static_cast<const unsigned long long *>(msg);
+    const int rw = 4 * ((d + 1 + 3) / 4);
+    for (int c = 0; c < k; ++c) {
+        const int st = (int)(pairs[(size_t)c * rw] >> 32);
+        bool same = true;
+        for (int j = 0; j < rw; ++j) {
+            const unsigned long long pr = pairs[(size_t)c * rw + j];
+            same = same && (int)(pr >> 32) == st;
+            if (j < d) {
+                const unsigned bits = (unsigned)(pr & 0xffffffffull);
+                memcpy(&rows[(size_t)c * d + j], &bits, sizeof(float));
+            }
+        }
+        row_round[c] = (same && st >= 0) ? st : -1;
+    }
+}
+
+void small_kernel_pack_message(int k, int d, const float *rows, const int *row_round, void *msg)
+{
+    unsigned long long *pairs = static_cast<unsigned long long *>(msg);
+    const int rw = 4 * ((d + 1 + 3) / 4);
+    for (int c = 0; c < k; ++c)
+        for (int j = 0; j < rw; ++j) {
+            unsigned bits = 0;
+            if (j < d) memcpy(&bits, &rows[(size_t)c * d + j], sizeof(float));
+            pairs[(size_t)c * rw + j] = row_round[c] < 0 ? ~0ull
+                                                         : (((unsigned long long)(unsigned)row_round[c] << 32) | bits);
+        }
 }
 
 bool small_kernel_supports(int k, int d, int b)
