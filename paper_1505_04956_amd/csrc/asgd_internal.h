@@ -110,7 +110,8 @@ hipError_t launch_mean_state(const float *w, int W, int kd, float *out, hipStrea
 int quant_partials_count();
 // specialisations of Eq. 8 (each fills `nblocks` <= quant_partials_count() partial sums; the generic launcher
 // below picks one and adds the partials in a fixed order)
-hipError_t launch_quant_error_small(const float *x, long long N, const float *w, double *partials, int nblocks, hipStream_t s);
+hipError_t launch_quant_error_small(const float *x, long long N, int d, int k, const float *w, double *partials, int nblocks,
+                                    hipStream_t s);   // shapes of small_kernel_supports()
 bool mfma_quant_error_supports(int k, int d, const void *x);
 hipError_t launch_quant_error_mfma(const float *x, long long N, int d, int k, const float *w, double *partials,
                                    int nblocks, hipStream_t s);

@@ -141,6 +141,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
     __syncthreads();
 
     long long my_recheck = 0;
+    const float redecide = fmaxf(1e-5f, 4.0f * (float)(d + 2) * 5.9604645e-8f);
     for (long long t = t0; t < t1; ++t) {
         const long long s = t % p.S;
         const float *xb = p.x + ((size_t)i * p.H + (size_t)s * b) * d;   // this step's mini-batch
@@ -163,9 +164,10 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 if (acc < best) { second = best; best = acc; arg = c; }
                 else if (acc < second) { second = acc; }
             }
-            // fp32 direct-form distances carry a relative error of about d * 2^-24; when the two
-            // best are closer than a generous multiple of that, decide in fp64.
-            if (!(second - best > 1e-5f * second)) {
+            // A direct-form distance in fp32 (one rounding per difference, one per fused multiply-add, all terms
+            // non-negative) is off by at most (d + 2) * 2^-24 of its value, the difference of two of them by at most
+            // 2 (d + 2) 2^-24 of the larger one.  Closer than twice that (and never less than 1e-5): decide in fp64.
+            if (!(second - best > redecide * second)) {
                 arg = exact_nearest(xr, wp, k, d);
                 my_recheck += 1;
             }
@@ -456,7 +458,7 @@ hipError_t launch_quant_error(const float *x, long long N, int d, int k, const f
     int nparts = QE_BLOCKS;
     hipError_t e = hipSuccess;
     if (small_kernel_supports(k, d, 1)) {
-        e = launch_quant_error_small(x, N, w, partials, nparts, s);            // streaming shape: HBM bound
+        e = launch_quant_error_small(x, N, d, k, w, partials, nparts, s);           // streaming shape: HBM bound
     } else if (mfma_quant_error_supports(k, d, x)) {
         nparts = 256;                                                           // one workgroup per CU
         e = launch_quant_error_mfma(x, N, d, k, w, partials, nparts, s);       // contraction shape: matrix cores

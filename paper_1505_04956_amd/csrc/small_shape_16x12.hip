@@ -1,0 +1,8 @@
+// The small-state step kernel and its Eq. 8 kernel for k = 16, d = 12.
+#include "small_steps.h"
+
+namespace asgd {
+
+ASGD_SMALL_SHAPE_DEFINE(16, 12, false)
+
+}  // namespace asgd

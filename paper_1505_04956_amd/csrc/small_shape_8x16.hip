@@ -1,0 +1,8 @@
+// The small-state step kernel and its Eq. 8 kernel for k = 8, d = 16.
+#include "small_steps.h"
+
+namespace asgd {
+
+ASGD_SMALL_SHAPE_DEFINE(8, 16, false)
+
+}  // namespace asgd

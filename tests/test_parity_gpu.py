@@ -99,6 +99,7 @@ def test_small_kernel_variants(B, oracle, tune):
     (16, 16, 4, 256, 4, 4 * 2048),
     (10, 10, 1, 500, 4, 5000),            # W = 1: nothing to exchange (Alg. 4)
     (70, 3, 2, 100, 2, 2 * 700),          # k > 64
+    (6, 700, 2, 120, 2, 2 * 500),         # long rows: the re-decision threshold follows d (4 (d + 2) 2^-24 > 1e-5)
 ])
 def test_generic_shapes(B, oracle, k, d, W, b, E, N):
     X = make_data(N, d, k, seed=11)
@@ -111,6 +112,26 @@ def test_small_kernel_ragged(B, oracle):
     for b in (37, 64, 65, 200, 500, 1000):
         X = make_data(4 * 3000 + 3, 10, 10, seed=b)
         run_both(B, oracle, X, 10, 4, b, 0.05, 3, 11, kernel=2)
+
+
+@pytest.mark.parametrize("k,d", [(4, 4), (8, 8), (8, 16), (16, 8), (16, 12)])
+@pytest.mark.parametrize("W,b,E,buffers,parts,tune", [
+    (6, 200, 2, 1, 1, 0),        # two waves per worker
+    (5, 130, 3, 2, 1, 8),        # one wave per worker, two buffers, ragged mini-batch
+    (4, 1000, 2, 3, 2, 0),       # the streaming workload's mini-batch, three buffers, partial messages
+])
+def test_small_kernel_other_shapes(B, oracle, k, d, W, b, E, buffers, parts, tune):
+    """The other small shapes the streaming kernel is built for (the automatic choice takes it for them too)."""
+    X = make_data(W * b * 4 + 5, d, k, seed=31 + k + d)
+    g, o = run_both(B, oracle, X, k, W, b, 0.05, E, 13, kernel=0, tune=tune, buffers=buffers, parts=parts)
+    assert g.stats().kernel == B.KERNEL_SMALL and g.stats().launches == 1
+
+
+def test_small_kernel_other_shapes_many_workers(B, oracle):
+    # more workers than workgroups can be resident (one wave per SIMD for the larger of these shapes), message loss
+    X = make_data(1500 * 260 + 7, 12, 16, seed=9)
+    g, o = run_both(B, oracle, X, 16, 1500, 64, 0.05, 2, 7, kernel=2, drop_rate=0.25)
+    assert g.stats().launches == 1
 
 
 def test_more_workers_than_resident_workgroups(B, oracle):
@@ -582,7 +603,8 @@ def test_mean_state(B, oracle):
     assert abs(qg - qo) <= TOL * qo
 
 
-@pytest.mark.parametrize("k,d,kernel_name", [(10, 10, "streaming"), (64, 32, "matrix-core"), (7, 5, "generic")])
+@pytest.mark.parametrize("k,d,kernel_name", [(10, 10, "streaming"), (64, 32, "matrix-core"), (7, 5, "generic"),
+                                             (4, 4, "streaming"), (8, 16, "streaming"), (16, 12, "streaming")])
 def test_quant_error_of_tight_clusters_far_from_the_origin(B, oracle, k, d, kernel_name):
     """Eq. 8 where |x|^2 is ten orders of magnitude above the distances: centres in [0, 1000]^d, sigma = 0.01.  An
     expanded-form evaluation |x|^2/2 - max score loses everything to cancellation in fp32; the kernels form the winner's
