@@ -248,26 +248,34 @@ __device__ __forceinline__ int decide(const float (&tk)[K], const float (&xc)[D]
     return arg;
 }
 
-// Sums `rows` accumulator rows of one float4 column (col[r], r < rows) in a fixed order and clears them.  The start
-// row depends on the task, so that the lanes of one access hit different banks.
+// Sums `rows` accumulator rows of one float4 column (col[r], r < rows) in a fixed order and clears them.  Row r of
+// the visit is row r ^ (task mod ROWS) of the column, so that the lanes of one access hit different banks; with the
+// column at a multiple of ROWS * 16 bytes in LDS the address of a row is ONE exclusive-or away from the address of the
+// first (no add, mask and shift per row).
+typedef float lds_vec4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) lds_vec4 *lds_vec4_ptr;
 template <int ROWS>
 __device__ __forceinline__ float4 sum_and_clear(float4 *col, int task)
 {
-    static_assert(ROWS % 2 == 0 && (ROWS & (ROWS - 1)) == 0, "rows are summed in two interleaved chains; the rotation wraps with a mask");
-    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
-    // (the row numbers are formed here, at every call, from a value the compiler cannot see through: hoisted out of
+    static_assert(ROWS % 2 == 0 && (ROWS & (ROWS - 1)) == 0, "rows are summed in two interleaved chains; the rotation is an exclusive-or");
+    unsigned first = (unsigned)(size_t)(lds_vec4_ptr)(lds_vec4 *)col + ((unsigned)(task & (ROWS - 1)) << 4);
+    // (the row addresses are formed here, at every call, from a value the compiler cannot see through: hoisted out of
     // the step loop they would be ROWS more registers per lane, held across the streaming part)
-    asm volatile("" : "+v"(task));
+    asm volatile("" : "+v"(first));
+    const lds_vec4 zero = {0.f, 0.f, 0.f, 0.f};
+    lds_vec4 s0 = zero, s1 = zero;
 #pragma unroll
     for (int r = 0; r < ROWS; r += 2) {
-        const int r0 = (r + task) & (ROWS - 1), r1 = (r + 1 + task) & (ROWS - 1);
-        const float4 v0 = col[r0], v1 = col[r1];
-        col[r0] = make_float4(0.f, 0.f, 0.f, 0.f);
-        col[r1] = make_float4(0.f, 0.f, 0.f, 0.f);
-        s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
-        s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
+        lds_vec4_ptr p0 = (lds_vec4_ptr)(size_t)(first ^ (unsigned)(r << 4));
+        lds_vec4_ptr p1 = (lds_vec4_ptr)(size_t)(first ^ (unsigned)((r + 1) << 4));
+        const lds_vec4 v0 = *p0, v1 = *p1;
+        *p0 = zero;
+        *p1 = zero;
+        s0 = r == 0 ? v0 : s0 + v0;
+        s1 = r == 0 ? v1 : s1 + v1;
     }
-    return make_float4(s0.x + s1.x, s0.y + s1.y, s0.z + s1.z, s0.w + s1.w);
+    const lds_vec4 t = s0 + s1;
+    return make_float4(t.x, t.y, t.z, t.w);
 }
 
 // The walk of a workgroup through its work, the same in every wave: segments of steps (in deterministic mode a
@@ -719,7 +727,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
     // acc[wave][row][q][r]: float4 number q of the row that lane r (RS = 2: lanes r and r+32) keeps for
     // centroid `row`; row K is scratch for masked lanes.  Consecutive lanes are 16 bytes apart.
-    __shared__ float4 acc[NW][K + 1][NQ][RL];
+    __shared__ __align__(1024) float4 acc[NW][K + 1][NQ][RL];    // (alignment: see sum_and_clear)
     __shared__ float4 wst[NW][NT];                  // state, rows padded to RW floats; one copy per wave
     __shared__ float4 wdt[NW][NT];                  // row k: w_k - w_0 in elements < D, (h_k - h_0) + 1 in element D
     __shared__ float4 part[2][NW][NPART][NT];       // per-wave totals, double-buffered by step parity
@@ -843,6 +851,13 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 float4 pr = prow[qoff[0]];
 
                 for (int m0 = 0; m0 < ngw; m0 += PF) {
+                    // Refills of this turn: slot 0 takes group m0 + PF - 1 of this mini-batch, slot u >= 1 group
+                    // m0 + PF + u - 1, which lies in the next mini-batch for all of them at once in the last turn
+                    // (ngw is a multiple of PF).  One scalar decision per turn, constants per slot.
+                    const bool tail = m0 + PF >= ngw;
+                    const float *pbase = tail ? xbn : xb;
+                    const unsigned turn_off = lane_off + (unsigned)(wave + NW * (tail ? 0 : m0 + PF)) * GROUP_BYTES;
+                    const unsigned own_off = lane_off + (unsigned)(wave + NW * (m0 + PF - 1)) * GROUP_BYTES;
 #pragma unroll
                     for (int u = 0; u < PF; ++u) {
                         const int up = (u + PF - 1) % PF;           // buffer of the previous group
@@ -891,9 +906,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                         }
                         // buffer `up` is free now: refill it with the group PF-1 turns ahead
                         {
-                            const int mm = m + PF - 1;
-                            const bool same = mm < ngw;
-                            load_row<D>(xr[up], sample_ptr(same ? xb : xbn, wave + NW * (same ? mm : mm - ngw)));
+                            const unsigned off = u == 0 ? own_off : turn_off + (unsigned)(NW * (u - 1)) * GROUP_BYTES;
+                            load_row<D>(xr[up], reinterpret_cast<const float *>(
+                                                    reinterpret_cast<const char *>(u == 0 ? xb : pbase) + min(off, max_off)));
                         }
 
                         const int n = (wave + m * NW) * 64 + lane;
