@@ -193,16 +193,14 @@ __device__ __forceinline__ float row_part(const float (&x)[D], int q, int c4)
     return j < D ? x[j] : (j == D ? 1.0f : 0.0f);
 }
 
-// Nearest centroid of a lane's sample from its tagged scores tk (largest = nearest; tag = 15 - index in the low 4
-// mantissa bits): exact where the fp32 scores are closer than thr.  wsf: the copy of the state in LDS, rows padded
-// to RW floats.
+// Nearest centroid of a lane's sample from its tagged scores tk and the two largest of them (largest = nearest;
+// tag = 15 - index in the low 4 mantissa bits): exact where the fp32 scores are closer than thr.  wsf: the copy of the
+// state in LDS, rows padded to RW floats.
 template <int K, int D>
-__device__ __forceinline__ int decide(const float (&tk)[K], const float (&xc)[D], bool valid, float thr, const float *wsf,
-                                      int &rechecks)
+__device__ __forceinline__ int decide(const float (&tk)[K], float best, float second, const float (&xc)[D], bool valid,
+                                      float thr, const float *wsf, int &rechecks)
 {
     constexpr int RW = SmallGeo<K, D>::RW;
-    float best, second;
-    top2<K>(tk, best, second);
     int arg = 15 - (int)(__float_as_uint(best) & 15u);
     if (valid && !(best - second > thr)) {
         // Too close to call in fp32.  Candidates are the centroids within thr of the best; with two of them their
@@ -701,6 +699,32 @@ struct SmallKeeper {
 //             of the previous round), and a sender waits until the recipient has consumed the older
 //             message that sits in the same buffer.  Every wait is on an earlier round, so the
 //             waits cannot form a cycle.
+// Score chains of the centroids C0 .. C0 + NC - 1 against the wave-uniform copy wv (row c - 1: w_c - w_0, element D:
+// (h_c - h_0) + 1), advancing together element by element; the result goes to tk[c] with 15 - c in the low 4 mantissa
+// bits.
+template <int K, int D, int C0, int NC>
+__device__ __forceinline__ void score_chains(const float (&xc)[D], const float (&wv)[K - 1][SmallGeo<K, D>::RW], float (&tk)[K])
+{
+    if constexpr (NC > 0) {
+        float sc[NC];
+#pragma unroll
+        for (int e = 0; e < NC; ++e) sc[e] = fmaf(xc[0], wv[C0 + e - 1][0], wv[C0 + e - 1][D]);
+#pragma unroll
+        for (int j = 1; j < D; ++j) {
+#pragma unroll
+            for (int e = 0; e < NC; ++e) sc[e] = fmaf(xc[j], wv[C0 + e - 1][j], sc[e]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // (the chains end here, not further down where their results are used: without this the compiler sinks the
+        // tails of the chains of one set into the next and serialises them)
+#pragma unroll
+        for (int e = 0; e < NC; ++e) asm volatile("" : "+v"(sc[e]));
+#pragma unroll
+        for (int e = 0; e < NC; ++e)
+            tk[C0 + e] = __uint_as_float((__float_as_uint(sc[e]) & 0xFFFFFFF0u) | (unsigned)(15 - (C0 + e)));
+    }
+}
+
 // Waves per SIMD the kernel is compiled for: RS (shared rows halve the LDS per wave so that two fit), unless the
 // registers of the shape (the wave-uniform copy of w_k - w_0, the ring, about a hundred more) go past the 256 that two
 // waves per SIMD leave each.
@@ -719,7 +743,6 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     constexpr int NQ = G::NQ, RW = G::RW, NT = G::NT, NPART = G::NPART;
     constexpr int RL = 64 / RS;                     // accumulator rows per centroid and wave
     constexpr int RPP = RL / NPART;                 // rows one lane sums in the reduction
-    constexpr int CPC = (K - 1 + NQ - 1) / NQ;      // score chains between two row phases
     static_assert(NW == 1 || NW == 2, "one or two waves per worker");
     static_assert(RS == 1 || (RS == 2 && NQ >= 2), "two lanes share a row only if it has two float4 or more");
     static_assert(PF >= 2, "the ring needs the previous group's buffer");
@@ -870,37 +893,26 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                         // previous group: add, write, (fence,) read for the next phase
                         float tk[K];
                         tk[0] = tk0;
+                        // The chains advance together, in two sets (a wave issues an instruction that depends on the
+                        // one before it at two thirds of the rate of independent ones, and four or more independent
+                        // chains issue at the full rate; the scheduling barriers in score_chains keep the compiler from
+                        // putting the chains one after the other).  Row phases 0 and 1 of the previous group follow a
+                        // set each and the remaining ones the search for the two largest scores, so that the LDS read
+                        // issued at the end of a phase returns under other work instead of being waited for at once.
+                        constexpr int CA = K / 2, CB = K - 1 - CA;
+                        score_chains<K, D, 1, CA>(xc, wv, tk);
+                        __builtin_amdgcn_sched_barrier(0);
+                        row_phase(xp, 0, prow, pr);
+                        __builtin_amdgcn_sched_barrier(0);
+                        score_chains<K, D, 1 + CA, CB>(xc, wv, tk);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (NQ > 1) row_phase(xp, 1, prow, pr);
+                        __builtin_amdgcn_sched_barrier(0);
+                        float best, second;
+                        top2<K>(tk, best, second);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int ph = 0; ph < NQ; ++ph) {
-                            // (the chains of a phase advance together: a wave issues an instruction that depends on the
-                            // one before it at two thirds of the rate of independent ones; the scheduling barriers keep
-                            // the compiler from putting the chains one after the other)
-                            {
-                                constexpr int C0 = 1;
-                                float sc[CPC];
-#pragma unroll
-                                for (int e = 0; e < CPC; ++e) {
-                                    const int c = C0 + ph * CPC + e;
-                                    sc[e] = c < K ? fmaf(xc[0], wv[c - 1][0], wv[c - 1][D]) : 0.0f;
-                                }
-#pragma unroll
-                                for (int j = 1; j < D; ++j) {
-#pragma unroll
-                                    for (int e = 0; e < CPC; ++e) {
-                                        const int c = C0 + ph * CPC + e;
-                                        if (c < K) sc[e] = fmaf(xc[j], wv[c - 1][j], sc[e]);
-                                    }
-                                    __builtin_amdgcn_sched_barrier(0);
-                                }
-#pragma unroll
-                                for (int e = 0; e < CPC; ++e) {
-                                    const int c = C0 + ph * CPC + e;
-                                    if (c < K) tk[c] = __uint_as_float((__float_as_uint(sc[e]) & 0xFFFFFFF0u) | (unsigned)(15 - c));
-                                }
-                            }
-                            // keep the order chains / row phase / chains ...: the LDS read issued at the end of a phase
-                            // then returns under the next chains instead of being waited for at once
-                            __builtin_amdgcn_sched_barrier(0);
+                        for (int ph = 2; ph < NQ; ++ph) {
                             row_phase(xp, ph, prow, pr);
                             __builtin_amdgcn_sched_barrier(0);
                         }
@@ -913,7 +925,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
                         const int n = (wave + m * NW) * 64 + lane;
                         const bool valid = n < b;
-                        const int arg = decide<K, D>(tk, xc, valid, thr, wsf, rechecks);
+                        const int arg = decide<K, D>(tk, best, second, xc, valid, thr, wsf, rechecks);
                         if (dump && valid) dump[n] = arg;
 
                         // start this group's row update: read for phase 0
