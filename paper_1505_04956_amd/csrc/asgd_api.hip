@@ -112,7 +112,7 @@ int clear_exchange(asgd_ctx *c, int kernel)
 {
     const int fill = (c->parts > 1 && kernel != ASGD_KERNEL_SMALL) ? 0 : 0xFF;
     HIP_TRY(c, hipMemsetAsync(c->slot, fill, c->slot_bytes, c->stream));
-    HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, 2 * (size_t)c->nb * c->W * sizeof(int), c->stream));   // -1
+    HIP_TRY(c, hipMemsetAsync(c->stamp, 0xFF, exchange_buffers_total(c->nb, c->W) * sizeof(int), c->stream));   // -1
     c->fill_kernel = kernel;
     return ASGD_OK;
 }
@@ -138,7 +138,7 @@ void inflight(const asgd_ctx *c, int *parity, long long *round)
 
 bool row_in_part(const asgd_ctx *c, int row, long long round, int worker, int n)
 {
-    return c->parts == 1 || row % c->parts == (int)((round + worker + n) % c->parts);
+    return row_travels(row, round, worker, n, c->parts);
 }
 
 enum { EXCHANGE_CHUNK_BYTES = 32 << 20 };
@@ -167,7 +167,7 @@ int export_exchange(asgd_ctx *c, int kernel, float *values, int32_t *rounds)
         return ASGD_ENOMEM;
     }
     for (int n = 0; n < c->nb; ++n) {
-        const size_t buf0 = ((size_t)par * c->nb + n) * W;             // index of (parity, buffer n, worker 0)
+        const size_t buf0 = exchange_buffer(par, c->nb, n, c->W, 0);
         if (!small)
             HIP_TRY(c, hipMemcpy(stamps.data(), c->stamp + buf0, W * sizeof(int), hipMemcpyDeviceToHost));
         for (size_t i0 = 0; i0 < W; i0 += per_chunk) {
@@ -220,7 +220,7 @@ int import_exchange(asgd_ctx *c, int kernel, const float *values, const int32_t 
     }
     const int fill = (c->parts > 1 && !small) ? 0 : 0xFF;              // what clear_exchange() left in an empty buffer
     for (int n = 0; n < c->nb; ++n) {
-        const size_t buf0 = ((size_t)par * c->nb + n) * W;
+        const size_t buf0 = exchange_buffer(par, c->nb, n, c->W, 0);
         for (size_t i0 = 0; i0 < W; i0 += per_chunk) {
             const size_t cnt = W - i0 < per_chunk ? W - i0 : per_chunk;
             for (size_t q = 0; q < cnt; ++q) {
@@ -294,7 +294,7 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
     const size_t kd = kd_of(c), Wz = (size_t)W;
     {
         const size_t plain = kd * sizeof(float), own = small_kernel_message_bytes(k, d);
-        c->slot_bytes_one = 2 * Wz * (plain > own ? plain : own);
+        c->slot_bytes_one = exchange_buffers_total(1, W) * (plain > own ? plain : own);
         c->slot_bytes = c->slot_bytes_one;
     }
     struct { void **p; size_t bytes; } allocs[] = {
@@ -303,7 +303,7 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
         {(void **)&c->acc, Wz * kd * sizeof(float)},
         {(void **)&c->xabsmax, (size_t)d * sizeof(float)},
         {(void **)&c->mean, kd * sizeof(float)},
-        {(void **)&c->stamp, 2 * Wz * sizeof(int)},
+        {(void **)&c->stamp, exchange_buffers_total(1, W) * sizeof(int)},
         {(void **)&c->consumed, Wz * sizeof(int)},
         {(void **)&c->cnt, Wz * k * sizeof(int)},
         {(void **)&c->assign_tmp, Wz * (size_t)b * sizeof(int)},
@@ -388,7 +388,7 @@ int asgd_set_option(asgd_ctx *ctx, int key, double value)
             float *slot = nullptr;
             int *stamp = nullptr;
             hipError_t e = hipMalloc((void **)&slot, (size_t)nb * ctx->slot_bytes_one);
-            if (e == hipSuccess) e = hipMalloc((void **)&stamp, 2 * (size_t)nb * ctx->W * sizeof(int));
+            if (e == hipSuccess) e = hipMalloc((void **)&stamp, exchange_buffers_total(nb, ctx->W) * sizeof(int));
             if (e != hipSuccess) {
                 if (slot) (void)hipFree(slot);
                 HIP_TRY(ctx, e);

@@ -5,48 +5,10 @@
 #include <stdint.h>
 
 #include "asgd.h"
+#include "exchange_index.h"
 
 namespace asgd {
 
-// ---- counter-based integer generator (published splitmix64 finaliser) --------------------
-// Used for the peer schedule and the message-loss test hook.  Integer only, so host and
-// device agree bit for bit.
-__host__ __device__ inline uint64_t mix64(uint64_t z)
-{
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
-    return z ^ (z >> 31);
-}
-__host__ __device__ inline uint64_t round_hash(uint64_t seed, int64_t r)
-{
-    return mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(r + 1));
-}
-// Deterministic schedule: one cyclic shift per round and copy, shared by all senders, so that every
-// worker receives exactly one message per round in each of its buffers (Alg. 5 line 9 asks only for
-// "a random node other than i").  Copy n of a message (0 <= n < number of buffers < W) goes into the
-// recipient's buffer n; the shifts of one round differ, so a worker's senders differ.
-__host__ __device__ inline int shift_deterministic(uint64_t seed, int64_t r, int W, int n = 0)
-{
-    return (int)(1 + (round_hash(seed, r) % (uint64_t)(W - 1) + (uint64_t)n) % (uint64_t)(W - 1));
-}
-__host__ __device__ inline int peer_deterministic(uint64_t seed, int64_t r, int i, int W, int n = 0)
-{
-    return (int)(((uint64_t)i + (uint64_t)shift_deterministic(seed, r, W, n)) % (uint64_t)W);
-}
-// Free-running schedule: every sender draws its own recipients; collisions are the data race
-// of Fig. 2 (III) and are allowed.
-__host__ __device__ inline int peer_free(uint64_t seed, int64_t r, int i, int W, int n = 0)
-{
-    uint64_t h = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(i + 1) + 0x5851F42D4C957F2DULL +
-                       0xD1B54A32D192ED03ULL * (uint64_t)n);
-    return (int)(((uint64_t)i + 1 + h % (uint64_t)(W - 1)) % (uint64_t)W);
-}
-__host__ __device__ inline bool message_dropped(uint64_t seed, int64_t r, int sender, uint32_t thr, int n = 0)
-{
-    uint64_t u = mix64(round_hash(seed, r) + 0x9E3779B97F4A7C15ULL * (uint64_t)(sender + 1) +
-                       0xD1B54A32D192ED03ULL * (uint64_t)n) >> 40;
-    return u < (uint64_t)thr;
-}
 enum { MAX_BUFFERS = 4 };   // external buffers per worker (Eq. 3)
 
 // Per-worker counters kept in device memory.

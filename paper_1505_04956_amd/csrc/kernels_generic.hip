@@ -211,7 +211,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         if (tid == 0) {
             int has = 0;                       // bit n: buffer n holds a message for this merge point
             for (int n = 0; merge_point && n < p.nb; ++n) {
-                int *stp = p.stamp + ((size_t)(rpar * p.nb + n) * p.W + i);
+                int *stp = p.stamp + exchange_buffer(rpar, p.nb, n, p.W, i);
                 const int st = *stp;
                 if (det ? (st == (int)(r_now - 1)) : (st >= 0)) has |= 1 << n;
                 s_ext_round[n] = st;
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         __syncthreads();
         const int has_mask = s_has_ext;        // uniform over the block
         const float *ext[MAX_BUFFERS];
-        for (int n = 0; n < MAX_BUFFERS; ++n) ext[n] = p.slot + ((size_t)(rpar * p.nb + (n < p.nb ? n : 0)) * p.W + i) * kd;
+        for (int n = 0; n < MAX_BUFFERS; ++n) ext[n] = p.slot + exchange_buffer(rpar, p.nb, n < p.nb ? n : 0, p.W, i) * kd;
         // descent gradient of Eq. 9, G = (c_k * w_k - S_k) / b, stored over the sums
         for (size_t e = tid; e < kd; e += GEN_THREADS) {
             const int c = (int)(e / d);
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
             for (int c = wave; c < k; c += GEN_THREADS / 64) {
                 int rowmask = 0;
                 for (int n = 0; n < p.nb; ++n) {
-                    if (!(has_mask >> n & 1) || c % p.parts != (s_ext_round[n] + i + n) % p.parts) continue;
+                    if (!(has_mask >> n & 1) || !row_travels(c, s_ext_round[n], i, n, p.parts)) continue;
                     double lhs = 0.0, rhs = 0.0, nrm = 0.0;
                     for (int j = lane; j < d; j += 64) {
                         const size_t e = (size_t)c * d + j;
@@ -324,13 +324,13 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 if (message_dropped(p.seed, r, i, p.drop_thr, n)) continue;
                 const int peer = det ? peer_deterministic(p.seed, r, i, p.W, n) : peer_free(p.seed, r, i, p.W, n);
                 const int spar = det ? (int)(r & 1) : 0;
-                float *dst = p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd;
-                const int part = (int)((r + peer + n) % p.parts);           // only the rows of this part travel
+                float *dst = p.slot + exchange_buffer(spar, p.nb, n, p.W, peer) * kd;
+                const int part = message_part(r, peer, n, p.parts);         // only the rows of this part travel
                 for (size_t e = tid; e < kd; e += GEN_THREADS)
                     if (p.parts == 1 || (int)(e / d) % p.parts == part) dst[e] = wp[e];
                 __threadfence();
                 __syncthreads();
-                if (tid == 0) p.stamp[(size_t)(spar * p.nb + n) * p.W + peer] = (int)r;
+                if (tid == 0) p.stamp[exchange_buffer(spar, p.nb, n, p.W, peer)] = (int)r;
             }
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }

@@ -678,7 +678,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (tid == MF_THREADS - 1) {
             int has = 0;                       // bit n: buffer n holds a message for this merge point
             for (int n = 0; merge_point && n < p.nb; ++n) {
-                int *stp = p.stamp + (size_t)(rpar * p.nb + n) * p.W + i;
+                int *stp = p.stamp + exchange_buffer(rpar, p.nb, n, p.W, i);
                 if (det) {
                     // stamps of one buffer only grow, so the test for the round needs no clearing
                     if (sync && t > t0) {      // (at the first step of a launch the message, if any, was sent before it)
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 
         const int has_mask = s_has_ext;      // uniform over the workgroup
         const float inv_b = 1.0f / (float)b;
-        const float *ext0 = p.slot + ((size_t)(rpar * p.nb) * p.W + i) * kd;          // buffer n: + n * W * kd
+        const float *ext0 = p.slot + exchange_buffer(rpar, p.nb, 0, p.W, i) * kd;          // buffer n: + n * W * kd
         const size_t ext_stride = (size_t)p.W * kd;
         if (p.parts > 1) {
             // ---- partial messages (Sec. 4.4): copy n for this worker carries the centroid rows c with
@@ -866,7 +866,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 int rowmask = 0;
                 for (int n = 0; n < p.nb; ++n) {
-                    if (!(has_mask >> n & 1) || c % p.parts != (s_ext_round[n] + i + n) % p.parts) continue;
+                    if (!(has_mask >> n & 1) || !row_travels(c, s_ext_round[n], i, n, p.parts)) continue;
                     float we[NJ];
                     double lhs = 0.0, rhs = 0.0, nrm = 0.0;
 #pragma unroll
@@ -1056,22 +1056,22 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                     __syncthreads();
                 }
-                float4 *dst = reinterpret_cast<float4 *>(p.slot + ((size_t)(spar * p.nb + n) * p.W + peer) * kd);
+                float4 *dst = reinterpret_cast<float4 *>(p.slot + exchange_buffer(spar, p.nb, n, p.W, peer) * kd);
                 const float4 *src = reinterpret_cast<const float4 *>(wst);
                 if (p.parts == 1) {
                     for (size_t e = tid; e < kd / 4; e += MF_THREADS) dst[e] = src[e];
                 } else {
                     // only the rows of the part travel: row c = part + P * m, float4 column q4 (d is a multiple of 4)
-                    const int part = (int)((r + peer + n) % p.parts), row4 = d / 4;
-                    const int nrows = (k - part + p.parts - 1) / p.parts;
+                    const int part = message_part(r, peer, n, p.parts), row4 = d / 4;
+                    const int nrows = part_rows(k, part, p.parts);
                     for (int e = tid; e < nrows * row4; e += MF_THREADS) {
-                        const size_t o = (size_t)(part + p.parts * (e / row4)) * row4 + e % row4;
+                        const size_t o = (size_t)part_row(part, p.parts, e / row4) * row4 + e % row4;
                         dst[o] = src[o];
                     }
                 }
                 __threadfence();
                 __syncthreads();
-                if (tid == 0) __hip_atomic_store(p.stamp + (size_t)(spar * p.nb + n) * p.W + peer, (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0) __hip_atomic_store(p.stamp + exchange_buffer(spar, p.nb, n, p.W, peer), (int)r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (tid == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
         }
