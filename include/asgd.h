@@ -60,12 +60,11 @@ enum {
                                     the way (Sec. 4.4: a lost message is harmless).  Default 0. */
     ASGD_OPT_KERNEL = 7,         /* ASGD_KERNEL_*: which implementation runs the steps.
                                     Default auto.  All give the same results to rounding.  The kernels keep
-                                    a message in flight in different formats, and one is in flight exactly
-                                    when the step counter is a positive multiple of E: a run that would
-                                    start there with another kernel than the previous run fails with
-                                    ASGD_ESTATE (run up to a step that is not a multiple of E first). */
+                                    messages in flight in different formats; when the kernel changes between
+                                    two runs the library carries them over (see asgd_get_exchange). */
     ASGD_OPT_TUNE = 8,           /* launch-shape variant of the chosen kernel (0 = default); for
-                                    performance experiments, never changes what is computed */
+                                    performance experiments: the variants compute the same thing and may
+                                    differ in the rounding of their sums */
     ASGD_OPT_COOPERATIVE = 9,    /* 1 (default): a run that needs all its workgroups resident at the
                                     same time is started with a cooperative launch, which refuses
                                     grids that cannot be; 0: plain launch of the same grid (for tools

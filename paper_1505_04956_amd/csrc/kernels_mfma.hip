@@ -127,9 +127,9 @@ struct MfmaGeom {
     int kq;        // centroids per owner wave (c % nwv), rounded up
     int ns;        // nwv * kq sort slots: slot(c) = (c % nwv) * kq + c / nwv
     int nr;        // shares of the mini-batch in the counting sort (waves that count and place): a power of two <= nwv
-    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, bytes;
+    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, off_sums, off_scale, bytes;
 };
-__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv)
+__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv, bool fused = false)
 {
     MfmaGeom g;
     const int DP = nch * 8 + 4;
@@ -147,6 +147,11 @@ __host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool reside
     g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
     g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
     if (resident) o += (size_t)nwv * 32 * ((b + 32 * nwv - 1) / (32 * nwv)) * sizeof(unsigned short);
+    o = (o + 15) / 16 * 16;
+    g.off_sums = o;         // fused sums: k rows of 8 * nch fixed-point sums, then scale and inverse scale per column
+    if (fused) o += (size_t)k * nch * 8 * sizeof(int);
+    g.off_scale = o;
+    if (fused) o += (size_t)2 * nch * 8 * sizeof(float);
     g.bytes = (o + 15) / 16 * 16;
     return g;
 }
@@ -204,7 +209,14 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
 //           before), and a sender waits until the recipient has passed the merge point that read the older message
 //           in the same buffer.  Every wait is on an earlier round, so the waits cannot form a cycle, and every
 //           wait is bounded: when the bound expires the worker goes on without the message and the host reports it.
-template <int NCH, bool RES, int NWV>
+// FS (fused sums, resident state only): the per-centroid sums of Eq. 9 are formed tile by tile from the sample
+//     fragments a wave still holds in registers when the assignments of the tile are final, so the mini-batch is read
+//     from memory ONCE.  The sums are 32-bit fixed-point numbers in LDS, added with integer atomics: integer addition
+//     is associative, so the result does not depend on the order in which waves and lanes get there (reproducible
+//     bit for bit), and with the scale of column j chosen as the largest power of two with b * max|x_j| * scale < 2^30
+//     a sum cannot overflow and is more accurate than an fp32 sum of the same terms (every term is off by at most
+//     half a unit = 2^-31 of the largest possible sum).  No counting sort, no gather.
+template <int NCH, bool RES, int NWV, bool FS>
 __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
                                                                  const float *xnorm2max_ptr, int sync)
 {
@@ -231,7 +243,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int k = p.k, d = p.d, b = p.b;
-    const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV);
+    static_assert(!FS || RES, "fused sums need the resident state");
+    const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV, FS);
     const size_t kd = (size_t)k * d;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
 
@@ -242,6 +255,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     unsigned short *idx = reinterpret_cast<unsigned short *>(smem_raw + g.off_idx);   // b assignments
     unsigned short *perm = reinterpret_cast<unsigned short *>(smem_raw + g.off_perm); // b samples sorted by centroid
     unsigned short *flist = reinterpret_cast<unsigned short *>(smem_raw + g.off_flist);
+    int *fxsum = reinterpret_cast<int *>(smem_raw + g.off_sums);                       // FS: k x DP8 fixed-point sums
+    float *colscale = reinterpret_cast<float *>(smem_raw + g.off_scale);              // FS: DP8 scales, then DP8 inverse scales
 
     float *wst = p.w + (size_t)i * kd;                  // state of this worker
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
@@ -275,6 +290,21 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     wn2max = 0.0f;
 #pragma unroll
     for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
+    if constexpr (FS) {
+        // scale of column j: 2^e with b * max|x_j| * 2^e in [2^29, 2^30) (max|x_j| over the loaded samples)
+        for (int j = tid; j < DP8; j += MF_THREADS) {
+            const float m = j < d ? (float)b * p.xabsmax[j] : 0.0f;
+            float sc = 0.0f, inv = 0.0f;
+            if (m > 0.0f && m < 1.0e30f) {
+                int q = 0;
+                (void)frexpf(m, &q);              // m = f * 2^q, f in [0.5, 1)
+                sc = ldexpf(1.0f, 30 - q);
+                inv = ldexpf(1.0f, q - 30);
+            }
+            colscale[j] = sc;
+            colscale[DP8 + j] = inv;
+        }
+    }
     __syncthreads();
 
     long long rechecks = 0;
@@ -336,8 +366,27 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             }
         };
-        // the wave's rows nbase .. nbase + 31; its next rows start at nbase_next (past the mini-batch: none)
-        auto do_tile = [&](float4(&xf)[NCH], int nbase, int nbase_next, bool refill) {
+        // FS: adds the sample whose fragments the lane pair (l32, half) holds to the fixed-point sums of centroid c.
+        // A fragment past the last column start of its half-wave is a clamped duplicate (see frag) and is left out.
+        auto add_sample = [&](const float4(&xv)[NCH], int c) {
+            int *row = fxsum + c * DP8 + col0;
+            const float *sc = colscale + col0;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                if (ch * 8 + col0 <= collim && (half == 0 || d >= 8)) {
+                    const float4 s4 = *reinterpret_cast<const float4 *>(sc + ch * 8);
+                    atomicAdd(row + ch * 8 + 0, __float2int_rn(xv[ch].x * s4.x));
+                    atomicAdd(row + ch * 8 + 1, __float2int_rn(xv[ch].y * s4.y));
+                    atomicAdd(row + ch * 8 + 2, __float2int_rn(xv[ch].z * s4.z));
+                    atomicAdd(row + ch * 8 + 3, __float2int_rn(xv[ch].w * s4.w));
+                }
+            }
+            if (half == 0) atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);      // samples of the centroid's slot
+        };
+        // the wave's rows nbase .. nbase + 31 (fragments xf); its next rows start at nbase_next (past the mini-batch:
+        // none) and their fragments go to xn (FS: another set of registers, xf is still needed when the tile is done;
+        // otherwise the same set)
+        auto do_tile = [&](float4(&xf)[NCH], float4(&xn)[NCH], int nbase, int nbase_next, bool refill) {
             float4 st[NST];
             if constexpr (!RES) {
                 __syncthreads();             // nobody still reads the stage
@@ -393,7 +442,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                     // the last half-block has used this fragment for the last time: fetch the next tile's into its
                     // place, so that the fetch runs behind the matrix work and the epilogue of this tile
-                    if constexpr (MODE == 2) xf[ch] = frag(nextoff, ch);
+                    if constexpr (MODE == 2) xn[ch] = frag(nextoff, ch);
                     __builtin_amdgcn_sched_barrier(0);
                     a = nx;
                 }
@@ -541,6 +590,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = arg;
                 }
             }
+            if constexpr (FS) {
+                // the assignment is final unless the sample waits for the exact decision between two candidates
+                // (those are added when they are decided); both lanes of the pair need it
+                const int settled = (mine && !(close2 && !close3)) ? arg : -1;
+                const int c = __shfl(settled, l32, 64);
+                if (c >= 0) add_sample(xf, c);
+            }
         };
         if constexpr (RES) {
             {
@@ -551,6 +607,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             }
             if (tid == 0) s_next_rows = TM;                   // the first 32 rows of every wave are fixed
+            if constexpr (FS) {
+                for (int e = tid; e < k * DP8; e += MF_THREADS) fxsum[e] = 0;
+                for (int e = tid; e < g.ns; e += MF_THREADS) cursor[e] = 0;
+            }
             __syncthreads();
         }
         {
@@ -560,17 +620,36 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             if constexpr (RES) {
                 // No barrier inside this phase: the waves take their groups of 32 rows from a counter, so that a
                 // wave that is held up (it shares its SIMD with a wave of another workgroup) does fewer of them.
-                int cur = wave * 32;
-                while (cur < b) {
+                auto next_rows = [&]() -> int {
                     int v = 0;
                     if (lane == 0) v = atomicAdd(&s_next_rows, 32);
-                    const int nxt = __builtin_amdgcn_readfirstlane(v);
-                    do_tile(xa, cur, nxt, nxt < b);
-                    cur = nxt;
+                    return __builtin_amdgcn_readfirstlane(v);
+                };
+                int cur = wave * 32;
+                if constexpr (FS) {
+                    // two sets of fragment registers take turns
+                    float4 xb2[NCH];
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) xb2[ch] = xa[ch];
+                    while (cur < b) {
+                        int nxt = next_rows();
+                        do_tile(xa, xb2, cur, nxt, nxt < b);
+                        cur = nxt;
+                        if (cur >= b) break;
+                        nxt = next_rows();
+                        do_tile(xb2, xa, cur, nxt, nxt < b);
+                        cur = nxt;
+                    }
+                } else {
+                    while (cur < b) {
+                        const int nxt = next_rows();
+                        do_tile(xa, xa, cur, nxt, nxt < b);
+                        cur = nxt;
+                    }
                 }
             } else {
                 for (int tile0 = 0; tile0 < b; tile0 += TM)
-                    do_tile(xa, tile0 + wave * 32, tile0 + TM + wave * 32, tile0 + TM < b);
+                    do_tile(xa, xa, tile0 + wave * 32, tile0 + TM + wave * 32, tile0 + TM < b);
             }
         }
         __builtin_amdgcn_s_setprio(3);
@@ -610,11 +689,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     dd += ((double)wa.w - (double)wb.w) * (((double)wa.w + (double)wb.w) - 2.0 * (double)xv[ch].w);
                 }
                 dd += __shfl_xor(dd, 32, 64);
+                const int lo = ca < cb2 ? ca : cb2;
+                const int res = dd < 0.0 ? ca : (dd > 0.0 ? cb2 : lo);
                 if (act && half == 0) {
-                    const int lo = ca < cb2 ? ca : cb2;
-                    const int res = dd < 0.0 ? ca : (dd > 0.0 ? cb2 : lo);
                     idx[n] = (unsigned short)res;
                     if (p.dump) p.dump[((size_t)(t - p.t_dump0) * p.W + i) * b + n] = res;
+                }
+                if constexpr (FS) {
+                    if (act) add_sample(xv, res);
                 }
             }
             rechecks += (lane == 0) ? nfl : 0;
@@ -634,6 +716,37 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int NR = g.nr;
         const int spw = ((b + 63) / 64 + NR - 1) / NR * 64;
         const int n_lo = min(b, wave * spw), n_hi = wave < NR ? min(b, n_lo + spw) : n_lo;
+        if constexpr (FS) {
+            // The sums and the counts per slot are complete once every wave is here.  The row passes below take the
+            // count of a centroid from the list starts: an exclusive prefix over the slots (one wave), and the
+            // fixed-point sums go to the scratch rows in fp32 (exact integers times a power of two).
+            __syncthreads();
+            if (wave == 0) {
+                int running = 0;
+                for (int base = 0; base < g.ns; base += 64) {
+                    const int e = base + lane;
+                    const int v = e < g.ns ? cursor[e] : 0;
+                    int incl = v;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const int o = __shfl_up(incl, off, 64);
+                        if (lane >= off) incl += o;
+                    }
+                    if (e < g.ns) cstart[e] = incl - v + running;
+                    running += __shfl(incl, 63, 64);
+                }
+                if (lane == 0) cstart[g.ns] = running;
+            }
+            for (int e = tid; e < k * (DP8 / 4); e += MF_THREADS) {
+                const int c = e / (DP8 / 4), j = 4 * (e - c * (DP8 / 4));
+                if (j < d) {
+                    const int4 v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
+                    const float4 inv = *reinterpret_cast<const float4 *>(colscale + DP8 + j);
+                    *reinterpret_cast<float4 *>(gsc + (size_t)c * d + j) =
+                        make_float4((float)v.x * inv.x, (float)v.y * inv.y, (float)v.z * inv.z, (float)v.w * inv.w);
+                }
+            }
+        } else {
         for (int s = tid; s < g.ns * NR; s += MF_THREADS) cursor[s] = 0;
         if (tid == 0) s_next_item = 0;
         __syncthreads();                                   // also: idx complete
@@ -672,6 +785,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             if (wave == MF_WAVES - 1 && lane == 0) cstart[g.ns] = woff + running;
         }
+        }
         const bool merge_point = (p.E > 0 && p.W > 1 && t > 0 && (t % p.E) == 0);
         const long long r_now = p.E > 0 ? t / p.E : 0;
         const int rpar = det ? (int)((r_now - 1) & 1) : 0;
@@ -704,6 +818,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __syncthreads();
         // the message was written by another workgroup, maybe on another XCD, during this launch
         if (sync && merge_point) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if constexpr (!FS) {
         // placement: a wave walks its samples in order
         int nbits = 1;
         while ((1 << nbits) < k) ++nbits;
@@ -835,6 +950,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (j < d) gsc[(size_t)cur * d + j] = S[jq];
                 }
             }
+        }
         }
         __threadfence_block();
         __syncthreads();
@@ -1255,15 +1371,15 @@ hipError_t launch_qe_nch(const float *x, long long N, int d, int k, const float 
 
 constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 
-template <int NCH, bool RES, int NWV>
+template <int NCH, bool RES, int NWV, bool FS = false>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
-    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV).bytes;
-    const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV>;
+    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV, FS).bytes;
+    const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV, FS>;
     hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     if (!persistent) {
-        hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max, 0);
+        hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FS>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max, 0);
         return hipGetLastError();
     }
     // one launch with waits inside: every workgroup must be resident
@@ -1279,7 +1395,7 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const
     int sync = 1;
     void *args[] = {&pp, &a0, &a1, &xn, &sync};
     if (p.cooperative) return hipLaunchCooperativeKernel(kern, dim3(p.W), dim3(64 * NWV), args, (unsigned)lds, s);
-    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV>), dim3(p.W), dim3(64 * NWV), lds, s, pp, a0, a1, xn, sync);
+    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FS>), dim3(p.W), dim3(64 * NWV), lds, s, pp, a0, a1, xn, sync);
     return hipGetLastError();
 }
 template <int NCH>
@@ -1288,6 +1404,17 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
     // tune bit 0 forces 8 waves, bit 1 forces 4 waves (resident variant only); bit 2 (host side) forces one launch per
     // round, bit 3 one launch with waits also for 8 waves
     const size_t half_cu = 78 * 1024;      // two workgroups per CU must fit 160 KB, a little is reserved
+    // Fused sums (the mini-batch is read once): eight waves, resident state and the fixed-point sums in LDS, which
+    // leaves room for ONE workgroup per CU.  Measured on the k = d = 100 workload: 6.5 ms per epoch against 7.2 ms for
+    // the same shape with sort and gather, but 6.1 ms for two four-wave workgroups per CU with sort and gather, whose
+    // memory phases hide behind each other's matrix work; so it is not the default.  tune bit 5 asks for it.
+    if constexpr (NCH <= 13) {             // (d = 128 would spill registers with two sets of fragments)
+        const bool fits = mfma_geom(p.k, p.b, NCH, true, 8, true).bytes <= MF_LDS_BUDGET;
+        if (fits && (p.tune & 32)) {
+            if (persistent && !(p.tune & 8)) return hipErrorNotSupported;      // one workgroup per CU: one launch per round
+            return launch_variant<NCH, true, 8, true>(p, t0, t1, xnorm2max, s, persistent);
+        }
+    }
     if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2)))
         return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);
     // One workgroup per CU: the workers keep pace by themselves and one launch per round measured 1 % faster than the

@@ -228,6 +228,29 @@ def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N):
     assert g.stats().kernel == 3
 
 
+@pytest.mark.parametrize("k,d,W,b,E,steps,N,weights,buffers,parts,drop", [
+    (100, 100, 4, 2000, 2, 7, 4 * 2000 * 3, "zipf1.1", 1, 1, 0.0),       # relative of the k = d = 100 workload
+    (33, 36, 5, 300, 3, 8, 5 * 1000 + 3, "equal", 1, 1, 0.0),            # ragged last tile, odd row length
+    (70, 8, 3, 100, 2, 9, 3 * 450 + 2, "equal", 1, 1, 0.3),              # b below one tile, small clusters
+    (2, 4, 2, 129, 1, 6, 2 * 400, "equal", 1, 1, 0.0),                   # smallest k and d: one half-wave holds the row
+    (128, 64, 2, 256, 1, 5, 2 * 1024, "equal", 1, 1, 0.0),               # exact multiples of all tile sizes
+    (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "zipf1.1", 2, 1, 0.0),     # skewed cluster sizes: many lanes add to one row
+    (40, 20, 12, 100, 2, 17, 12 * 1800 + 7, "equal", 2, 4, 0.0),         # with partial messages and two buffers
+])
+def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weights, buffers, parts, drop):
+    """The variant that forms the gradient sums tile by tile in fixed point (no second read of the mini-batch), asked for
+    with its tune bit; against the oracle, and bit for bit against itself (run twice, run in
+    pieces) - integer sums do not depend on the order in which the waves get there."""
+    X = make_data(N, d, k, seed=29, weights=weights)
+    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=32, buffers=buffers, parts=parts, drop_rate=drop)
+    assert g.stats().kernel == 3
+    Xg = to_dev(X)
+    kw = dict(E=E, kernel=3, tune=32, buffers=buffers, parts=parts, drop_rate=drop)
+    again = B.ASGD(k, d, W, b, 0.02, **kw); again.load_shards(Xg); again.run_steps(2); again.run_steps(steps - 2)
+    assert np.array_equal(g.get_state(), again.get_state())
+    assert np.array_equal(g.worker_counters(), again.worker_counters())
+
+
 def test_matrix_core_kernel_options(B, oracle):
     X = make_data(6 * 1200, 20, 40, seed=22)
     run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11, parzen=False, kernel=3)
