@@ -29,6 +29,7 @@
 #include <type_traits>
 
 #include "asgd_internal.h"
+#include "mfma_geom.h"
 
 namespace asgd {
 
@@ -37,7 +38,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Waves per workgroup is a template parameter NWV (8 or 4): a tile has 32 samples per wave.
-constexpr int WB = 64;           // centroid rows per block (2 matrix tiles of 32)
+constexpr int WB = MFMA_WB;      // centroid rows per block (2 matrix tiles of 32)
 constexpr int RB = 8;            // rows per wave and iteration in the row passes (loads in flight)
 constexpr int GS = 16;           // sample rows in flight per wave in the gather (small clusters)
 constexpr int GU = 16;           // sample rows in flight per half-wave in the gather (large clusters)
@@ -120,42 +121,6 @@ __device__ __forceinline__ float wave_sum_f(float v)
     return (a + b) + (c + d);
 }
 
-// LDS layout, shared by host and device
-struct MfmaGeom {
-    int kpad;      // k rounded up to a multiple of WB
-    int nblocks;   // kpad / WB
-    int kq;        // centroids per owner wave (c % nwv), rounded up
-    int ns;        // nwv * kq sort slots: slot(c) = (c % nwv) * kq + c / nwv
-    int nr;        // shares of the mini-batch in the counting sort (waves that count and place): a power of two <= nwv
-    size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, off_sums, off_scale, bytes;
-};
-__host__ __device__ inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv, bool fused = false)
-{
-    MfmaGeom g;
-    const int DP = nch * 8 + 4;
-    g.kpad = (k + WB - 1) / WB * WB;
-    g.nblocks = g.kpad / WB;
-    g.kq = (k + nwv - 1) / nwv;
-    g.ns = nwv * g.kq;
-    g.nr = nwv;
-    while (g.nr > 1 && (size_t)g.ns * g.nr * sizeof(int) > 32768) g.nr /= 2;     // the counters stay within 32 KB
-    size_t o = (size_t)(resident ? g.kpad : 2 * WB) * DP * sizeof(float);
-    g.off_h = o;            o += (size_t)g.kpad * sizeof(float);
-    g.off_cstart = o;       o += ((size_t)g.ns + 4) / 4 * 4 * sizeof(int);
-    g.off_cursor = o;       o += ((size_t)g.ns * g.nr + 3) / 4 * 4 * sizeof(int);
-    g.off_idx = o;          o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
-    g.off_perm = o;         o += ((size_t)b + 7) / 8 * 8 * sizeof(unsigned short);
-    g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
-    if (resident) o += (size_t)nwv * 32 * ((b + 32 * nwv - 1) / (32 * nwv)) * sizeof(unsigned short);
-    o = (o + 15) / 16 * 16;
-    g.off_sums = o;         // fused sums: k rows of 8 * nch fixed-point sums, then scale and inverse scale per column
-    if (fused) o += (size_t)k * nch * 8 * sizeof(int);
-    g.off_scale = o;
-    if (fused) o += (size_t)2 * nch * 8 * sizeof(float);
-    g.bytes = (o + 15) / 16 * 16;
-    return g;
-}
-inline int mfma_chunks(int d) { return d <= 32 ? 4 : d <= 64 ? 8 : d <= 104 ? 13 : 16; }
 
 // max over rows of |x|^2 (one value), used by the rounding-error bound.  A half-wave takes a row (32 lanes x float4
 // cover d <= 128 floats, d a multiple of 4, rows 16-byte aligned: what the matrix-core kernel requires anyway), so
