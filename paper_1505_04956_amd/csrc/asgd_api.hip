@@ -555,9 +555,9 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     const bool mfma_parts_ok = ctx->parts == 1 || (double)ctx->W * ctx->k * ctx->d <= (double)ASGD_MFMA_PARTS_MAX_STATE;
     const bool mfma_ok = mfma_kernel_supports(ctx->k, ctx->d, ctx->b, ctx->x) && ctx->lr_mode == ASGD_LR_CONST && mfma_parts_ok;
     if (kernel == ASGD_KERNEL_AUTO) {
-        // the matrix-core kernel pays off once the k x d contraction dominates a step
-        kernel = small_ok ? ASGD_KERNEL_SMALL
-                          : (mfma_ok && ctx->k >= 32 && ctx->d >= 16 ? ASGD_KERNEL_MFMA : ASGD_KERNEL_GENERIC);
+        // the streaming kernel for the small shapes it is built for; else the matrix-core kernel wherever its
+        // layout rules allow (measured faster than the shape-agnostic kernel down to k = d = 4); else the latter
+        kernel = small_ok ? ASGD_KERNEL_SMALL : (mfma_ok ? ASGD_KERNEL_MFMA : ASGD_KERNEL_GENERIC);
     }
     if (kernel == ASGD_KERNEL_SMALL && !small_ok) return ASGD_EINVAL;
     if (kernel == ASGD_KERNEL_MFMA) {

@@ -251,6 +251,17 @@ def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weigh
     assert np.array_equal(g.worker_counters(), again.worker_counters())
 
 
+@pytest.mark.parametrize("k,d", [(12, 8), (5, 4), (20, 32)])
+def test_automatic_choice_prefers_the_matrix_core_kernel(B, oracle, k, d):
+    # shapes the streaming kernel is not built for, with rows the matrix-core kernel can take (d % 4 = 0)
+    X = make_data(4 * 900 + 3, d, k, seed=44)
+    g, o = run_both(B, oracle, X, k, 4, 150, 0.05, 2, 9)
+    assert g.stats().kernel == B.KERNEL_MFMA
+    Xo = make_data(4 * 900 + 3, d + 1, k, seed=45)                      # odd row length: the shape-agnostic kernel
+    g, o = run_both(B, oracle, Xo, k, 4, 150, 0.05, 2, 9)
+    assert g.stats().kernel == B.KERNEL_GENERIC
+
+
 def test_matrix_core_kernel_options(B, oracle):
     X = make_data(6 * 1200, 20, 40, seed=22)
     run_both(B, oracle, X, 40, 6, 200, 0.05, 2, 11, parzen=False, kernel=3)
