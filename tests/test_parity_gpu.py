@@ -621,6 +621,28 @@ def test_resume_at_a_merge_point(B, oracle, kernel, k, d, W, b, buffers, parts):
     assert e.value.code == B.EINVAL
 
 
+@pytest.mark.parametrize("kernel,k,d,W,b", [(2, 10, 10, 6, 200), (3, 40, 20, 4, 600), (1, 7, 5, 5, 150)])
+def test_exchange_export_in_free_running_mode(B, kernel, k, d, W, b):
+    """Free-running mode makes no promise of reproducibility; the export still has to be a consistent snapshot: rounds
+    between -1 and the newest one that has sent, finite rows, zeros where nothing waits; handed to a new context (also
+    one that runs another kernel) the run goes on, and the messages are found at the next merge point."""
+    E, t_stop = 2, 8
+    X = to_dev(make_data(W * b * 5 + 3, d, k, seed=52))
+    a = B.ASGD(k, d, W, b, 0.1, E=E, seed=3, kernel=kernel, mode=B.MODE_FREE_RUNNING, buffers=2)
+    a.load_shards(X); a.run_steps(t_stop)
+    values, rounds = a.get_exchange()
+    assert rounds.min() >= -1 and rounds.max() <= t_stop // E - 1 and (rounds >= 0).any()
+    assert np.all(np.isfinite(values)) and not values[rounds < 0].any() and values[rounds >= 0].any()
+    for other in (kernel, 1):
+        c = B.ASGD(k, d, W, b, 0.1, E=E, seed=3, kernel=other, mode=B.MODE_FREE_RUNNING, buffers=2)
+        c.load_shards(X)
+        c.set_state(-2, a.get_state()); c.set_step(t_stop); c.set_exchange(values, rounds)
+        c.run_steps(1)                                        # t_stop is a merge point: the waiting messages are looked at
+        assert c.stats().received == int((rounds >= 0).sum()) and np.all(np.isfinite(c.get_state()))
+        c.run_steps(5)
+        assert np.all(np.isfinite(c.get_state()))
+
+
 def test_schedule_matches_oracle(B, oracle):
     for W in (2, 5, 1024):
         for r in range(5):
