@@ -43,8 +43,11 @@ struct asgd_ctx {
     uint64_t tab_seed = 0;
     int tab_W = 0;
     bool xnorm2max_valid = false;
-    int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr, *error_flag = nullptr;
-    int *flag_host = nullptr;   // pinned: the error flag is copied here behind the kernels of a run, one wait covers both
+    int *stamp = nullptr, *consumed = nullptr, *cnt = nullptr, *assign_tmp = nullptr;
+    // Error flag of the kernels (an expired bounded wait), in pinned host memory that the device writes directly: the
+    // host clears and reads it around a run without a memset or a copy on the stream (each is a separate operation
+    // of several microseconds, which counts when a run is one launch of less than a millisecond).
+    int *flag_host = nullptr;
     long long *ncum = nullptr, *counters = nullptr;
     double *qpart = nullptr, *qout = nullptr;
     int32_t *dump = nullptr;
@@ -79,7 +82,7 @@ size_t kd_of(const asgd_ctx *c) { return (size_t)c->k * c->d; }
 void free_all(asgd_ctx *c)
 {
     void *ptrs[] = {c->w, c->slot, c->acc, c->xabsmax, c->mean, c->stamp, c->consumed, c->cnt, c->assign_tmp,
-                    c->error_flag, c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max, c->shift_tab};
+                    c->ncum, c->counters, c->qpart, c->qout, c->xnorm2max, c->shift_tab};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     if (c->flag_host) (void)hipHostFree(c->flag_host);
@@ -93,7 +96,7 @@ StepParams make_params(const asgd_ctx *c)
     memset(&p, 0, sizeof(p));
     p.x = c->x; p.w = c->w; p.slot = c->slot; p.stamp = c->stamp; p.consumed = c->consumed; p.ncum = c->ncum;
     p.counters = c->counters; p.acc = c->acc; p.cnt = c->cnt; p.assign_tmp = c->assign_tmp;
-    p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->error_flag;
+    p.dump = c->dump; p.xabsmax = c->xabsmax; p.error_flag = c->flag_host;
     p.H = c->H; p.S = c->S; p.t_dump0 = c->t; p.seed = c->seed;
     p.k = c->k; p.d = c->d; p.W = c->W; p.b = c->b; p.E = c->E; p.eps = c->lr; p.nb = c->nb; p.parts = c->parts;
     p.parzen = c->parzen; p.lr_mode = c->lr_mode; p.mode = c->mode;
@@ -307,7 +310,6 @@ int asgd_create(asgd_ctx **out, int k, int d, int W, int b, float lr)
         {(void **)&c->consumed, Wz * sizeof(int)},
         {(void **)&c->cnt, Wz * k * sizeof(int)},
         {(void **)&c->assign_tmp, Wz * (size_t)b * sizeof(int)},
-        {(void **)&c->error_flag, sizeof(int)},
         {(void **)&c->ncum, Wz * k * sizeof(long long)},
         {(void **)&c->counters, Wz * CNT_STRIDE * sizeof(long long)},
         {(void **)&c->qpart, (size_t)quant_partials_count() * sizeof(double)},
@@ -446,7 +448,6 @@ int asgd_load_shards(asgd_ctx *ctx, const float *x_dev, int64_t N, void *hip_str
     ctx->fill_kernel = 0;
     HIP_TRY(ctx, hipMemsetAsync(ctx->ncum, 0, (size_t)ctx->W * ctx->k * sizeof(long long), ctx->stream));
     HIP_TRY(ctx, hipMemsetAsync(ctx->counters, 0, (size_t)ctx->W * CNT_STRIDE * sizeof(long long), ctx->stream));
-    HIP_TRY(ctx, hipMemsetAsync(ctx->error_flag, 0, sizeof(int), ctx->stream));
     // per-dimension max |x| over the rows the workers own: input of the rounding-error bound
     // that decides when an assignment is recomputed exactly
     HIP_TRY(ctx, launch_absmax(x_dev, H * ctx->W, ctx->d, ctx->xabsmax, ctx->stream));
@@ -633,7 +634,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     // earlier launch on the same stream.
     const bool rounds = (ctx->mode == ASGD_MODE_DETERMINISTIC && ctx->E > 0 && ctx->W > 1);
     int launches = 0;
-    HIP_TRY(ctx, hipMemsetAsync(ctx->error_flag, 0, sizeof(int), ctx->stream));
+    *ctx->flag_host = 0;         // (no kernel of this context is in flight: every run ends with a wait for the stream)
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
     bool done = false;
     const bool one_launch = (kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3) || (kernel == ASGD_KERNEL_MFMA && !(ctx->tune & 4));
@@ -672,7 +673,6 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         ctx->passed_t = -1;
     }
     HIP_TRY(ctx, hipEventRecord(ctx->ev1, ctx->stream));
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->flag_host, ctx->error_flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     float ms = 0.f;
     HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev0, ctx->ev1));

@@ -28,7 +28,7 @@ struct StepParams {
     int *assign_tmp;       // W x b assignment scratch
     int32_t *dump;         // optional assignment dump (step-major), or nullptr
     const float *xabsmax;  // d per-dimension max |x| over the loaded samples
-    int *error_flag;       // set non-zero by a kernel whose bounded wait expired
+    int *error_flag;       // pinned host memory, set to 1 by a kernel whose bounded wait expired
     const int *shift_tab;  // deterministic schedule: cyclic shift of round r at [r - shift_r0] (small-state kernel)
     long long shift_r0;
     long long H, S;        // shard length, steps per epoch

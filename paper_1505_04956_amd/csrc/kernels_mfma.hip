@@ -766,7 +766,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         if ((p.drop_unannounced || !message_dropped(p.seed, rs, sender, p.drop_thr, n)) && !s_wait_failed &&
                             !mf_wait_flag(stp, (int)rs, false, &s_wait_budget)) {
                             s_wait_failed = 1;
-                            atomicOr(p.error_flag, 1);
+                            __hip_atomic_store(p.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // host memory
                         }
                     }
                     if (__hip_atomic_load(stp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)(r_now - 1)) has |= 1 << n;
@@ -1133,7 +1133,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     // the buffer still holds the message of round r - 2 until the peer has passed merge point r - 1
                     if (tid == 0 && !s_wait_failed && !mf_wait_flag(p.consumed + peer, (int)(r - 1), true, &s_wait_budget)) {
                         s_wait_failed = 1;
-                        atomicOr(p.error_flag, 1);
+                        __hip_atomic_store(p.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // host memory
                     }
                     __syncthreads();
                 }

@@ -976,7 +976,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     if (lane == 0 && rechecks)
         atomicAdd((unsigned long long *)&p.counters[(size_t)blockIdx.x * CNT_STRIDE + CNT_RECHECK],
                   (unsigned long long)rechecks);
-    if (lane == 0 && kp.wait_failed) atomicOr(p.error_flag, 1);
+    if (lane == 0 && kp.wait_failed) __hip_atomic_store(p.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // host memory
 }
 
 // resident workgroups of a kernel on the current device (queried once per device and kernel)
