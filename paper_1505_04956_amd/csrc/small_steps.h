@@ -135,6 +135,25 @@ __device__ __forceinline__ void phase_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
+// One 32-bit value from a wave-uniform address, through the scalar unit: a vector load would have to be waited for with
+// the vector-memory counter, and loads return in order, so that wait would cover every sample load issued before it.
+// (Read only: the table it is used for was written by an earlier kernel.)
+__device__ __forceinline__ int uniform_load(const int *ptr)
+{
+    int v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(ptr) : "memory");
+    return v;
+}
+
+// Adds to a counter in global memory without reading it back: an atomic without return value is not waited for,
+// whereas "counter += v" is a load the wave would have to wait for, and on this chip that wait also covers every
+// sample load issued before it.
+__device__ __forceinline__ void bump(long long *counter, int v)
+{
+    if (v) (void)__hip_atomic_fetch_add(reinterpret_cast<unsigned long long *>(counter), (unsigned long long)v, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // A message of this kernel is self-validating: every element travels as a 64-bit pair (value, round
 // stamp), written and read with relaxed device-scope 64-bit atomic accesses (single-copy atomic; they go
 // through to the memory level all workgroups share, so no cache-wide write-back or invalidation is
@@ -443,9 +462,23 @@ struct SmallKeeper {
     // (the shifts of the rounds of a launch come from a table: no 64-bit division in the kernel)
     __device__ __forceinline__ int shift_of(const StepParams &p, int r, int n) const
     {
-        int sh = p.shift_tab[(long long)r - p.shift_r0] + n;
+        int sh = uniform_load(p.shift_tab + ((long long)r - p.shift_r0)) + n;
         if (sh > p.W - 1) sh -= p.W - 1;
         return sh;
+    }
+
+    // Called once the ring has gone round after fetch(): every load that fetch() issued has returned by then (loads
+    // return in order, and samples requested after them have been used).  Telling the compiler so here, where it can
+    // count the loads issued since, keeps it from waiting for ALL outstanding loads - the samples of the next
+    // mini-batch among them - where the values are first used, at the end of the step.
+    __device__ __forceinline__ void settle_fetched()
+    {
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) asm volatile("" : "+v"(mp[n][c4]));
+            asm volatile("" : "+v"(ackv[n]));
+        }
     }
 
     // Exchange, early part: fetch at the start of a step what its end will need, so that the latency of these
@@ -537,6 +570,11 @@ struct SmallKeeper {
                             --budget;
 #pragma unroll
                             for (int c4 = 0; c4 < 4; ++c4) mp[n][c4] = load_pair(mslot[n] + c4);
+                            // (all four have returned before any is looked at: the test below stops at the first
+                            // pair that does not match, and a load left pending here would make the compiler wait
+                            // for ALL outstanding loads where the values are used, on every path)
+#pragma unroll
+                            for (int c4 = 0; c4 < 4; ++c4) asm volatile("" : "+v"(mp[n][c4]));
                             has_ext[n] = complete();
                         }
                         if (!has_ext[n]) wait_failed = 1;
@@ -593,9 +631,9 @@ struct SmallKeeper {
                     }
                     if (first && nz) {
                         long long *cn = p.counters + (size_t)i * CNT_STRIDE;
-                        cn[CNT_RECEIVED] += __builtin_popcount(nz);
-                        cn[CNT_ACCEPTED] += __builtin_popcount(accb);
-                        cn[CNT_PARZEN_NEAR] += near;
+                        bump(cn + CNT_RECEIVED, __builtin_popcount(nz));
+                        bump(cn + CNT_ACCEPTED, __builtin_popcount(accb));
+                        bump(cn + CNT_PARZEN_NEAR, near);
                     }
                 }
             }
@@ -626,9 +664,9 @@ struct SmallKeeper {
                         }
                         if (first) {
                             long long *cn = p.counters + (size_t)i * CNT_STRIDE;
-                            cn[CNT_RECEIVED] += 1;
-                            cn[CNT_ACCEPTED] += delta;
-                            if (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) cn[CNT_PARZEN_NEAR] += 1;
+                            bump(cn + CNT_RECEIVED, 1);
+                            bump(cn + CNT_ACCEPTED, delta);
+                            bump(cn + CNT_PARZEN_NEAR, (rhs > 0.0 && fabs(lhs - rhs) / rhs < 1e-6) ? 1 : 0);
                         }
                     }
                 }
@@ -681,7 +719,7 @@ struct SmallKeeper {
                     for (int c4 = 0; c4 < 4; ++c4) store_pair(dst + c4, pack_pair(w4[c4], round));
                 }
             }
-            if (lane == 0) p.counters[(size_t)i * CNT_STRIDE + CNT_SENT] += 1;
+            if (lane == 0) bump(p.counters + (size_t)i * CNT_STRIDE + CNT_SENT, 1);
         }
     }
 };
@@ -796,6 +834,14 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
         const float *x0 = wk.first_batch(p, blockIdx.x, D);
 #pragma unroll
         for (int u = 0; u + 1 < PF; ++u) load_row<D>(xr[u], sample_ptr(x0, wave + u * NW));
+        // Wait for them here, once per launch.  The compiler may issue these loads in any order, and a loop entered
+        // with buffer 0 as the youngest load outstanding would make it wait, at the head of EVERY turn of the ring,
+        // until no load at all is outstanding (the count it waits for has to hold on every path into the loop).
+#pragma unroll
+        for (int u = 0; u + 1 < PF; ++u) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) asm volatile("" : "+v"(xr[u][j]));
+        }
     }
 
     // one phase of a row update: add, write, (fence,) read for the next phase
@@ -873,7 +919,8 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 float4 *prow = &acc[wave][K][0][lane % RL];
                 float4 pr = prow[qoff[0]];
 
-                for (int m0 = 0; m0 < ngw; m0 += PF) {
+                int m0 = 0;
+                do {        // (ngw >= PF: at least one turn, which the compiler has to know for settle_fetched)
                     // Refills of this turn: slot 0 takes group m0 + PF - 1 of this mini-batch, slot u >= 1 group
                     // m0 + PF + u - 1, which lies in the next mini-batch for all of them at once in the last turn
                     // (ngw is a multiple of PF).  One scalar decision per turn, constants per slot.
@@ -933,7 +980,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                         prow = &acc[wave][valid ? arg : K][0][lane % RL];
                         pr = prow[qoff[0]];
                     }
-                }
+                    kp.settle_fetched();
+                    m0 += PF;
+                } while (m0 < ngw);
                 // finish the last group of the mini-batch (buffer PF-1)
 #pragma unroll
                 for (int ph = 0; ph < NQ; ++ph) row_phase(xr[PF - 1], ph, prow, pr);
