@@ -65,7 +65,9 @@ void small_kernel_pack_message(int k, int d, const float *rows, const int *row_r
 
 hipError_t launch_small_steps(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
-    if (t1 - t0 > 0x7fffffffLL || p.S > 0x7fffffffLL || (p.E > 0 && t1 / p.E > 0x7ffffff0LL)) return hipErrorInvalidValue;
+    // (32-bit bookkeeping in the kernel: steps of a launch, steps per epoch, rounds, rows of a shard)
+    if (t1 - t0 > 0x7fffffffLL || p.S > 0x7fffffffLL || (p.E > 0 && t1 / p.E > 0x7ffffff0LL) || p.H > 0xffffffffLL)
+        return hipErrorInvalidValue;
 #define LAUNCH_SHAPE(K, D) if (p.k == K && p.d == D) return launch_small_steps_##K##x##D(p, t0, t1, s, persistent);
     ASGD_SMALL_SHAPES(LAUNCH_SHAPE)
 #undef LAUNCH_SHAPE

@@ -333,17 +333,20 @@ struct SmallWalk {
         }
         if (done < nsteps) begin_segment();
     }
-    // first mini-batch of worker i in this segment, and of whatever the workgroup does after worker i's segment
-    // (only loaded from; at the very end any valid address will do)
-    __device__ __forceinline__ const float *first_batch(const StepParams &p, int i, int d) const
+    // First mini-batch of this segment in a shard, and of whatever the workgroup does after this segment of worker i
+    // (only loaded from; at the very end any valid address will do).  shard: first row of worker i's shard; first:
+    // of the workgroup's first worker; stride: elements between the shards of two successive workers of the
+    // workgroup.  (Pointers are carried along instead of being formed from the worker number: 64-bit products are
+    // many scalar instructions, and this runs on every worker's critical path at every round boundary.)
+    __device__ __forceinline__ const float *first_batch(const float *shard, int d) const
     {
-        return p.x + ((size_t)i * p.H + (size_t)s_seg * b) * d;
+        return shard + (size_t)((unsigned)s_seg * (unsigned)b) * (unsigned)d;
     }
-    __device__ __forceinline__ const float *batch_after(const StepParams &p, int i, int d) const
+    __device__ __forceinline__ const float *batch_after(const float *shard, const float *first, size_t stride, int i, int d) const
     {
-        if (i + (int)gridDim.x < W) return p.x + ((size_t)(i + gridDim.x) * p.H + (size_t)s_seg * b) * d;
-        if (!last_seg) return p.x + ((size_t)blockIdx.x * p.H + (size_t)s_next_seg * b) * d;
-        return first_batch(p, i, d);
+        if (i + (int)gridDim.x < W) return shard + stride + (size_t)((unsigned)s_seg * (unsigned)b) * (unsigned)d;
+        if (!last_seg) return first + (size_t)((unsigned)s_next_seg * (unsigned)b) * (unsigned)d;
+        return first_batch(shard, d);
     }
 };
 
@@ -831,7 +834,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
         for (int j = 0; j < D; ++j) xr[u][j] = 0.0f;
     }
     {
-        const float *x0 = wk.first_batch(p, blockIdx.x, D);
+        const float *x0 = wk.first_batch(p.x + (size_t)blockIdx.x * (size_t)p.H * D, D);
 #pragma unroll
         for (int u = 0; u + 1 < PF; ++u) load_row<D>(xr[u], sample_ptr(x0, wave + u * NW));
         // Wait for them here, once per launch.  The compiler may issue these loads in any order, and a loop entered
@@ -869,11 +872,13 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     // values); one that takes several workers in turn stores and reloads it.
     const bool one_worker = (long long)blockIdx.x + gridDim.x >= W;
 
+    const float *xs_first = p.x + (size_t)blockIdx.x * (size_t)p.H * D;      // shard of the workgroup's first worker
+    const size_t xs_stride = (size_t)gridDim.x * (size_t)p.H * D;
     while (wk.done < wk.nsteps) {
-        for (int i = blockIdx.x; i < W; i += gridDim.x) {
-            const float *xs = p.x + (size_t)i * p.H * D;            // this worker's shard
-            const float *xb = wk.first_batch(p, i, D);              // the current mini-batch
-            const float *x_after = wk.batch_after(p, i, D);
+        const float *xs = xs_first;                                 // shard of the worker in turn
+        for (int i = blockIdx.x; i < W; i += gridDim.x, xs += xs_stride) {
+            const float *xb = wk.first_batch(xs, D);                // the current mini-batch
+            const float *x_after = wk.batch_after(xs, xs_first, xs_stride, i, D);
             if (!one_worker || wk.done == 0) kp.load_state(p, i);
             int s_epoch = wk.s_seg, te = wk.te_seg, round = wk.round_seg;
 
