@@ -59,6 +59,19 @@ __device__ __forceinline__ double wave_sum(double v)
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
+// Three sums over the wave at once, level by level: the lane reads of a level are issued together and waited for
+// once, instead of three butterflies of six dependent round trips each one after the other.  Same additions in the
+// same order as wave_sum for each of the three, so every lane ends with the same bits.
+__device__ __forceinline__ void wave_sum3(double &a, double &b, double &c)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double pa = __shfl_xor(a, off, 64), pb = __shfl_xor(b, off, 64), pc = __shfl_xor(c, off, 64);
+        __builtin_amdgcn_sched_barrier(0);
+        a += pa; b += pb; c += pc;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
 
 // max over the wave of a non-negative value, without LDS: butterfly inside rows of 16 lanes with DPP
 // (lane ^ 1, lane ^ 2, mirror inside 8, mirror inside 16), then the four rows through scalar reads.
@@ -657,7 +670,7 @@ struct SmallKeeper {
                             lhs += a * a; rhs += c2 * c2; nrm += wed * wed;
                         }
                     }
-                    lhs = wave_sum(lhs); rhs = wave_sum(rhs); nrm = wave_sum(nrm);
+                    wave_sum3(lhs, rhs, nrm);
                     if (nrm > 0.0) {     // lambda of Eq. 3: an all-zero buffer is empty
                         const int delta = p.parzen ? (lhs < rhs) : 1;       // Eq. 4, every buffer on its own (Eq. 6)
                         if (delta) {
