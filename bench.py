@@ -194,9 +194,9 @@ def main():
         for mode in ("deterministic", "free", "silent"):
             if mode not in per_mode:
                 c = context(mode)
-                for _ in range(args.warmup):
+                for _ in range(max(args.warmup, 20)):      # (the first epochs of a fresh context run slower)
                     c.run_epochs(1)
-                _, ms = timed(c, args.steps)
+                _, ms = timed(c, max(args.steps, 20))
                 per_mode[mode] = sum(ms) / len(ms)
                 c.close()
         out["exchange_overhead"] = {
