@@ -181,7 +181,10 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
 //     bit for bit), and with the scale of column j chosen as the largest power of two with b * max|x_j| * scale < 2^30
 //     a sum cannot overflow and is more accurate than an fp32 sum of the same terms (every term is off by at most
 //     half a unit = 2^-31 of the largest possible sum).  No counting sort, no gather.
-template <int NCH, bool RES, int NWV, bool FS>
+// FSM: 0 = sort and gather, 1 = FS, 2 = sort and gather with the sample fragments of the NEXT tile fetched into a second
+//     set of registers during the first half-block of a tile (instead of into the same set during the last one), so
+//     that a fetch has a whole tile of matrix work to arrive (resident state only).
+template <int NCH, bool RES, int NWV, int FSM>
 __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
                                                                  const float *xnorm2max_ptr, int sync)
 {
@@ -208,7 +211,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int k = p.k, d = p.d, b = p.b;
-    static_assert(!FS || RES, "fused sums need the resident state");
+    constexpr bool FS = FSM == 1, TWO = FSM != 0, PRE = FSM == 2;
+    static_assert(!TWO || RES, "fused sums and the second set of fragments need the resident state");
     const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV, FS);
     const size_t kd = (size_t)k * d;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
@@ -425,7 +429,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if constexpr (!RES) __syncthreads();      // Ws[cb & 1] complete; Ws[(cb + 1) & 1] free
                 const float *Wc = Ws + (RES ? cb : (cb & 1)) * WB * DP;
                 const bool more = !RES && cb + 1 < g.nblocks;
-                const bool lastb = refill && cb + 1 == g.nblocks;
+                const bool lastb = !PRE && refill && cb + 1 == g.nblocks;
                 const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
                 const float *w0row = Wc + l32 * DP + 4 * half;
                 const float *w1row = Wc + (32 + l32) * DP + 4 * half;
@@ -436,7 +440,8 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 // rows 0..31 of this block; meanwhile the scores of rows 32..63 of the previous block are inserted
                 if (cb == 0) {
-                    if (more) half_block(M1(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    if (PRE && refill) half_block(M2(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    else if (more) half_block(M1(), std::false_type(), acc0, w0row, acc1, -1, cb);
                     else half_block(M0(), std::false_type(), acc0, w0row, acc1, -1, cb);
                 } else {
                     if (more) half_block(M1(), std::true_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
@@ -591,7 +596,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     return __builtin_amdgcn_readfirstlane(v);
                 };
                 int cur = wave * 32;
-                if constexpr (FS) {
+                if constexpr (TWO) {
                     // two sets of fragment registers take turns
                     float4 xb2[NCH];
 #pragma unroll
@@ -1336,15 +1341,15 @@ hipError_t launch_qe_nch(const float *x, long long N, int d, int k, const float 
 
 constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 
-template <int NCH, bool RES, int NWV, bool FS = false>
+template <int NCH, bool RES, int NWV, int FSM = 0>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
-    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV, FS).bytes;
-    const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV, FS>;
+    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV, FSM == 1).bytes;
+    const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV, FSM>;
     hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     if (!persistent) {
-        hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FS>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max, 0);
+        hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FSM>), dim3(p.W), dim3(64 * NWV), lds, s, p, t0, t1, xnorm2max, 0);
         return hipGetLastError();
     }
     // one launch with waits inside: every workgroup must be resident
@@ -1360,7 +1365,7 @@ hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const
     int sync = 1;
     void *args[] = {&pp, &a0, &a1, &xn, &sync};
     if (p.cooperative) return hipLaunchCooperativeKernel(kern, dim3(p.W), dim3(64 * NWV), args, (unsigned)lds, s);
-    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FS>), dim3(p.W), dim3(64 * NWV), lds, s, pp, a0, a1, xn, sync);
+    hipLaunchKernelGGL((mfma_steps_kernel<NCH, RES, NWV, FSM>), dim3(p.W), dim3(64 * NWV), lds, s, pp, a0, a1, xn, sync);
     return hipGetLastError();
 }
 template <int NCH>
@@ -1377,11 +1382,17 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
         const bool fits = mfma_geom(p.k, p.b, NCH, true, 8, true).bytes <= MF_LDS_BUDGET;
         if (fits && (p.tune & 32)) {
             if (persistent && !(p.tune & 8)) return hipErrorNotSupported;      // one workgroup per CU: one launch per round
-            return launch_variant<NCH, true, 8, true>(p, t0, t1, xnorm2max, s, persistent);
+            return launch_variant<NCH, true, 8, 1>(p, t0, t1, xnorm2max, s, persistent);
         }
     }
-    if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2)))
+    if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2))) {
+        // the next tile's samples go to a second set of registers a whole tile ahead (1.2 % on the k = d = 100 workload;
+        // d = 128 has no registers for it); tune bit 6 switches it off
+        if constexpr (NCH <= 13) {
+            if (!(p.tune & 64)) return launch_variant<NCH, true, 4, 2>(p, t0, t1, xnorm2max, s, persistent);
+        }
         return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);
+    }
     // One workgroup per CU: the workers keep pace by themselves and one launch per round measured 1 % faster than the
     // waits inside one launch; two workgroups per CU drift apart and gain 3 % from not meeting at every round.
     if (persistent && !(p.tune & 8)) return hipErrorNotSupported;

@@ -221,11 +221,17 @@ def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights
     (70, 8, 3, 100, 2, 9, 3 * 450 + 2),
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5),
 ])
-def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N):
-    # the variant with four waves per worker (two workers per CU), which large W selects by itself
+@pytest.mark.parametrize("tune", [2, 66])
+def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N, tune):
+    # the variant with four waves per worker (two workers per CU), which large W selects by itself: the samples of the
+    # next tile are fetched a whole tile ahead into a second set of registers; +64: into the same registers during the
+    # last block of a tile (same arithmetic, same order)
     X = make_data(N, d, k, seed=23)
-    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=2)
+    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=tune)
     assert g.stats().kernel == 3
+    if tune != 2:
+        plain = B.ASGD(k, d, W, b, 0.02, E=E, kernel=3, tune=2); plain.load_shards(to_dev(X)); plain.run_steps(steps)
+        assert np.array_equal(g.get_state(), plain.get_state())
 
 
 @pytest.mark.parametrize("k,d,W,b,E,steps,N,weights,buffers,parts,drop", [

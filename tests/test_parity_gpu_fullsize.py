@@ -35,10 +35,11 @@ def compare(tag, g, o, ag, ao, gap, q_per_sample, state_tol=1e-4):
     check_counters(g.worker_counters(), o.counters, o.parzen_near)
 
 
-def run_config(oracle, wl, steps, expect_kernel, expect_launches=None):
+def run_config(oracle, wl, steps, expect_kernel, expect_launches=None, kernel=0, **exchange):
+    """`exchange`: options both sides take (parts, buffers); `kernel`: the library's kernel choice (0 = its own)."""
     from paper_1505_04956_amd import binding as B
     X = workloads.generate_device(wl, device="cuda:0")
-    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed)
+    g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed, kernel=kernel, **exchange)
     g.load_shards(X)
     g.enable_assign_dump(steps)
     g.run_steps(steps)
@@ -48,10 +49,10 @@ def run_config(oracle, wl, steps, expect_kernel, expect_launches=None):
         assert st.launches == expect_launches
     ag = g.assign_dump(steps)
     oracle.set_threads(16)
-    o = oracle.OracleASGD(X.cpu().numpy(), k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed)
+    o = oracle.OracleASGD(X.cpu().numpy(), k=wl.k, W=wl.W, b=wl.b, lr=wl.lr, E=wl.E, seed=wl.schedule_seed, **exchange)
     ao, gap = o.run_steps(steps, dump=True)
     qg, qo = g.quant_error(0), o.quant_error(0)
-    compare(wl.name, g, o, ag, ao, gap, qo / wl.N)
+    compare(wl.name + "".join(" %s=%s" % kv for kv in exchange.items()), g, o, ag, ao, gap, qo / wl.N)
     assert abs(qg - qo) <= 1e-4 * qo
     return g, o
 
@@ -74,6 +75,24 @@ def test_contraction_workload_full_size(oracle):
     wl = workloads.CONFIGS[4]
     g, o = run_config(oracle, wl, wl.S + 1, B.KERNEL_MFMA)                # the step after the epoch is a merge step
     assert o.counters[:, 1].sum() == wl.W
+
+
+def test_partial_messages_full_size_streaming_kernel(oracle):
+    """Sec. 4.4 at full size: messages of one part in five of the rows (two centroid rows each), two buffers, on the
+    streaming workload with the kernel the library chooses there; one epoch, every assignment, state and counter."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[1]
+    g, o = run_config(oracle, wl, wl.S, B.KERNEL_SMALL, expect_launches=1, parts=5, buffers=2)
+    assert o.counters[:, 2].sum() > 0
+
+
+def test_partial_messages_full_size_wider_workload(oracle):
+    """Sec. 4.4 on the k = d = 100 workload at full size (W = 512, 25 rows per message), on the shape-agnostic kernel -
+    the matrix-core kernel refuses partial messages for states of this size."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[2]
+    g, o = run_config(oracle, wl, wl.S, B.KERNEL_GENERIC, kernel=B.KERNEL_GENERIC, parts=4)
+    assert o.counters[:, 2].sum() > 0
 
 
 @pytest.mark.skip(reason="partial messages (Sec. 4.4) on the matrix-core kernel at full size: the only batch of such runs "
