@@ -36,6 +36,7 @@ namespace asgd {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Waves per workgroup is a template parameter NWV (8 or 4): a tile has 32 samples per wave.
 constexpr int WB = MFMA_WB;      // centroid rows per block (2 matrix tiles of 32)
@@ -211,9 +212,9 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int i = blockIdx.x;                       // worker
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int k = p.k, d = p.d, b = p.b;
-    constexpr bool FS = FSM == 1, TWO = FSM != 0, PRE = FSM == 2;
+    constexpr bool FS = FSM == 1, TWO = FSM != 0, PRE = FSM >= 2, SS = FSM == 3;
     static_assert(!TWO || RES, "fused sums and the second set of fragments need the resident state");
-    const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV, FS);
+    const MfmaGeom g = mfma_geom(k, b, NCH, RES, NWV, FS ? 1 : (SS ? 2 : 0));
     const size_t kd = (size_t)k * d;
     const int det = (p.mode == ASGD_MODE_DETERMINISTIC);
 
@@ -227,6 +228,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     int *fxsum = reinterpret_cast<int *>(smem_raw + g.off_sums);                       // FS: k x DP8 fixed-point sums
     float *colscale = reinterpret_cast<float *>(smem_raw + g.off_scale);              // FS: DP8 scales, then DP8 inverse scales
 
+    // the last half-block of 32 rows holds at most eight centroids and is the second one of its block: 4x4 tiles there
+    constexpr bool TAILOK = RES && NCH <= 13 && FSM != 1;       // (the other variants have no registers to spare)
+    const int tail_groups = (TAILOK && !(p.tune & 256) && (k & 31) >= 1 && (k & 31) <= 8 && ((k >> 5) & 1)) ? ((k & 31) + 3) / 4 : 0;
+    const int tail_row0 = k & ~31;
     float *wst = p.w + (size_t)i * kd;                  // state of this worker
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
     const float xn2 = *xnorm2max_ptr;
@@ -259,7 +264,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     wn2max = 0.0f;
 #pragma unroll
     for (int v = 0; v < MF_WAVES; ++v) wn2max = fmaxf(wn2max, red_f[v]);
-    if constexpr (FS) {
+    if constexpr (FS || SS) {
         // scale of column j: 2^e with b * max|x_j| * 2^e in [2^29, 2^30) (max|x_j| over the loaded samples)
         for (int j = tid; j < DP8; j += MF_THREADS) {
             const float m = j < d ? (float)b * p.xabsmax[j] : 0.0f;
@@ -379,10 +384,23 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             // instructions; which half-block the two largest came from is found by comparing bit patterns before and
             // after (i1, i2 hold tags until the loop ends).  Two different elements with the same bit pattern end up
             // as v1 == v2 or v2 == v3, which the decisions below treat as "more than two candidates".
-            auto half_block = [&](auto mode, auto ins, floatx16 &acc, const float *wrow, const floatx16 &prev, int prev_tag,
-                                  int cb) {
+            // TAIL (resident state): the half-block holds at most eight centroids (k mod 32 <= 8), whose scores come from
+            // v_mfma_f32_4x4x1 instead - in each block of four lanes a column of four state rows (lane 4q + r supplies
+            // row r) times a row of four samples (lane 4q + j supplies its own), D[r][j] in register r of lane 4q + j:
+            // 8 cycles of the matrix pipe per instruction instead of 64 for 28 rows of padding.  A lane's sum covers
+            // the columns of its own half-wave; the two halves are added afterwards and the scores are put where
+            // a 32x32 tile would have left them (row 4 * half + r in register r), so that everything downstream is
+            // unchanged.  wrow: row (lane mod 4) of the half-block, this half-wave's columns.
+            auto half_block = [&](auto mode, auto ins, auto tail, floatx16 &acc, const float *wrow, const floatx16 &prev,
+                                  int prev_tag, int cb) {
                 constexpr int MODE = decltype(mode)::value;
                 constexpr bool INS = decltype(ins)::value;      // false: first half-block of a tile, nothing to insert
+                constexpr bool TAIL = decltype(tail)::value;
+                floatx4 te = {0.0f, 0.0f, 0.0f, 0.0f}, to = te, t2 = te;      // rows 0..3 (even, odd chunks), rows 4..7
+                float4 a2 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if constexpr (TAIL) {
+                    if (tail_groups > 1) a2 = *reinterpret_cast<const float4 *>(wrow + 4 * DP);
+                }
                 unsigned nextoff = 0;
                 if constexpr (MODE == 2) {
                     nextoff = rowoff_of(nbase_next);
@@ -394,13 +412,28 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int ch = 0; ch < NCH; ++ch) {
                     // operands of the next chunk are read under the matrix work of this one; the scheduling
                     // barrier keeps the compiler from hoisting the reads of ALL chunks to the top (registers)
-                    float4 nx = a;
+                    float4 nx = a, nx2 = a2;
                     if (ch + 1 < NCH) nx = *reinterpret_cast<const float4 *>(wrow + (ch + 1) * 8);
                     const float4 xv = xf[ch];
+                    if constexpr (TAIL) {
+                        if (ch + 1 < NCH && tail_groups > 1) nx2 = *reinterpret_cast<const float4 *>(wrow + 4 * DP + (ch + 1) * 8);
+                        floatx4 &t = (ch & 1) ? to : te;           // two chains: the instructions depend on each other
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.x, xv.x, t, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.y, xv.y, t, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.z, xv.z, t, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.w, xv.w, t, 0, 0, 0);
+                        if (tail_groups > 1) {
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.x, xv.x, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.y, xv.y, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.z, xv.z, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.w, xv.w, t2, 0, 0, 0);
+                        }
+                    } else {
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, xv.x, acc, 0, 0, 0);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, xv.y, acc, 0, 0, 0);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, xv.z, acc, 0, 0, 0);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, xv.w, acc, 0, 0, 0);
+                    }
                     if constexpr (INS) {
 #pragma unroll
                         for (int r = ch * 16 / NCH; r < (ch + 1) * 16 / NCH; ++r)
@@ -414,6 +447,20 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if constexpr (MODE == 2) xn[ch] = frag(nextoff, ch);
                     __builtin_amdgcn_sched_barrier(0);
                     a = nx;
+                    if constexpr (TAIL) a2 = nx2;
+                }
+                if constexpr (TAIL) {
+                    // rows 0..3 belong to the registers of half-wave 0, rows 4..7 to those of half-wave 1
+                    const float4 hv = *reinterpret_cast<const float4 *>(hs + tail_row0 + 4 * half);
+                    const float hq[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float lo = te[r] + to[r], hi = t2[r];
+                        const float lo_o = __shfl_xor(lo, 32, 64), hi_o = __shfl_xor(hi, 32, 64);
+                        acc[r] = (half ? hi + hi_o : lo + lo_o) + hq[r];
+                    }
+#pragma unroll
+                    for (int r = 4; r < 16; ++r) acc[r] = PAD_SCORE;
                 }
                 if constexpr (INS) {
                     const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2);
@@ -440,28 +487,43 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 // rows 0..31 of this block; meanwhile the scores of rows 32..63 of the previous block are inserted
                 if (cb == 0) {
-                    if (PRE && refill) half_block(M2(), std::false_type(), acc0, w0row, acc1, -1, cb);
-                    else if (more) half_block(M1(), std::false_type(), acc0, w0row, acc1, -1, cb);
-                    else half_block(M0(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    if (PRE && refill) half_block(M2(), std::false_type(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    else if (more) half_block(M1(), std::false_type(), std::false_type(), acc0, w0row, acc1, -1, cb);
+                    else half_block(M0(), std::false_type(), std::false_type(), acc0, w0row, acc1, -1, cb);
                 } else {
-                    if (more) half_block(M1(), std::true_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
-                    else half_block(M0(), std::true_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
+                    if (more) half_block(M1(), std::true_type(), std::false_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
+                    else half_block(M0(), std::true_type(), std::false_type(), acc0, w0row, acc1, 2 * cb - 1, cb);
                 }
+                bool tail_done = false;
+                if constexpr (TAILOK) {
+                    if (tail_groups > 0 && cb + 1 == g.nblocks) {
+                        const float *wtail = Wc + (32 + (lane & 3)) * DP + 4 * half;
+                        if (lastb) half_block(M2(), std::true_type(), std::true_type(), acc1, wtail, acc0, 2 * cb, cb);
+                        else half_block(M0(), std::true_type(), std::true_type(), acc1, wtail, acc0, 2 * cb, cb);
+                        tail_done = true;
+                    }
+                }
+                if (!tail_done) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const float4 h1 = hp[8 + 2 * q];
                     acc1[4 * q + 0] = h1.x; acc1[4 * q + 1] = h1.y; acc1[4 * q + 2] = h1.z; acc1[4 * q + 3] = h1.w;
                 }
                 // rows 32..63; meanwhile the scores of rows 0..31 are inserted
-                if (lastb) half_block(M2(), std::true_type(), acc1, w1row, acc0, 2 * cb, cb);
-                else half_block(M0(), std::true_type(), acc1, w1row, acc0, 2 * cb, cb);
+                if (lastb) half_block(M2(), std::true_type(), std::false_type(), acc1, w1row, acc0, 2 * cb, cb);
+                else half_block(M0(), std::true_type(), std::false_type(), acc1, w1row, acc0, 2 * cb, cb);
+                }
                 if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
             }
             {
                 // the last half-block's scores
                 const int o1 = __float_as_int(top.v1), o2 = __float_as_int(top.v2);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], r), big);
+                for (int r = 0; r < 4; ++r) top3_insert_value(top, tag_low5(acc1[r], r), big);
+                if (tail_groups == 0) {          // (4x4 tiles: the other registers hold padding)
+#pragma unroll
+                    for (int r = 4; r < 16; ++r) top3_insert_value(top, tag_low5(acc1[r], r), big);
+                }
                 const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2), tg = 2 * g.nblocks - 1;
                 const int nb2 = (n2 == o2) ? top.i2 : ((n2 == o1) ? top.i1 : tg);
                 top.i1 = (n1 != o1) ? tg : top.i1;
@@ -686,7 +748,59 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int NR = g.nr;
         const int spw = ((b + 63) / 64 + NR - 1) / NR * 64;
         const int n_lo = min(b, wave * spw), n_hi = wave < NR ? min(b, n_lo + spw) : n_lo;
-        if constexpr (FS) {
+        if constexpr (SS) {
+            // Second pass over the mini-batch, in memory order (whole cache lines, many loads in flight, no sort): the
+            // state rows in LDS are not needed any more, the fixed-point sums take their place.  A thread takes every
+            // MF_THREADS-th group of four columns; the four sums of a group lie DP8/4 apart, so that neighbouring lanes
+            // (neighbouring groups of one sample row) add to neighbouring addresses.
+            constexpr int SU = 8, Q4 = DP8 / 4;
+            const int nf4 = b * (d >> 2);
+            const float4 *x4 = reinterpret_cast<const float4 *>(xb);
+            const int dq = (4 * MF_THREADS) / d, dr = (4 * MF_THREADS) - dq * d;      // a stride of MF_THREADS groups in (rows, columns)
+            int n = (4 * tid) / d, j = 4 * tid - n * d;
+            auto fetch = [&](float4(&v)[SU], int f0) {
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int f = f0 + u * MF_THREADS;
+                    v[u] = x4[f < nf4 ? f : 0];
+                }
+            };
+            auto add = [&](const float4(&v)[SU], int f0) {
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    if (f0 + u * MF_THREADS < nf4) {
+                        const int c = idx[n];
+                        const float4 s4 = *reinterpret_cast<const float4 *>(colscale + j);
+                        int *cell = fxsum + c * DP8 + (j >> 2);
+                        atomicAdd(cell, __float2int_rn(v[u].x * s4.x));
+                        atomicAdd(cell + Q4, __float2int_rn(v[u].y * s4.y));
+                        atomicAdd(cell + 2 * Q4, __float2int_rn(v[u].z * s4.z));
+                        atomicAdd(cell + 3 * Q4, __float2int_rn(v[u].w * s4.w));
+                        if (j == 0) atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);
+                    }
+                    n += dq; j += dr;
+                    if (j >= d) { j -= d; ++n; }
+                }
+            };
+            // two sets of SU loads take turns: one is in flight while the other is added
+            float4 va[SU], vb[SU];
+            fetch(va, tid);
+            __syncthreads();                                   // every wave is through with the state rows; idx complete
+            for (int e = tid; e < k * DP8; e += MF_THREADS) fxsum[e] = 0;
+            for (int e = tid; e < g.ns; e += MF_THREADS) cursor[e] = 0;
+            __syncthreads();
+            for (int f0 = tid; f0 < nf4; f0 += 2 * SU * MF_THREADS) {
+                fetch(vb, f0 + SU * MF_THREADS);
+                __builtin_amdgcn_sched_barrier(0);
+                add(va, f0);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(va, f0 + 2 * SU * MF_THREADS);
+                __builtin_amdgcn_sched_barrier(0);
+                add(vb, f0 + SU * MF_THREADS);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if constexpr (FS || SS) {
             // The sums and the counts per slot are complete once every wave is here.  The row passes below take the
             // count of a centroid from the list starts: an exclusive prefix over the slots (one wave), and the
             // fixed-point sums go to the scratch rows in fp32 (exact integers times a power of two).
@@ -710,7 +824,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int e = tid; e < k * (DP8 / 4); e += MF_THREADS) {
                 const int c = e / (DP8 / 4), j = 4 * (e - c * (DP8 / 4));
                 if (j < d) {
-                    const int4 v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
+                    int4 v;
+                    if constexpr (SS) {
+                        const int *cell = fxsum + c * DP8 + (j >> 2);
+                        v = make_int4(cell[0], cell[DP8 / 4], cell[2 * (DP8 / 4)], cell[3 * (DP8 / 4)]);
+                    } else {
+                        v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
+                    }
                     const float4 inv = *reinterpret_cast<const float4 *>(colscale + DP8 + j);
                     *reinterpret_cast<float4 *>(gsc + (size_t)c * d + j) =
                         make_float4((float)v.x * inv.x, (float)v.y * inv.y, (float)v.z * inv.z, (float)v.w * inv.w);
@@ -788,7 +908,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __syncthreads();
         // the message was written by another workgroup, maybe on another XCD, during this launch
         if (sync && merge_point) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        if constexpr (!FS) {
+        if constexpr (!FS && !SS) {
         // placement: a wave walks its samples in order
         int nbits = 1;
         while ((1 << nbits) < k) ++nbits;
@@ -1344,7 +1464,7 @@ constexpr size_t MF_LDS_BUDGET = 150 * 1024;
 template <int NCH, bool RES, int NWV, int FSM = 0>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
-    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV, FSM == 1).bytes;
+    const size_t lds = mfma_geom(p.k, p.b, NCH, RES, NWV, FSM == 1 ? 1 : (FSM == 3 ? 2 : 0)).bytes;
     const void *kern = (const void *)mfma_steps_kernel<NCH, RES, NWV, FSM>;
     hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -1379,7 +1499,7 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
     // the same shape with sort and gather, but 6.1 ms for two four-wave workgroups per CU with sort and gather, whose
     // memory phases hide behind each other's matrix work; so it is not the default.  tune bit 5 asks for it.
     if constexpr (NCH <= 13) {             // (d = 128 would spill registers with two sets of fragments)
-        const bool fits = mfma_geom(p.k, p.b, NCH, true, 8, true).bytes <= MF_LDS_BUDGET;
+        const bool fits = mfma_geom(p.k, p.b, NCH, true, 8, 1).bytes <= MF_LDS_BUDGET;
         if (fits && (p.tune & 32)) {
             if (persistent && !(p.tune & 8)) return hipErrorNotSupported;      // one workgroup per CU: one launch per round
             return launch_variant<NCH, true, 8, 1>(p, t0, t1, xnorm2max, s, persistent);
@@ -1389,6 +1509,7 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
         // the next tile's samples go to a second set of registers a whole tile ahead (1.2 % on the k = d = 100 workload;
         // d = 128 has no registers for it); tune bit 6 switches it off
         if constexpr (NCH <= 13) {
+            if (p.tune & 128) return launch_variant<NCH, true, 4, 3>(p, t0, t1, xnorm2max, s, persistent);
             if (!(p.tune & 64)) return launch_variant<NCH, true, 4, 2>(p, t0, t1, xnorm2max, s, persistent);
         }
         return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);

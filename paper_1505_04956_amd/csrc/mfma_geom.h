@@ -19,7 +19,9 @@ struct MfmaGeom {
     int nr;        // shares of the mini-batch in the counting sort (waves that count and place): a power of two <= nwv
     size_t off_h, off_cstart, off_cursor, off_idx, off_perm, off_flist, off_sums, off_scale, bytes;
 };
-ASGD_HD inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv, bool fused = false)
+// sums: 0 = none in LDS, 1 = fixed-point sums and column scales behind the lists (fused sums), 2 = column scales only (the
+// fixed-point sums take the place of the resident state once the assignments are done)
+ASGD_HD inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv, int sums = 0)
 {
     MfmaGeom g;
     const int DP = nch * 8 + 4;
@@ -38,10 +40,10 @@ ASGD_HD inline MfmaGeom mfma_geom(int k, int b, int nch, bool resident, int nwv,
     g.off_flist = o;        // resident variant: per-wave lists of samples to re-decide, 32 * ceil(b / (32 nwv)) each
     if (resident) o += (size_t)nwv * 32 * ((b + 32 * nwv - 1) / (32 * nwv)) * sizeof(unsigned short);
     o = (o + 15) / 16 * 16;
-    g.off_sums = o;         // fused sums: k rows of 8 * nch fixed-point sums, then scale and inverse scale per column
-    if (fused) o += (size_t)k * nch * 8 * sizeof(int);
+    g.off_sums = sums == 2 ? 0 : o;      // k rows of 8 * nch fixed-point sums, then scale and inverse scale per column
+    if (sums == 1) o += (size_t)k * nch * 8 * sizeof(int);
     g.off_scale = o;
-    if (fused) o += (size_t)2 * nch * 8 * sizeof(float);
+    if (sums != 0) o += (size_t)2 * nch * 8 * sizeof(float);
     g.bytes = (o + 15) / 16 * 16;
     return g;
 }

@@ -208,6 +208,8 @@ def test_wider_shapes_generic(B, oracle):
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "uniform10", "zipf1.1"),  # skewed cluster sizes, big and small ones in one gather
     (3, 16, 2, 500, 2, 5, 2 * 1000, "uniform10", "zipf1.1"),            # fewer centroids than half-waves
     (2048, 16, 2, 2304, 1, 3, 2 * 2304 * 2, "uniform10", "equal"),      # many centroids: the sort uses fewer shares than waves
+    (104, 40, 2, 512, 1, 5, 2 * 1024, "uniform10", "equal"),            # last 32 rows hold 8 centroids: two groups of 4x4 tiles
+    (37, 12, 3, 300, 2, 7, 3 * 900 + 2, "uniform10", "zipf1.1"),        # ... 5 centroids: the second group is partly padding
 ])
 def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights):
     X = make_data(N, d, k, seed=21, centres=centres, weights=weights)
@@ -220,16 +222,17 @@ def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights
     (33, 36, 5, 300, 3, 8, 5 * 1000 + 3),
     (70, 8, 3, 100, 2, 9, 3 * 450 + 2),
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5),
+    (38, 24, 3, 200, 2, 7, 3 * 200 * 3 + 1),
 ])
-@pytest.mark.parametrize("tune", [2, 66])
+@pytest.mark.parametrize("tune", [2, 66, 258])
 def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N, tune):
     # the variant with four waves per worker (two workers per CU), which large W selects by itself: the samples of the
     # next tile are fetched a whole tile ahead into a second set of registers; +64: into the same registers during the
-    # last block of a tile (same arithmetic, same order)
+    # last block of a tile (same arithmetic, same order); +256: no 4x4 tiles for a last half-block of at most 8 centroids
     X = make_data(N, d, k, seed=23)
     g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=tune)
     assert g.stats().kernel == 3
-    if tune != 2:
+    if tune == 66:
         plain = B.ASGD(k, d, W, b, 0.02, E=E, kernel=3, tune=2); plain.load_shards(to_dev(X)); plain.run_steps(steps)
         assert np.array_equal(g.get_state(), plain.get_state())
 
@@ -243,15 +246,17 @@ def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N, tune)
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "zipf1.1", 2, 1, 0.0),     # skewed cluster sizes: many lanes add to one row
     (40, 20, 12, 100, 2, 17, 12 * 1800 + 7, "equal", 2, 4, 0.0),         # with partial messages and two buffers
 ])
-def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weights, buffers, parts, drop):
-    """The variant that forms the gradient sums tile by tile in fixed point (no second read of the mini-batch), asked for
-    with its tune bit; against the oracle, and bit for bit against itself (run twice, run in
-    pieces) - integer sums do not depend on the order in which the waves get there."""
+@pytest.mark.parametrize("tune", [32, 130])
+def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weights, buffers, parts, drop, tune):
+    """The variants with gradient sums in fixed point, asked for with their tune bits: 32 forms them tile by tile (no
+    second read of the mini-batch), 2 + 128 (four waves) in a second pass over the mini-batch in memory order, in the LDS
+    the state rows no longer need; against the oracle, and bit for bit against itself (run twice, run in pieces) -
+    integer sums do not depend on the order in which the waves get there."""
     X = make_data(N, d, k, seed=29, weights=weights)
-    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=32, buffers=buffers, parts=parts, drop_rate=drop)
+    g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=tune, buffers=buffers, parts=parts, drop_rate=drop)
     assert g.stats().kernel == 3
     Xg = to_dev(X)
-    kw = dict(E=E, kernel=3, tune=32, buffers=buffers, parts=parts, drop_rate=drop)
+    kw = dict(E=E, kernel=3, tune=tune, buffers=buffers, parts=parts, drop_rate=drop)
     again = B.ASGD(k, d, W, b, 0.02, **kw); again.load_shards(Xg); again.run_steps(2); again.run_steps(steps - 2)
     assert np.array_equal(g.get_state(), again.get_state())
     assert np.array_equal(g.worker_counters(), again.worker_counters())
