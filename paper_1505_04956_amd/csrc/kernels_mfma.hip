@@ -272,8 +272,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             if (m > 0.0f && m < 1.0e30f) {
                 int q = 0;
                 (void)frexpf(m, &q);              // m = f * 2^q, f in [0.5, 1)
-                sc = ldexpf(1.0f, 30 - q);
-                inv = ldexpf(1.0f, q - 30);
+                int e = 30 - q;
+                if constexpr (SS) {               // ... and a single term stays below 2^22 (it is rounded in a float)
+                    int q1 = 0;
+                    (void)frexpf(p.xabsmax[j], &q1);
+                    e = min(e, 22 - q1);
+                }
+                sc = ldexpf(1.0f, e);
+                inv = ldexpf(1.0f, -e);
             }
             colscale[j] = sc;
             colscale[DP8 + j] = inv;
@@ -750,54 +756,71 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int n_lo = min(b, wave * spw), n_hi = wave < NR ? min(b, n_lo + spw) : n_lo;
         if constexpr (SS) {
             // Second pass over the mini-batch, in memory order (whole cache lines, many loads in flight, no sort): the
-            // state rows in LDS are not needed any more, the fixed-point sums take their place.  A thread takes every
-            // MF_THREADS-th group of four columns; the four sums of a group lie DP8/4 apart, so that neighbouring lanes
-            // (neighbouring groups of one sample row) add to neighbouring addresses.
+            // state rows in LDS are not needed any more, the fixed-point sums take their place.  The workgroup sweeps
+            // R = threads / (d / 4) whole rows at a time, a thread keeps its group of four columns for the whole pass
+            // (its scales stay in registers; threads past R rows idle), and the four sums of a group lie DP8/4 apart,
+            // so that neighbouring lanes add to neighbouring addresses.  A term x * scale is rounded to an integer by
+            // adding 1.5 * 2^23 in the same fused multiply-add; the BIT PATTERN of that float is what is added: it is
+            // 0x4B400000 plus the integer, and the count of the centroid times that constant is taken off when the
+            // sums are read (all modulo 2^32).
             constexpr int SU = 8, Q4 = DP8 / 4;
-            const int nf4 = b * (d >> 2);
-            const float4 *x4 = reinterpret_cast<const float4 *>(xb);
-            const int dq = (4 * MF_THREADS) / d, dr = (4 * MF_THREADS) - dq * d;      // a stride of MF_THREADS groups in (rows, columns)
-            int n = (4 * tid) / d, j = 4 * tid - n * d;
-            auto fetch = [&](float4(&v)[SU], int f0) {
+            const int c4n = d >> 2;                              // float4 per row
+            const int R = MF_THREADS / c4n;
+            const int myr = tid / c4n, myc = tid - myr * c4n;
+            const bool act = myr < R;
+            const float4 *xq = reinterpret_cast<const float4 *>(xb) + tid;      // sweep s: + s * R * c4n
+            const unsigned sweep4 = (unsigned)(R * c4n);
+            const float4 s4 = *reinterpret_cast<const float4 *>(colscale + (act ? 4 * myc : 0));
+            int *cell0 = fxsum + myc;
+            const int nfull = b / R;                             // sweeps with R valid rows
+            const int nsweep = (b + R - 1) / R;
+            auto fetch = [&](float4(&v)[SU], int s0) {
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int f = f0 + u * MF_THREADS;
-                    v[u] = x4[f < nf4 ? f : 0];
+                    const int sw = s0 + u;
+                    v[u] = xq[(sw * R + myr < b ? (unsigned)sw : 0u) * sweep4];
                 }
             };
-            auto add = [&](const float4(&v)[SU], int f0) {
+            auto add = [&](auto guard, const float4(&v)[SU], int s0) {
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    if (f0 + u * MF_THREADS < nf4) {
-                        const int c = idx[n];
-                        const float4 s4 = *reinterpret_cast<const float4 *>(colscale + j);
-                        int *cell = fxsum + c * DP8 + (j >> 2);
-                        atomicAdd(cell, __float2int_rn(v[u].x * s4.x));
-                        atomicAdd(cell + Q4, __float2int_rn(v[u].y * s4.y));
-                        atomicAdd(cell + 2 * Q4, __float2int_rn(v[u].z * s4.z));
-                        atomicAdd(cell + 3 * Q4, __float2int_rn(v[u].w * s4.w));
-                        if (j == 0) atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);
+                    const int n = (s0 + u) * R + myr;
+                    if (!decltype(guard)::value || n < b) {
+                        int *cell = cell0 + (int)idx[n] * DP8;
+                        atomicAdd(cell, __float_as_int(fmaf(v[u].x, s4.x, 12582912.0f)));
+                        atomicAdd(cell + Q4, __float_as_int(fmaf(v[u].y, s4.y, 12582912.0f)));
+                        atomicAdd(cell + 2 * Q4, __float_as_int(fmaf(v[u].z, s4.z, 12582912.0f)));
+                        atomicAdd(cell + 3 * Q4, __float_as_int(fmaf(v[u].w, s4.w, 12582912.0f)));
                     }
-                    n += dq; j += dr;
-                    if (j >= d) { j -= d; ++n; }
                 }
             };
             // two sets of SU loads take turns: one is in flight while the other is added
             float4 va[SU], vb[SU];
-            fetch(va, tid);
+            if (act) fetch(va, 0);
             __syncthreads();                                   // every wave is through with the state rows; idx complete
             for (int e = tid; e < k * DP8; e += MF_THREADS) fxsum[e] = 0;
             for (int e = tid; e < g.ns; e += MF_THREADS) cursor[e] = 0;
             __syncthreads();
-            for (int f0 = tid; f0 < nf4; f0 += 2 * SU * MF_THREADS) {
-                fetch(vb, f0 + SU * MF_THREADS);
-                __builtin_amdgcn_sched_barrier(0);
-                add(va, f0);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch(va, f0 + 2 * SU * MF_THREADS);
-                __builtin_amdgcn_sched_barrier(0);
-                add(vb, f0 + SU * MF_THREADS);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int n = tid; n < b; n += MF_THREADS) {          // samples per centroid slot
+                const int c = idx[n];
+                atomicAdd(&cursor[(c % NWV) * g.kq + c / NWV], 1);
+            }
+            if (act) {
+                int s0 = 0;
+                for (; s0 + 2 * SU <= nfull; s0 += 2 * SU) {
+                    fetch(vb, s0 + SU);
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(std::false_type(), va, s0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(va, s0 + 2 * SU);
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(std::false_type(), vb, s0 + SU);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                for (; s0 < nsweep; s0 += SU) {
+                    add(std::true_type(), va, s0);
+                    if (s0 + SU < nsweep) fetch(va, s0 + SU);
+                }
             }
         }
         if constexpr (FS || SS) {
@@ -827,7 +850,9 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     int4 v;
                     if constexpr (SS) {
                         const int *cell = fxsum + c * DP8 + (j >> 2);
-                        v = make_int4(cell[0], cell[DP8 / 4], cell[2 * (DP8 / 4)], cell[3 * (DP8 / 4)]);
+                        const unsigned bias = (unsigned)cursor[(c % NWV) * g.kq + c / NWV] * 0x4B400000u;      // modulo 2^32, like the sums
+                        v = make_int4((int)((unsigned)cell[0] - bias), (int)((unsigned)cell[DP8 / 4] - bias),
+                                      (int)((unsigned)cell[2 * (DP8 / 4)] - bias), (int)((unsigned)cell[3 * (DP8 / 4)] - bias));
                     } else {
                         v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
                     }
@@ -1506,10 +1531,12 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
         }
     }
     if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2))) {
-        // the next tile's samples go to a second set of registers a whole tile ahead (1.2 % on the k = d = 100 workload;
-        // d = 128 has no registers for it); tune bit 6 switches it off
+        // d <= 104 (d = 128 has no registers for it): the next tile's samples go to a second set of registers a whole
+        // tile ahead, and the gradient sums are formed in a second pass over the mini-batch in memory order (on the
+        // k = d = 100 workload 6.07 -> 5.99 -> 5.6 ms per epoch).  tune bit 7: sort and gather instead of the second
+        // pass; bit 6: neither
         if constexpr (NCH <= 13) {
-            if (p.tune & 128) return launch_variant<NCH, true, 4, 3>(p, t0, t1, xnorm2max, s, persistent);
+            if (!(p.tune & (64 | 128))) return launch_variant<NCH, true, 4, 3>(p, t0, t1, xnorm2max, s, persistent);
             if (!(p.tune & 64)) return launch_variant<NCH, true, 4, 2>(p, t0, t1, xnorm2max, s, persistent);
         }
         return launch_variant<NCH, true, 4>(p, t0, t1, xnorm2max, s, persistent);

@@ -224,16 +224,18 @@ def test_matrix_core_kernel(B, oracle, k, d, W, b, E, steps, N, centres, weights
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5),
     (38, 24, 3, 200, 2, 7, 3 * 200 * 3 + 1),
 ])
-@pytest.mark.parametrize("tune", [2, 66, 258])
+@pytest.mark.parametrize("tune", [2, 66, 130, 258])
 def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N, tune):
     # the variant with four waves per worker (two workers per CU), which large W selects by itself: the samples of the
-    # next tile are fetched a whole tile ahead into a second set of registers; +64: into the same registers during the
-    # last block of a tile (same arithmetic, same order); +256: no 4x4 tiles for a last half-block of at most 8 centroids
+    # next tile are fetched a whole tile ahead into a second set of registers and the gradient sums are formed in fixed
+    # point in a second pass over the mini-batch; +128: counting sort and gather instead (fp32 sums in sample order);
+    # +64: also one set of registers (same arithmetic and order as +128); +256: no 4x4 tiles for a last half-block of
+    # at most 8 centroids
     X = make_data(N, d, k, seed=23)
     g, o = run_both(B, oracle, X, k, W, b, 0.02, E, steps, kernel=3, tune=tune)
     assert g.stats().kernel == 3
     if tune == 66:
-        plain = B.ASGD(k, d, W, b, 0.02, E=E, kernel=3, tune=2); plain.load_shards(to_dev(X)); plain.run_steps(steps)
+        plain = B.ASGD(k, d, W, b, 0.02, E=E, kernel=3, tune=130); plain.load_shards(to_dev(X)); plain.run_steps(steps)
         assert np.array_equal(g.get_state(), plain.get_state())
 
 
@@ -246,10 +248,10 @@ def test_matrix_core_kernel_four_waves(B, oracle, k, d, W, b, E, steps, N, tune)
     (64, 32, 3, 1024, 2, 6, 3 * 1024 * 2 + 5, "zipf1.1", 2, 1, 0.0),     # skewed cluster sizes: many lanes add to one row
     (40, 20, 12, 100, 2, 17, 12 * 1800 + 7, "equal", 2, 4, 0.0),         # with partial messages and two buffers
 ])
-@pytest.mark.parametrize("tune", [32, 130])
+@pytest.mark.parametrize("tune", [32, 2])
 def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weights, buffers, parts, drop, tune):
     """The variants with gradient sums in fixed point, asked for with their tune bits: 32 forms them tile by tile (no
-    second read of the mini-batch), 2 + 128 (four waves) in a second pass over the mini-batch in memory order, in the LDS
+    second read of the mini-batch), 2 (four waves) in a second pass over the mini-batch in memory order, in the LDS
     the state rows no longer need; against the oracle, and bit for bit against itself (run twice, run in pieces) -
     integer sums do not depend on the order in which the waves get there."""
     X = make_data(N, d, k, seed=29, weights=weights)
