@@ -461,12 +461,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     const float hq[4] = {hv.x, hv.y, hv.z, hv.w};
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float lo = te[r] + to[r], hi = t2[r];
-                        const float lo_o = __shfl_xor(lo, 32, 64), hi_o = __shfl_xor(hi, 32, 64);
-                        acc[r] = (half ? hi + hi_o : lo + lo_o) + hq[r];
+                        // v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
+                        // second: afterwards the lower half-wave holds both halves' sums of rows 0..3, the upper
+                        // half-wave those of rows 4..7
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(te[r] + to[r]), __float_as_uint(t2[r]), false, false);
+                        acc[r] = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) + hq[r];
                     }
-#pragma unroll
-                    for (int r = 4; r < 16; ++r) acc[r] = PAD_SCORE;
+                    // (registers 4..15 are not looked at after a half-block of this kind)
                 }
                 if constexpr (INS) {
                     const int n1 = __float_as_int(top.v1), n2 = __float_as_int(top.v2);
@@ -543,8 +544,12 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             // merge the two half-waves (same sample, other centroid rows)
             {
-                const float pv1 = __shfl_xor(top.v1, 32, 64), pv2 = __shfl_xor(top.v2, 32, 64), pv3 = __shfl_xor(top.v3, 32, 64);
-                const int pi1 = __shfl_xor(top.i1, 32, 64), pi2 = __shfl_xor(top.i2, 32, 64);
+                // only the lower half-wave's result is used below: it gets the upper one's values (second result of
+                // v_permlane32_swap of a register with itself), the upper half-wave sees its own again
+                auto upper = [](unsigned v) -> unsigned { return __builtin_amdgcn_permlane32_swap(v, v, false, false)[1]; };
+                const float pv1 = __uint_as_float(upper(__float_as_uint(top.v1))), pv2 = __uint_as_float(upper(__float_as_uint(top.v2))),
+                            pv3 = __uint_as_float(upper(__float_as_uint(top.v3)));
+                const int pi1 = (int)upper((unsigned)top.i1), pi2 = (int)upper((unsigned)top.i2);
                 top3_insert(top, pv1, pi1);
                 top3_insert(top, pv2, pi2);
                 top.v3 = fmaxf(top.v3, pv3);
@@ -823,7 +828,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             }
         }
-        if constexpr (FS || SS) {
+        if constexpr (FS) {
             // The sums and the counts per slot are complete once every wave is here.  The row passes below take the
             // count of a centroid from the list starts: an exclusive prefix over the slots (one wave), and the
             // fixed-point sums go to the scratch rows in fp32 (exact integers times a power of two).
@@ -847,21 +852,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int e = tid; e < k * (DP8 / 4); e += MF_THREADS) {
                 const int c = e / (DP8 / 4), j = 4 * (e - c * (DP8 / 4));
                 if (j < d) {
-                    int4 v;
-                    if constexpr (SS) {
-                        const int *cell = fxsum + c * DP8 + (j >> 2);
-                        const unsigned bias = (unsigned)cursor[(c % NWV) * g.kq + c / NWV] * 0x4B400000u;      // modulo 2^32, like the sums
-                        v = make_int4((int)((unsigned)cell[0] - bias), (int)((unsigned)cell[DP8 / 4] - bias),
-                                      (int)((unsigned)cell[2 * (DP8 / 4)] - bias), (int)((unsigned)cell[3 * (DP8 / 4)] - bias));
-                    } else {
-                        v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
-                    }
+                    const int4 v = *reinterpret_cast<const int4 *>(fxsum + c * DP8 + j);
                     const float4 inv = *reinterpret_cast<const float4 *>(colscale + DP8 + j);
                     *reinterpret_cast<float4 *>(gsc + (size_t)c * d + j) =
                         make_float4((float)v.x * inv.x, (float)v.y * inv.y, (float)v.z * inv.z, (float)v.w * inv.w);
                 }
             }
-        } else {
+        } else if constexpr (!SS) {
         for (int s = tid; s < g.ns * NR; s += MF_THREADS) cursor[s] = 0;
         if (tid == 0) s_next_item = 0;
         __syncthreads();                                   // also: idx complete
@@ -1070,6 +1067,26 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         __threadfence_block();
         __syncthreads();
 
+        // Samples and sum of the samples of a centroid, for the row passes below (lane l owns columns l and l + 64).
+        // Streamed sums: straight from the fixed-point cells in LDS - the count times the rounding constant comes off
+        // (modulo 2^32, like the additions), then the column's inverse scale; no list starts are formed.
+        float invs[NJ];
+        int cellofs[NJ];
+#pragma unroll
+        for (int jq = 0; jq < NJ; ++jq) {
+            const int j = lane + 64 * jq, jc = j < d ? j : 0;
+            invs[jq] = SS ? colscale[DP8 + jc] : 0.0f;
+            cellofs[jq] = (jc & 3) * (DP8 / 4) + (jc >> 2);
+        }
+        auto count_of = [&](int c) -> int {
+            const int sl = (c % NWV) * g.kq + c / NWV;
+            if constexpr (SS) return cursor[sl];
+            else return cstart[sl + 1] - cstart[sl];
+        };
+        auto sum_of = [&](int c, int cn, int jq, unsigned e) -> float {
+            if constexpr (SS) return (float)(int)((unsigned)fxsum[c * DP8 + cellofs[jq]] - (unsigned)cn * 0x4B400000u) * invs[jq];
+            else return gsc[e];
+        };
         const int has_mask = s_has_ext;      // uniform over the workgroup
         const float inv_b = 1.0f / (float)b;
         const float *ext0 = p.slot + exchange_buffer(rpar, p.nb, 0, p.W, i) * kd;          // buffer n: + n * W * kd
@@ -1083,15 +1100,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             int nz = 0, acc = 0, near = 0;
             wn2max = 0.0f;
             for (int c = wave; c < k; c += MF_WAVES) {
-                const int sl = (c % NWV) * g.kq + c / NWV;
-                const int cn = cstart[sl + 1] - cstart[sl];
+                const int cn = count_of(c);
                 float w[NJ], gq[NJ], wesum[NJ];
 #pragma unroll
                 for (int jq = 0; jq < NJ; ++jq) {
                     const int j = lane + 64 * jq;
                     const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
                     w[jq] = wst[e];
-                    const float sums = cn > 0 ? gsc[e] : 0.0f;
+                    const float sums = cn > 0 ? sum_of(c, cn, jq, e) : 0.0f;
                     gq[jq] = ((float)cn * w[jq] - sums) * inv_b;            // descent gradient of Eq. 9
                     wesum[jq] = 0.0f;
                 }
@@ -1169,13 +1185,12 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                 for (int q = 0; q < RB; ++q) {
                     const int c = c0 + q < k ? c0 + q : k - 1;
-                    const int s = (c % NWV) * g.kq + c / NWV;
-                    cn[q] = cstart[s + 1] - cstart[s];
+                    cn[q] = count_of(c);
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
                         const int j = lane + 64 * jq;
                         const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
-                        w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = ext[e];
+                        w[q][jq] = wst[e]; sm[q][jq] = sum_of(c, cn[q], jq, e); we[q][jq] = ext[e];
                     }
                 }
 #pragma unroll
@@ -1218,7 +1233,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int first = delta ? __builtin_ctz(delta_mask) : 0;
             const int more_mask = delta_mask & (delta_mask - 1);             // accepted buffers after the first
             const float inv = 1.0f / (float)(__builtin_popcount(delta_mask) + 1);
-            const float *extp = delta ? ext0 + first * ext_stride : wst;    // read something valid when there is nothing to merge
+            const float *extp = ext0 + first * ext_stride;                  // read only when a message was accepted
             wn2max = 0.0f;
             for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
                 float w[RB][NJ], sm[RB][NJ], we[RB][NJ], s2[RB];
@@ -1226,13 +1241,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                 for (int q = 0; q < RB; ++q) {
                     const int c = c0 + q < k ? c0 + q : k - 1;
-                    const int s = (c % NWV) * g.kq + c / NWV;
-                    cn[q] = cstart[s + 1] - cstart[s];
+                    cn[q] = count_of(c);
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
                         const int j = lane + 64 * jq;
                         const unsigned e = (unsigned)c * (unsigned)d + (unsigned)(j < d ? j : 0);
-                        w[q][jq] = wst[e]; sm[q][jq] = gsc[e]; we[q][jq] = extp[e];
+                        w[q][jq] = wst[e]; sm[q][jq] = sum_of(c, cn[q], jq, e);
+                        we[q][jq] = delta ? extp[e] : 0.0f;
                         for (int m = more_mask; m; m &= m - 1) we[q][jq] += ext0[__builtin_ctz(m) * ext_stride + e];
                     }
                 }
