@@ -803,7 +803,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             float4 va[SU], vb[SU];
             if (act) fetch(va, 0);
             __syncthreads();                                   // every wave is through with the state rows; idx complete
-            for (int e = tid; e < k * DP8; e += MF_THREADS) fxsum[e] = 0;
+            for (int e = tid; e < k * (DP8 / 4); e += MF_THREADS) reinterpret_cast<int4 *>(fxsum)[e] = make_int4(0, 0, 0, 0);
             for (int e = tid; e < g.ns; e += MF_THREADS) cursor[e] = 0;
             __syncthreads();
             for (int n = tid; n < b; n += MF_THREADS) {          // samples per centroid slot
