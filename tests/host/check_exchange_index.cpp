@@ -75,10 +75,12 @@ int main(int argc, char **argv)
     // ---- LDS layout of the matrix-core kernel for this shape, all the forms it is launched in ----
     if (d % 4 == 0 && d <= 128 && k >= 2 && b <= 65535) {
         const int nch = mfma_chunks(d), DP = nch * 8 + 4;
-        for (int variant = 0; variant < 4; ++variant) {
-            const bool resident = variant != 0, fused = variant == 3;
-            const int nwv = variant == 1 ? 4 : 8;
-            const MfmaGeom g = mfma_geom(k, b, nch, resident, nwv, fused);
+        for (int variant = 0; variant < 5; ++variant) {
+            // 0: state streamed; 1: resident, four waves; 2: resident, eight waves; 3: fused sums; 4: four waves with
+            // the fixed-point sums of the second pass in place of the state rows
+            const bool resident = variant != 0, fused = variant == 3, streamed_sums = variant == 4;
+            const int nwv = (variant == 1 || variant == 4) ? 4 : 8;
+            const MfmaGeom g = mfma_geom(k, b, nch, resident, nwv, fused ? 1 : (streamed_sums ? 2 : 0));
             REQUIRE(g.kpad >= k && g.kpad % MFMA_WB == 0 && g.nblocks * MFMA_WB == g.kpad, "kpad %d", g.kpad);
             REQUIRE(nch * 8 >= d, "chunks %d for d = %d", nch, d);
             // regions in order, each large enough for what the kernel keeps there
@@ -90,9 +92,14 @@ int main(int argc, char **argv)
             REQUIRE(g.off_perm + (size_t)b * sizeof(unsigned short) <= g.off_flist, "permutation");
             const int TM = 32 * nwv;
             const size_t flist = resident ? (size_t)nwv * 32 * ((b + TM - 1) / TM) * sizeof(unsigned short) : 0;
-            REQUIRE(g.off_flist + flist <= g.off_sums, "lists of samples to re-decide");
-            REQUIRE(g.off_sums + (fused ? (size_t)k * nch * 8 * sizeof(int) : 0) <= g.off_scale, "fixed-point sums");
-            REQUIRE(g.off_scale + (fused ? (size_t)2 * nch * 8 * sizeof(float) : 0) <= g.bytes, "scales");
+            if (streamed_sums) {
+                REQUIRE(g.off_sums == 0 && (size_t)k * nch * 8 * sizeof(int) <= g.off_h, "fixed-point sums in place of the state rows");
+                REQUIRE(g.off_flist + flist <= g.off_scale, "lists of samples to re-decide");
+            } else {
+                REQUIRE(g.off_flist + flist <= g.off_sums, "lists of samples to re-decide");
+                REQUIRE(g.off_sums + (fused ? (size_t)k * nch * 8 * sizeof(int) : 0) <= g.off_scale, "fixed-point sums");
+            }
+            REQUIRE(g.off_scale + ((fused || streamed_sums) ? (size_t)2 * nch * 8 * sizeof(float) : 0) <= g.bytes, "scales");
             REQUIRE(g.off_h % 16 == 0 && g.off_sums % 16 == 0 && g.off_scale % 16 == 0 && g.off_cstart % 4 == 0, "alignment");
             // slots of the counting sort: a bijection of the centroids into [0, ns), counters inside their region
             REQUIRE(g.nr >= 1 && g.nr <= nwv && (g.nr & (g.nr - 1)) == 0, "shares %d", g.nr);
