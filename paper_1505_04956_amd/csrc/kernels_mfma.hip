@@ -1335,7 +1335,9 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
 // maximum per sample is kept, with the place it came from in its low mantissa bits, and the distance to that
 // centroid is then formed directly as sum_j (x_j - w_cj)^2 (no cancellation).  A workgroup (8 waves) walks tiles of 256 samples with a fixed stride, every lane pair adds its samples
 // in fp64 in a fixed order, the partials are added in a fixed order: the result does not depend on scheduling.
-template <int NCH>
+// RES: the whole padded state fits LDS and is staged once per launch (no barriers in the loop over the samples); then a
+// last half-block of at most eight centroids goes to 4x4 matrix tiles as in the step kernel.
+template <int NCH, bool RES>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void quant_error_mfma_kernel(
     const float *__restrict__ x, long long N, int k, int d, const float *__restrict__ w, double *partials)
 {
@@ -1346,8 +1348,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ double red[NWV];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int kpad = (k + WB - 1) / WB * WB, nblocks = kpad / WB;
-    float *Ws = reinterpret_cast<float *>(smem_raw);                      // 2 x WB x DP
-    float *hs = Ws + 2 * WB * DP;                                         // kpad
+    float *Ws = reinterpret_cast<float *>(smem_raw);                      // (RES ? kpad : 2 x WB) x DP
+    float *hs = Ws + (size_t)(RES ? kpad : 2 * WB) * DP;                  // kpad
+    constexpr bool TAILOK = RES && NCH <= 13;
+    const int tail_groups = (TAILOK && (k & 31) >= 1 && (k & 31) <= 8 && ((k >> 5) & 1)) ? ((k & 31) + 3) / 4 : 0;
+    const int tail_row0 = k & ~31;
 
     for (int c0 = wave * RB; c0 < kpad; c0 += NWV * RB) {                 // h_c = -|w_c|^2 / 2
 #pragma unroll
@@ -1387,6 +1392,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     };
 
+    if constexpr (RES) {
+        float4 st[NST];
+        for (int cb = 0; cb < nblocks; ++cb) {
+            fetch_block(st, cb);
+            store_block(st, Ws + (size_t)cb * WB * DP);
+        }
+        __syncthreads();                 // state rows and hs complete
+    }
     double sum = 0.0;
     for (long long tile0 = (long long)blockIdx.x * TM; tile0 < N; tile0 += (long long)gridDim.x * TM) {
         const long long n = tile0 + wave * 32 + l32;
@@ -1399,15 +1412,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             xf[ch] = *reinterpret_cast<const float4 *>(row + (col < collim ? col : collim));
         }
         float4 st[NST];
-        __syncthreads();                 // nobody still reads the stage (and hs is complete)
-        fetch_block(st, 0);
-        store_block(st, Ws);
+        if constexpr (!RES) {
+            __syncthreads();             // nobody still reads the stage (and hs is complete)
+            fetch_block(st, 0);
+            store_block(st, Ws);
+        }
         float best = -INFINITY;         // largest score so far, the number of its accumulator register in its low 5 bits
         int bestcb = 0;                 // ... and the block it came from
         for (int cb = 0; cb < nblocks; ++cb) {
-            __syncthreads();
-            const float *Wc = Ws + (cb & 1) * WB * DP;
-            const bool more = cb + 1 < nblocks;
+            if constexpr (!RES) __syncthreads();
+            const float *Wc = Ws + (size_t)(RES ? cb : (cb & 1)) * WB * DP;
+            const bool more = !RES && cb + 1 < nblocks;
+            const bool tailb = TAILOK && tail_groups > 0 && cb + 1 == nblocks;
             floatx16 acc0, acc1;
             {
                 const float4 *hp = reinterpret_cast<const float4 *>(hs + cb * WB + 4 * half);
@@ -1420,27 +1436,77 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             const float *w0row = Wc + l32 * DP + 4 * half;
             const float *w1row = Wc + (32 + l32) * DP + 4 * half;
-            float4 a0 = *reinterpret_cast<const float4 *>(w0row);
-            float4 a1 = *reinterpret_cast<const float4 *>(w1row);
+            if (tailb) {
+                if constexpr (TAILOK) {
+                    // rows 32 + (lane mod 4) (+ 4): a column of four state rows per block of four lanes
+                    const float *wt = Wc + (32 + (lane & 3)) * DP + 4 * half;
+                    floatx4 te = {0.0f, 0.0f, 0.0f, 0.0f}, to = te, t2 = te;
+                    float4 a0 = *reinterpret_cast<const float4 *>(w0row);
+                    float4 at = *reinterpret_cast<const float4 *>(wt);
+                    float4 a2 = at;
+                    if (tail_groups > 1) a2 = *reinterpret_cast<const float4 *>(wt + 4 * DP);
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) {
-                float4 n0 = a0, n1 = a1;
-                if (ch + 1 < NCH) {
-                    n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
-                    n1 = *reinterpret_cast<const float4 *>(w1row + (ch + 1) * 8);
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        float4 n0 = a0, nt = at, n2 = a2;
+                        if (ch + 1 < NCH) {
+                            n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
+                            nt = *reinterpret_cast<const float4 *>(wt + (ch + 1) * 8);
+                            if (tail_groups > 1) n2 = *reinterpret_cast<const float4 *>(wt + 4 * DP + (ch + 1) * 8);
+                        }
+                        const float4 xv = xf[ch];
+                        floatx4 &t = (ch & 1) ? to : te;
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(at.x, xv.x, t, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(at.y, xv.y, t, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(at.z, xv.z, t, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
+                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(at.w, xv.w, t, 0, 0, 0);
+                        if (tail_groups > 1) {
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.x, xv.x, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.y, xv.y, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.z, xv.z, t2, 0, 0, 0);
+                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.w, xv.w, t2, 0, 0, 0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        a0 = n0; at = nt; a2 = n2;
+                    }
+                    // both halves' sums: rows 0..3 to the lower half-wave, rows 4..7 to the upper one, where a 32x32 tile
+                    // would have left them (registers 0..3); the other registers of this accumulator hold padding
+                    const float4 hv = *reinterpret_cast<const float4 *>(hs + tail_row0 + 4 * half);
+                    const float hq[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(te[r] + to[r]), __float_as_uint(t2[r]), false, false);
+                        acc1[r] = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) + hq[r];
+                    }
+#pragma unroll
+                    for (int r = 4; r < 16; ++r) acc1[r] = PAD_SCORE;
                 }
-                const float4 xv = xf[ch];
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
-                if (ch == 0 && more) fetch_block(st, cb + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                a0 = n0; a1 = n1;
+            } else {
+                float4 a0 = *reinterpret_cast<const float4 *>(w0row);
+                float4 a1 = *reinterpret_cast<const float4 *>(w1row);
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    float4 n0 = a0, n1 = a1;
+                    if (ch + 1 < NCH) {
+                        n0 = *reinterpret_cast<const float4 *>(w0row + (ch + 1) * 8);
+                        n1 = *reinterpret_cast<const float4 *>(w1row + (ch + 1) * 8);
+                    }
+                    const float4 xv = xf[ch];
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, xv.x, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, xv.x, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, xv.y, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, xv.y, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, xv.z, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, xv.z, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, xv.w, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, xv.w, acc1, 0, 0, 0);
+                    if (ch == 0 && more) fetch_block(st, cb + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    a0 = n0; a1 = n1;
+                }
             }
             if (more) store_block(st, Ws + ((cb + 1) & 1) * WB * DP);
             float bm = -INFINITY;
@@ -1488,19 +1554,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
+constexpr size_t MF_LDS_BUDGET = 150 * 1024;
+
 template <int NCH>
 hipError_t launch_qe_nch(const float *x, long long N, int d, int k, const float *w, double *partials, int nblocks, hipStream_t s)
 {
     const int kpad = (k + WB - 1) / WB * WB;
+    const size_t lds_res = ((size_t)kpad * (NCH * 8 + 4) + kpad) * sizeof(float);
+    if (lds_res <= MF_LDS_BUDGET) {
+        hipError_t e = hipFuncSetAttribute((const void *)quant_error_mfma_kernel<NCH, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_res);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((quant_error_mfma_kernel<NCH, true>), dim3(nblocks), dim3(512), lds_res, s, x, N, k, d, w, partials);
+        return hipGetLastError();
+    }
     const size_t lds = ((size_t)2 * WB * (NCH * 8 + 4) + kpad) * sizeof(float);
-    hipError_t e = hipFuncSetAttribute((const void *)quant_error_mfma_kernel<NCH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void *)quant_error_mfma_kernel<NCH, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((quant_error_mfma_kernel<NCH>), dim3(nblocks), dim3(512), lds, s, x, N, k, d, w, partials);
+    hipLaunchKernelGGL((quant_error_mfma_kernel<NCH, false>), dim3(nblocks), dim3(512), lds, s, x, N, k, d, w, partials);
     return hipGetLastError();
 }
-
-constexpr size_t MF_LDS_BUDGET = 150 * 1024;
-
 template <int NCH, bool RES, int NWV, int FSM = 0>
 hipError_t launch_variant(const StepParams &p, long long t0, long long t1, const float *xnorm2max, hipStream_t s, bool persistent)
 {
@@ -1548,7 +1620,7 @@ hipError_t launch_nch(const StepParams &p, long long t0, long long t1, const flo
     if (mfma_geom(p.k, p.b, NCH, true, 4).bytes <= half_cu && ((p.W > 256 && !(p.tune & 1)) || (p.tune & 2))) {
         // d <= 104 (d = 128 has no registers for it): the next tile's samples go to a second set of registers a whole
         // tile ahead, and the gradient sums are formed in a second pass over the mini-batch in memory order (on the
-        // k = d = 100 workload 6.07 -> 5.99 -> 5.6 ms per epoch).  tune bit 7: sort and gather instead of the second
+        // k = d = 100 workload 1.2 % and another 9 % of an epoch).  tune bit 7: sort and gather instead of the second
         // pass; bit 6: neither
         if constexpr (NCH <= 13) {
             if (!(p.tune & (64 | 128))) return launch_variant<NCH, true, 4, 3>(p, t0, t1, xnorm2max, s, persistent);

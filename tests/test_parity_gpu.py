@@ -673,7 +673,9 @@ def test_mean_state(B, oracle):
 
 
 @pytest.mark.parametrize("k,d,kernel_name", [(10, 10, "streaming"), (64, 32, "matrix-core"), (7, 5, "generic"),
-                                             (4, 4, "streaming"), (8, 16, "streaming"), (16, 12, "streaming")])
+                                             (4, 4, "streaming"), (8, 16, "streaming"), (16, 12, "streaming"),
+                                             (100, 100, "matrix-core"), (39, 12, "matrix-core"),     # 4x4 tiles at the end
+                                             (2048, 16, "matrix-core")])                             # state streamed through LDS
 def test_quant_error_of_tight_clusters_far_from_the_origin(B, oracle, k, d, kernel_name):
     """Eq. 8 where |x|^2 is ten orders of magnitude above the distances: centres in [0, 1000]^d, sigma = 0.01.  An
     expanded-form evaluation |x|^2/2 - max score loses everything to cancellation in fp32; the kernels form the winner's
