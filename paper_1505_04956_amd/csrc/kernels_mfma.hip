@@ -373,6 +373,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 fetch_block(st, 0);
                 store_block(st, Ws);
             }
+            if constexpr (PRE) {
+                // The loads into xf were issued a whole tile ago; touching the registers here makes the compiler wait
+                // for them now, BEFORE this tile issues the loads into xn.  Otherwise it cannot tell the two sets'
+                // loads apart (loads return in order, it counts them) and waits for the new ones at every use of xf.
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch)
+                    asm volatile("" : "+v"(xf[ch].x), "+v"(xf[ch].y), "+v"(xf[ch].z), "+v"(xf[ch].w));
+            }
             Top3 top;
             const float big = opaque_infinity();
             top.v1 = top.v2 = top.v3 = -INFINITY;
@@ -402,11 +410,11 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 constexpr int MODE = decltype(mode)::value;
                 constexpr bool INS = decltype(ins)::value;      // false: first half-block of a tile, nothing to insert
                 constexpr bool TAIL = decltype(tail)::value;
-                floatx4 te = {0.0f, 0.0f, 0.0f, 0.0f}, to = te, t2 = te;      // rows 0..3 (even, odd chunks), rows 4..7
-                float4 a2 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if constexpr (TAIL) {
-                    if (tail_groups > 1) a2 = *reinterpret_cast<const float4 *>(wrow + 4 * DP);
-                }
+                // TAIL: one chain of 4x4 tiles per component of the operand fragments, so that consecutive matrix
+                // instructions do not depend on each other; rows 0..3 in this loop, rows 4..7 (if any) in one of their own
+                floatx4 tq[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) tq[q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
                 unsigned nextoff = 0;
                 if constexpr (MODE == 2) {
                     nextoff = rowoff_of(nbase_next);
@@ -418,22 +426,14 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int ch = 0; ch < NCH; ++ch) {
                     // operands of the next chunk are read under the matrix work of this one; the scheduling
                     // barrier keeps the compiler from hoisting the reads of ALL chunks to the top (registers)
-                    float4 nx = a, nx2 = a2;
+                    float4 nx = a;
                     if (ch + 1 < NCH) nx = *reinterpret_cast<const float4 *>(wrow + (ch + 1) * 8);
                     const float4 xv = xf[ch];
                     if constexpr (TAIL) {
-                        if (ch + 1 < NCH && tail_groups > 1) nx2 = *reinterpret_cast<const float4 *>(wrow + 4 * DP + (ch + 1) * 8);
-                        floatx4 &t = (ch & 1) ? to : te;           // two chains: the instructions depend on each other
-                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.x, xv.x, t, 0, 0, 0);
-                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.y, xv.y, t, 0, 0, 0);
-                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.z, xv.z, t, 0, 0, 0);
-                        t = __builtin_amdgcn_mfma_f32_4x4x1f32(a.w, xv.w, t, 0, 0, 0);
-                        if (tail_groups > 1) {
-                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.x, xv.x, t2, 0, 0, 0);
-                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.y, xv.y, t2, 0, 0, 0);
-                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.z, xv.z, t2, 0, 0, 0);
-                            t2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.w, xv.w, t2, 0, 0, 0);
-                        }
+                        tq[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.x, xv.x, tq[0], 0, 0, 0);
+                        tq[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.y, xv.y, tq[1], 0, 0, 0);
+                        tq[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.z, xv.z, tq[2], 0, 0, 0);
+                        tq[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(a.w, xv.w, tq[3], 0, 0, 0);
                     } else {
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, xv.x, acc, 0, 0, 0);
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, xv.y, acc, 0, 0, 0);
@@ -450,12 +450,32 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                     // the last half-block has used this fragment for the last time: fetch the next tile's into its
                     // place, so that the fetch runs behind the matrix work and the epilogue of this tile
-                    if constexpr (MODE == 2) xn[ch] = frag(nextoff, ch);
+                    if constexpr (MODE == 2) {
+                        // (one set of registers and a second group of 4x4 tiles to come: that loop refills)
+                        if (!TAIL || tail_groups <= 1) xn[ch] = frag(nextoff, ch);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                     a = nx;
-                    if constexpr (TAIL) a2 = nx2;
                 }
                 if constexpr (TAIL) {
+                    const floatx4 lo = (tq[0] + tq[1]) + (tq[2] + tq[3]);
+                    floatx4 hi = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (tail_groups > 1) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) tq[q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                        const float *wrow2 = wrow + 4 * DP;
+#pragma unroll
+                        for (int ch = 0; ch < NCH; ++ch) {
+                            const float4 a2 = *reinterpret_cast<const float4 *>(wrow2 + ch * 8);
+                            const float4 xv = xf[ch];
+                            tq[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.x, xv.x, tq[0], 0, 0, 0);
+                            tq[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.y, xv.y, tq[1], 0, 0, 0);
+                            tq[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.z, xv.z, tq[2], 0, 0, 0);
+                            tq[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.w, xv.w, tq[3], 0, 0, 0);
+                            if constexpr (MODE == 2) xn[ch] = frag(nextoff, ch);
+                        }
+                        hi = (tq[0] + tq[1]) + (tq[2] + tq[3]);
+                    }
                     // rows 0..3 belong to the registers of half-wave 0, rows 4..7 to those of half-wave 1
                     const float4 hv = *reinterpret_cast<const float4 *>(hs + tail_row0 + 4 * half);
                     const float hq[4] = {hv.x, hv.y, hv.z, hv.w};
@@ -464,7 +484,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                         // v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
                         // second: afterwards the lower half-wave holds both halves' sums of rows 0..3, the upper
                         // half-wave those of rows 4..7
-                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(te[r] + to[r]), __float_as_uint(t2[r]), false, false);
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo[r]), __float_as_uint(hi[r]), false, false);
                         acc[r] = (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) + hq[r];
                     }
                     // (registers 4..15 are not looked at after a half-block of this kind)
