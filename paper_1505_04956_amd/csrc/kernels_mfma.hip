@@ -1255,11 +1255,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             const float inv = 1.0f / (float)(__builtin_popcount(delta_mask) + 1);
             const float *extp = ext0 + first * ext_stride;                  // read only when a message was accepted
             wn2max = 0.0f;
-            for (int c0 = wave * RB; c0 < k; c0 += MF_WAVES * RB) {
-                float w[RB][NJ], sm[RB][NJ], we[RB][NJ], s2[RB];
-                int cn[RB];
+            // four waves: twice the rows per wave in flight (the pass is a chain of load latencies, its registers are free here)
+            constexpr int UB = NWV == 4 ? 2 * RB : RB;
+            for (int c0 = wave * UB; c0 < k; c0 += MF_WAVES * UB) {
+                float w[UB][NJ], sm[UB][NJ], we[UB][NJ], s2[UB];
+                int cn[UB];
 #pragma unroll
-                for (int q = 0; q < RB; ++q) {
+                for (int q = 0; q < UB; ++q) {
                     const int c = c0 + q < k ? c0 + q : k - 1;
                     cn[q] = count_of(c);
 #pragma unroll
@@ -1272,7 +1274,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < RB; ++q) {
+                for (int q = 0; q < UB; ++q) {
                     s2[q] = 0.0f;
 #pragma unroll
                     for (int jq = 0; jq < NJ; ++jq) {
@@ -1288,7 +1290,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < RB; ++q) {
+                for (int q = 0; q < UB; ++q) {
                     const float sq = wave_sum_f(s2[q]);
                     if (lane == 0 && c0 + q < k) hs[c0 + q] = -0.5f * sq;
                     wn2max = fmaxf(wn2max, sq);
