@@ -184,7 +184,9 @@ __global__ void rownorm2_final_kernel(const float *partial, int n, float *out)
 //     half a unit = 2^-31 of the largest possible sum).  No counting sort, no gather.
 // FSM: 0 = sort and gather, 1 = FS, 2 = sort and gather with the sample fragments of the NEXT tile fetched into a second
 //     set of registers during the first half-block of a tile (instead of into the same set during the last one), so
-//     that a fetch has a whole tile of matrix work to arrive (resident state only).
+//     that a fetch has a whole tile of matrix work to arrive (resident state only), 3 = as 2, but no sort and no gather:
+//     once the assignments of the mini-batch are final, the state rows in LDS make room for fixed-point sums as in FS
+//     and the mini-batch is read a second time in memory order (see the pass itself).
 template <int NCH, bool RES, int NWV, int FSM>
 __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_steps_kernel(StepParams p, long long t0, long long t1,
                                                                  const float *xnorm2max_ptr, int sync)
