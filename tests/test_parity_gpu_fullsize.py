@@ -95,6 +95,15 @@ def test_partial_messages_full_size_wider_workload(oracle):
     assert o.counters[:, 2].sum() > 0
 
 
+def test_partial_messages_full_size_contraction_workload(oracle):
+    """Sec. 4.4 where the paper wants it, on the largest state (k = 1024, d = 128: 512 KB per full message, 64 centroid
+    rows per partial one with P = 16): one epoch plus the merge step after it, shape-agnostic kernel."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[4]
+    g, o = run_config(oracle, wl, wl.S + 1, B.KERNEL_GENERIC, kernel=B.KERNEL_GENERIC, parts=16)
+    assert o.counters[:, 1].sum() > 0
+
+
 @pytest.mark.skip(reason="partial messages (Sec. 4.4) on the matrix-core kernel at full size: the only batch of such runs "
                          "(k = d = 100 and k = 1024, d = 128 workloads, P = 1/4/16, also with 4 buffers) ended with the GPU box "
                          "reporting a fault or a hung queue; its log was lost with the box and no cause was found by reading "
