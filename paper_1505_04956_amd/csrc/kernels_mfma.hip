@@ -29,6 +29,7 @@
 #include <type_traits>
 
 #include "asgd_internal.h"
+#include "fixed_point_sums.h"
 #include "mfma_geom.h"
 
 namespace asgd {
@@ -269,17 +270,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     if constexpr (FS || SS) {
         // scale of column j: 2^e with b * max|x_j| * 2^e in [2^29, 2^30) (max|x_j| over the loaded samples)
         for (int j = tid; j < DP8; j += MF_THREADS) {
-            const float m = j < d ? (float)b * p.xabsmax[j] : 0.0f;
             float sc = 0.0f, inv = 0.0f;
-            if (m > 0.0f && m < 1.0e30f) {
-                int q = 0;
-                (void)frexpf(m, &q);              // m = f * 2^q, f in [0.5, 1)
-                int e = 30 - q;
-                if constexpr (SS) {               // ... and a single term stays below 2^22 (it is rounded in a float)
-                    int q1 = 0;
-                    (void)frexpf(p.xabsmax[j], &q1);
-                    e = min(e, 22 - q1);
-                }
+            int e = 0;
+            // (streamed sums: a single term must also stay below 2^22, it is rounded inside a float)
+            if (j < d && fx_scale_exponent(b, p.xabsmax[j], SS, &e)) {
                 sc = ldexpf(1.0f, e);
                 inv = ldexpf(1.0f, -e);
             }
@@ -814,10 +808,10 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
                     const int n = (s0 + u) * R + myr;
                     if (!decltype(guard)::value || n < b) {
                         int *cell = cell0 + (int)idx[n] * DP8;
-                        atomicAdd(cell, __float_as_int(fmaf(v[u].x, s4.x, 12582912.0f)));
-                        atomicAdd(cell + Q4, __float_as_int(fmaf(v[u].y, s4.y, 12582912.0f)));
-                        atomicAdd(cell + 2 * Q4, __float_as_int(fmaf(v[u].z, s4.z, 12582912.0f)));
-                        atomicAdd(cell + 3 * Q4, __float_as_int(fmaf(v[u].w, s4.w, 12582912.0f)));
+                        atomicAdd(cell, (int)fx_term_bits(v[u].x, s4.x));
+                        atomicAdd(cell + Q4, (int)fx_term_bits(v[u].y, s4.y));
+                        atomicAdd(cell + 2 * Q4, (int)fx_term_bits(v[u].z, s4.z));
+                        atomicAdd(cell + 3 * Q4, (int)fx_term_bits(v[u].w, s4.w));
                     }
                 }
             };
@@ -1106,7 +1100,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             else return cstart[sl + 1] - cstart[sl];
         };
         auto sum_of = [&](int c, int cn, int jq, unsigned e) -> float {
-            if constexpr (SS) return (float)(int)((unsigned)fxsum[c * DP8 + cellofs[jq]] - (unsigned)cn * 0x4B400000u) * invs[jq];
+            if constexpr (SS) return (float)fx_unbias((unsigned)fxsum[c * DP8 + cellofs[jq]], (unsigned)cn) * invs[jq];
             else return gsc[e];
         };
         const int has_mask = s_has_ext;      // uniform over the workgroup
