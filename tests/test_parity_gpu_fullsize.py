@@ -70,6 +70,25 @@ def test_wider_workload_full_size(oracle):
     assert o.counters[:, 2].sum() > 0
 
 
+def test_wider_workload_is_reproducible_bit_for_bit():
+    """Two runs of the k = d = 100 workload in the benchmark's launch configuration (one launch, 512 co-resident
+    workgroups, gradient sums added with integer atomics in whatever order the waves arrive) end in identical states
+    and counters."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[2]
+    X = workloads.generate_device(wl, device="cuda:0")
+    out = []
+    for rep in range(2):
+        g = B.ASGD(wl.k, wl.d, wl.W, wl.b, wl.lr, E=wl.E, seed=wl.schedule_seed)
+        g.load_shards(X)
+        g.run_epochs(2)
+        assert g.stats().kernel == B.KERNEL_MFMA
+        out.append((g.get_state().copy(), g.worker_counters().copy()))
+        g.close()
+    assert np.array_equal(out[0][0], out[1][0])
+    assert np.array_equal(out[0][1], out[1][1])
+
+
 def test_contraction_workload_full_size(oracle):
     from paper_1505_04956_amd import binding as B
     wl = workloads.CONFIGS[4]
