@@ -26,11 +26,14 @@ KERNEL_NAMES = {1: "generic_steps_kernel", 2: "small_steps_kernel", 3: "mfma_ste
 
 
 def traffic_from_profile(kernel_name, workload_name):
-    """HBM bytes per launch measured with rocprofv3 counters (committed summary), or None."""
+    """HBM bytes per EPOCH measured with rocprofv3 counters (committed summary: bytes per launch and the epochs a
+    launch of the profiled command covered), or None."""
     path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel_name, workload_name))
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
-        return float(m.group(1)) if m else None
+        text = open(path).read()
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
+        e = re.search(r"^epochs_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
+        return float(m.group(1)) / (float(e.group(1)) if e else 1.0) if m else None
     except OSError:
         return None
 
@@ -96,6 +99,11 @@ def main():
                     help="untimed device time spent on the same epochs before the warmup steps, until the clocks of a "
                          "freshly woken device have settled (the first few dozen launches of a process run up to 10 %% "
                          "slower); reported in the JSON line; 0 switches it off")
+    ap.add_argument("--epochs-per-call", type=int, default=10,
+                    help="epochs (= steps of this benchmark) handed to the library in one asgd_run_epochs call; where "
+                         "the library runs a call as ONE launch (streaming kernel, matrix-core kernel with two "
+                         "workgroups per CU) the start and the tail of a launch are then paid once per call, not once "
+                         "per epoch.  1: one call, one host synchronisation per epoch")
     ap.add_argument("--no-exchange-overhead", action="store_true",
                     help="skip the two extra timed runs (free-running, silent) behind the exchange_overhead object")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -133,31 +141,40 @@ def main():
         c.load_shards(X)
         return c
 
+    per_call = max(1, args.epochs_per_call)
+
+    def run(c, epochs):
+        """`epochs` epochs in calls of `per_call` (the last one may be shorter); kernel time and epochs of every call."""
+        calls = []
+        while epochs > 0:
+            n = min(per_call, epochs)
+            c.run_epochs(n)                   # returns after the device has finished
+            calls.append((c.last_run_ms(), n))
+            epochs -= n
+        return calls
+
     def timed(c, steps):
-        """`steps` epochs, one library call each; wall time over all of them and the kernel time of each."""
-        ms = []
+        """`steps` epochs; wall time over all of them and (kernel ms, epochs) of each library call."""
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            c.run_epochs(1)                   # returns after the device has finished
-            ms.append(c.last_run_ms())
+        calls = run(c, steps)
         torch.cuda.synchronize()
-        return time.perf_counter() - t0, ms
+        return time.perf_counter() - t0, calls
 
     g = context(args.mode)
     settle_epochs, settle_ms = 0, 0.0
     while settle_ms < args.settle_ms and settle_epochs < 10000:
-        g.run_epochs(1)
-        settle_ms += g.last_run_ms()
-        settle_epochs += 1
-    for _ in range(args.warmup):
-        g.run_epochs(1)
-    elapsed, kernel_ms = timed(g, args.steps)
+        for ms, n in run(g, per_call):
+            settle_ms += ms
+            settle_epochs += n
+    run(g, args.warmup)
+    elapsed, calls = timed(g, args.steps)
     st = g.stats()
 
     samples = wl.processed_per_epoch
     value = args.steps * samples / elapsed
-    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    avg_kernel_ms = sum(ms for ms, n in calls) / sum(n for ms, n in calls)       # per epoch
+    last_call_epochs = calls[-1][1]
     algo_bytes = samples * wl.d * 4            # one read of every processed sample
     algo_flops = samples * (2.0 * wl.k * wl.d + wl.k + wl.d)   # expanded-form scores, compares, accumulation
     kname = KERNEL_NAMES.get(int(st.kernel), "?")
@@ -170,8 +187,18 @@ def main():
         achieved = algo_bytes / (avg_kernel_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBPS, "algorithmic_bytes_per_launch": algo_bytes}
-    roofline.update({"traffic": traffic_from_profile(kname, wl.name), "kernel": kname, "kernel_ms": avg_kernel_ms,
-                     "launches": int(st.launches)})
+    # per epoch: kernel_ms and the algorithmic bytes / flops above; the launches of the last library call and its epochs
+    # say how many epochs one launch covers (traffic is per launch of the profiled command, see profiles/)
+    epochs_per_launch = last_call_epochs / max(1, int(st.launches))
+    per_epoch_traffic = traffic_from_profile(kname, wl.name)
+    roofline.update({"traffic": None if per_epoch_traffic is None else per_epoch_traffic * epochs_per_launch,
+                     "kernel": kname, "kernel_ms": avg_kernel_ms, "launches": int(st.launches),
+                     "epochs_per_launch": epochs_per_launch, "kernel_ms_per_launch": avg_kernel_ms * epochs_per_launch,
+                     "kernel_ms_per_call": [round(ms, 4) for ms, n in calls][:8]})
+    if "algorithmic_bytes_per_launch" in roofline:
+        roofline["algorithmic_bytes_per_launch"] = algo_bytes * epochs_per_launch
+    else:
+        roofline["algorithmic_flops_per_launch"] = algo_flops * epochs_per_launch
     out = {
         "metric": "samples/sec (assign+grad+update+merge) and % of peak HBM GB/s, 1 MI355X",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -180,7 +207,8 @@ def main():
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "k": wl.k, "W": wl.W, "b": wl.b, "lr": wl.lr,
                    "exchange_every": (0 if args.mode == "silent" else wl.E), "epochs_per_step": 1, "mode": args.mode,
                    "buffers": args.buffers, "parts": args.parts,
-                   "samples_per_step": samples, "kernel": int(st.kernel), "launches_per_step": int(st.launches)},
+                   "samples_per_step": samples, "kernel": int(st.kernel), "epochs_per_call": per_call,
+                   "launches_per_step": int(st.launches) / last_call_epochs},
         "roofline": roofline,
         "stats": {"messages_sent": int(st.sent), "messages_received": int(st.received),
                   "messages_accepted": int(st.accepted), "exact_rechecks": int(st.exact_rechecks)},
@@ -194,10 +222,9 @@ def main():
         for mode in ("deterministic", "free", "silent"):
             if mode not in per_mode:
                 c = context(mode)
-                for _ in range(max(args.warmup, 20)):      # (the first epochs of a fresh context run slower)
-                    c.run_epochs(1)
-                _, ms = timed(c, max(args.steps, 20))
-                per_mode[mode] = sum(ms) / len(ms)
+                run(c, max(args.warmup, 20))               # (the first epochs of a fresh context run slower)
+                _, cs = timed(c, max(args.steps, 20))
+                per_mode[mode] = sum(ms for ms, n in cs) / sum(n for ms, n in cs)
                 c.close()
         out["exchange_overhead"] = {
             "kernel_ms": per_mode, "unit": "ms per epoch",
