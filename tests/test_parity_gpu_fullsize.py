@@ -5,7 +5,8 @@
   - wider workload (k = d = 100, W = 512, b = 2000, E = 8): two epochs in one call (one launch), all assignments and
     states;
   - contraction workload (k = 1024, d = 128, W = 256, b = 4096, E = 4): one epoch plus the first
-    merge step, all assignments and states;
+    merge step (one launch per round), and two epochs plus a merge step in one call (one launch), all assignments
+    and states;
   - HBM-scale workload (N = 2.5e9, W = 4096, E = 16; 100 GB of samples): the whole epoch, round by
     round (the oracle is fed the rows of one communication round at a time), every assignment,
     every state at every round boundary, counters, Eq. 8 at the end; then the free-running mode.
@@ -96,6 +97,15 @@ def test_contraction_workload_full_size(oracle):
     wl = workloads.CONFIGS[4]
     g, o = run_config(oracle, wl, wl.S + 1, B.KERNEL_MFMA)                # the step after the epoch is a merge step
     assert o.counters[:, 1].sum() == wl.W
+
+
+def test_contraction_workload_full_size_one_launch(oracle):
+    """The same workload as bench.py times it: a call that covers several rounds is ONE launch of 256 co-resident
+    workgroups that wait for each other's messages (two epochs and the merge step after them)."""
+    from paper_1505_04956_amd import binding as B
+    wl = workloads.CONFIGS[4]
+    g, o = run_config(oracle, wl, 2 * wl.S + 1, B.KERNEL_MFMA, expect_launches=1)
+    assert o.counters[:, 1].sum() == 2 * wl.W
 
 
 def test_partial_messages_full_size_streaming_kernel(oracle):
