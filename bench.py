@@ -110,6 +110,8 @@ def main():
                     help="also run one plain device copy of the sample array (known size: N*d*4 bytes read and "
                          "written), so that a counter profile of this command can be scaled")
     args = ap.parse_args()
+    if args.steps < 1 or args.warmup < 0:
+        sys.exit("bench.py: --steps must be at least 1 and --warmup at least 0")
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (all workers share one MI355X); use --gpus 1")
 
