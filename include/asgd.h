@@ -195,7 +195,10 @@ int asgd_set_exchange(asgd_ctx *ctx, const float *values_host, const int32_t *ro
  * m' = b), merge of a buffered external state when t > 0 and t mod E == 0 (Eq. 4,
  * Eq. 7), update w <- w - eps * step (Alg. 5 line 8) and, when (t+1) mod E == 0, the
  * send of the new state to one other worker (Alg. 5 line 9).  Returns after the work
- * has finished on the device.
+ * has finished on the device.  The result does not depend on how a run is cut into
+ * calls (deterministic mode: bit for bit), the time does: where all workers fit the
+ * device at once, a call is ONE kernel launch however many epochs it covers, and the
+ * start and the tail of a launch are then paid once per call (asgd_stats.launches).
  */
 int asgd_run_epochs(asgd_ctx *ctx, int epochs);
 
