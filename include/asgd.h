@@ -197,8 +197,9 @@ int asgd_set_exchange(asgd_ctx *ctx, const float *values_host, const int32_t *ro
  * send of the new state to one other worker (Alg. 5 line 9).  Returns after the work
  * has finished on the device.  The result does not depend on how a run is cut into
  * calls (deterministic mode: bit for bit), the time does: where all workers fit the
- * device at once, a call is ONE kernel launch however many epochs it covers, and the
- * start and the tail of a launch are then paid once per call (asgd_stats.launches).
+ * device at once, a call is ONE kernel launch for every 1024 communication rounds it
+ * covers, and the start and the tail of a launch are then paid once per launch, not once
+ * per epoch (asgd_stats.launches).
  */
 int asgd_run_epochs(asgd_ctx *ctx, int epochs);
 

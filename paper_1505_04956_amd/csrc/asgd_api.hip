@@ -68,6 +68,9 @@ struct asgd_ctx {
 
 namespace {
 
+// rounds one launch with in-kernel waits covers at most (a longer call becomes several such launches)
+constexpr long long ONE_LAUNCH_MAX_ROUNDS = 1024;
+
 #define HIP_TRY(ctx, call)                              \
     do {                                                \
         hipError_t e__ = (call);                        \
@@ -636,7 +639,7 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
     int launches = 0;
     *ctx->flag_host = 0;         // (no kernel of this context is in flight: every run ends with a wait for the stream)
     HIP_TRY(ctx, hipEventRecord(ctx->ev0, ctx->stream));
-    bool done = false;
+    long long t_done = ctx->t;           // steps [ctx->t, t_done) have been launched
     const bool one_launch = (kernel == ASGD_KERNEL_SMALL && (ctx->tune & 3) != 3) || (kernel == ASGD_KERNEL_MFMA && !(ctx->tune & 4));
     if (rounds && one_launch && steps > 0) {
         // every worker has passed the merge points before the first step of this run
@@ -645,19 +648,27 @@ int asgd_run_steps(asgd_ctx *ctx, int64_t steps)
         // (a one-launch run leaves exactly these values behind: no need to write them again for the run that follows it)
         if (ctx->passed_t != ctx->t)
             HIP_TRY(ctx, hipMemsetD32Async((hipDeviceptr_t)ctx->consumed, passed, (size_t)ctx->W, ctx->stream));
-        hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, ctx->t, t_end, ctx->stream, true)
-                                                     : launch_mfma_steps(p, ctx->t, t_end, ctx->xnorm2max, ctx->stream, true);
-        if (e == hipSuccess) {
-            done = true;
-            launches = 1;
-            ctx->passed_t = t_end;
-        } else if (e == hipErrorCooperativeLaunchTooLarge || e == hipErrorNotSupported) {
-            (void)hipGetLastError();     // fall back to one launch per round
-        } else {
-            HIP_TRY(ctx, e);
+        // A launch covers at most ONE_LAUNCH_MAX_ROUNDS rounds and ends on a round boundary: the waits of a workgroup
+        // draw on one budget of polls per launch, which the short waits of a healthy run must not use up however long
+        // the call is.
+        while (t_done < t_end) {
+            long long tb = (t_done / ctx->E + ONE_LAUNCH_MAX_ROUNDS) * (long long)ctx->E;
+            if (tb > t_end) tb = t_end;
+            hipError_t e = (kernel == ASGD_KERNEL_SMALL) ? launch_small_steps(p, t_done, tb, ctx->stream, true)
+                                                         : launch_mfma_steps(p, t_done, tb, ctx->xnorm2max, ctx->stream, true);
+            if (e == hipSuccess) {
+                ++launches;
+                t_done = tb;
+                ctx->passed_t = tb;
+            } else if (e == hipErrorCooperativeLaunchTooLarge || e == hipErrorNotSupported) {
+                (void)hipGetLastError();     // the rest (or all of it): one launch per round
+                break;
+            } else {
+                HIP_TRY(ctx, e);
+            }
         }
     }
-    for (long long ta = ctx->t; !done && ta < t_end;) {
+    for (long long ta = t_done; ta < t_end;) {
         long long tb = t_end;
         if (rounds) {
             const long long next = (ta / ctx->E + 1) * (long long)ctx->E;

@@ -693,6 +693,22 @@ def test_quant_error_of_tight_clusters_far_from_the_origin(B, oracle, k, d, kern
     assert abs(qg - qo) <= TOL * qo
 
 
+@pytest.mark.parametrize("kernel,tune,k,d,W,b", [(2, 0, 10, 10, 8, 64), (3, 2, 40, 20, 12, 32), (3, 8, 40, 20, 12, 32)])
+def test_long_call_is_cut_into_launches_of_bounded_length(B, kernel, tune, k, d, W, b):
+    """A call that covers more rounds than one launch with in-kernel waits is allowed (1024) becomes several such
+    launches; the result is that of the same steps handed over in small pieces, bit for bit."""
+    steps = 2500                                      # E = 1: 2500 rounds -> 3 launches
+    X = make_data(W * b * 7 + 5, d, k, seed=47)       # (7 steps per epoch: the run wraps around many times)
+    Xg = to_dev(X)
+    whole = B.ASGD(k, d, W, b, 0.02, E=1, kernel=kernel, tune=tune); whole.load_shards(Xg); whole.run_steps(steps)
+    assert whole.stats().launches == 3
+    pieces = B.ASGD(k, d, W, b, 0.02, E=1, kernel=kernel, tune=tune); pieces.load_shards(Xg)
+    for n in (1000, 1, 1023, 476):
+        pieces.run_steps(n)
+    assert np.array_equal(whole.get_state(), pieces.get_state())
+    assert np.array_equal(whole.worker_counters(), pieces.worker_counters())
+
+
 @pytest.mark.parametrize("kernel,tune,k,d,W,b", [(2, 0, 10, 10, 8, 200), (3, 2, 40, 20, 12, 100)])
 def test_expired_wait_is_reported_and_the_context_recovers(B, kernel, tune, k, d, W, b):
     """The error path of the runs that are one launch: the host makes every message get lost without telling the
