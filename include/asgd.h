@@ -40,8 +40,9 @@ enum {
     ASGD_EHIP = -4,     /* a HIP runtime call failed; asgd_last_hip_error() has its code */
     ASGD_ESYNC = -5     /* a bounded wait inside a kernel expired (runs that are one launch of workgroups
                            which wait for each other's messages; all the waits of a workgroup draw on one
-                           budget of polls, so such a launch ends within about a second of waiting whatever
-                           its length).  The run is lost: the step counter is not advanced and later runs
+                           budget of polls that grows with the rounds of the launch, and a launch covers
+                           at most 1024 rounds, so such a launch ends within a second plus a few
+                           milliseconds per round of waiting).  The run is lost: the step counter is not advanced and later runs
                            fail with ASGD_ESTATE until asgd_load_shards(), or asgd_set_state() followed by
                            asgd_set_step(), have put the context back on a known footing. */
 };

@@ -52,6 +52,7 @@ constexpr float PAD_SCORE = -1.0e30f;   // offset of the padding rows: never the
 // waits for nothing any more (s_wait_failed), so a launch outlasts its normal duration by about a quarter of a second
 // at most, however many rounds it covers.
 constexpr int MF_WAIT_BUDGET = 1 << 18;
+constexpr int MF_WAIT_PER_ROUND = 4096;
 __device__ __forceinline__ bool mf_wait_flag(const int *flag, int want, bool at_least, int *budget)
 {
     int left = *budget;
@@ -239,7 +240,13 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
     float *gsc = p.acc + (size_t)i * kd;                // per-centroid sums of assigned samples
     const float xn2 = *xnorm2max_ptr;
 
-    if (threadIdx.x == 0) { s_wait_failed = 0; s_wait_budget = p.wait_polls > 0 ? p.wait_polls : MF_WAIT_BUDGET; }       // read after the barriers below
+    if (threadIdx.x == 0) {              // read after the barriers below
+        s_wait_failed = 0;
+        // the budget grows with the rounds of the launch: a healthy run of the k = d = 100 workload spends up to ~700
+        // polls per round on the workgroup that waits most (the host keeps launches to 1024 rounds)
+        const long long rounds_here = p.E > 0 ? (t1 - t0) / p.E + 1 : 0;
+        s_wait_budget = p.wait_polls > 0 ? p.wait_polls : MF_WAIT_BUDGET + MF_WAIT_PER_ROUND * (int)min(rounds_here, (long long)(1 << 16));
+    }
     // ---- h_c = -|w_c|^2/2 and max_c |w_c|^2 ----
     float wn2max = 0.0f;
     for (int c0 = wave * RB; c0 < g.kpad; c0 += MF_WAVES * RB) {

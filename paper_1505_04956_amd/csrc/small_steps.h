@@ -189,10 +189,11 @@ __device__ __forceinline__ unsigned long long load_pair(const unsigned long long
 }
 
 // Polls a workgroup may spend, in total, on all the waits of a launch: every wait of this kernel draws on one
-// budget, so a launch whose workgroups do not find each other ends after a fraction of a second however many
-// rounds it covers (a poll takes ~0.3 us of sleep plus one uncached load).  When the budget is gone the caller
+// budget, so a launch whose workgroups do not find each other ends after a fraction of a second plus under a
+// millisecond per round it covers (a poll takes ~0.3 us of sleep plus one uncached load).  When the budget is gone the caller
 // goes on without the message (and waits for nothing else) and the host reports the failure.
 constexpr int WAIT_BUDGET = 1 << 19;
+constexpr int WAIT_PER_ROUND = 512;      // ... plus this many per round of the launch (the host keeps launches to 1024 rounds)
 
 __device__ __forceinline__ bool wait_at_least(const int *flag, int want, int &budget)
 {
@@ -829,6 +830,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
     SmallKeeper<K, D, NB, PARTS> kp;
     kp.init(p, lane);
+    // the budget of polls grows with the rounds the launch covers: a healthy run of the streaming workload spends up
+    // to ~30 polls per round on the workgroup that waits most
+    if (p.wait_polls <= 0 && p.E > 0) kp.budget += WAIT_PER_ROUND * (int)min((t1 - t0) / p.E + 1, (long long)(1 << 20));
     // float4 number this lane works on in phase ph of a row update, as an offset in float4 units
     int qoff[NQ];
 #pragma unroll
