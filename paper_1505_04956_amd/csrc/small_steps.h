@@ -13,24 +13,23 @@
 //     of a network of three-input max/median instructions; when they are closer than a rigorous
 //     bound on the fp32 rounding error (packing included), the lane decides exactly in fp64, so the
 //     assignment is the exact-arithmetic nearest centroid of the fp32 state;
-//   - the gradient sums of Eq. 9 are kept per lane in LDS: a row holds the d sums and the count of
-//     one centroid, as NQ float4, for one lane (RS = 1) or for the lane pair l, l+32 (RS = 2).  A
-//     sample is added to its row in NQ phases of one 128-bit read, four adds and one 128-bit write;
-//     in phase p the lower lanes work on float4 number p and the upper lanes on number p+1 (mod NQ),
-//     so a shared row is never touched twice in one phase and every LDS instruction serves all 64
-//     lanes.  The phases of a group are interleaved with the score computation of the next group,
-//     which hides their LDS latency.  Lanes past the end of a mini-batch use a scratch row.  A
-//     fixed-order reduction follows once per step.
+//   - the gradient sums of Eq. 9 are kept in LDS as 32-bit fixed-point cells, one copy per lane (RS = 1) or per
+//     lane pair l, l+32 (RS = 2): a sample adds its d values, each scaled by its column's power of two and rounded
+//     to an integer, and a one for the count to the cells of its centroid with d + 1 LDS atomics that return
+//     nothing.  Lanes past the end of a mini-batch use a scratch centroid.  Once per step the copies of every cell
+//     are summed and cleared.
 // The part of a step that does not stream (row sums, totals, update, the new wave-uniform copies) is
 // on every worker's critical path, once per mini-batch; it is written for few instructions: all step
 // bookkeeping is 32-bit and scalar, the state lives in registers in the layout the row sums come out
 // in, and the wave-uniform copies are made with one LDS write and broadcast reads.
-// Every sum is formed in one fixed order, so a run is reproducible bit for bit.
+// The sums are integers, so they do not depend on the order of the additions; everything after them is formed in one
+// fixed order: a run is reproducible bit for bit.
 #pragma once
 
 #include <string.h>
 
 #include "asgd_internal.h"
+#include "fixed_point_sums.h"
 
 namespace asgd {
 
@@ -139,9 +138,9 @@ __device__ __forceinline__ void top2(const float (&t)[N], float &best, float &se
     second = M;
 }
 
-// Lanes l and l+32 hand parts of an accumulator row to each other through LDS.  The hardware executes
-// the LDS accesses of a wave in program order; this keeps the compiler from moving the read of one
-// phase above the write of the previous one (to a single lane the two look unrelated).
+// The lanes of a wave hand values to each other through LDS (the copies of the state, the accumulator cells).  The
+// hardware executes the LDS accesses of a wave in program order; this keeps the compiler from moving a read above
+// the write or atomic of another lane that it has to see (to a single lane the two look unrelated).
 __device__ __forceinline__ void phase_fence()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -205,26 +204,18 @@ __device__ __forceinline__ bool wait_at_least(const int *flag, int want, int &bu
     return false;
 }
 
-// Geometry of a small state: rows of d sums and a count, padded to NQ float4.
+// Geometry of a small state: per centroid d sums and a count, padded to NQ groups of four elements.
 template <int K, int D>
 struct SmallGeo {
     static constexpr int KD = K * D;
-    static constexpr int NQ = (D + 1 + 3) / 4;      // float4 per accumulator row: d sums, count, padding
+    static constexpr int NQ = (D + 1 + 3) / 4;      // groups of four elements per centroid: d sums, count, padding
     static constexpr int RW = 4 * NQ;               // floats per padded row
-    static constexpr int NT = K * NQ;               // tasks: one float4 column each
-    static constexpr int NPART = 64 / NT;           // lanes of a wave that share a task split the rows in the reduction
+    static constexpr int NT = K * NQ;               // tasks: four elements of one centroid each
+    static constexpr int NPART = 64 / NT;           // lanes of a wave that share a task split the copies in the reduction
     static constexpr int CQ = D / 4, CI = D % 4;    // float4 and component that hold the count
     static_assert(K >= 2 && K <= 16, "index packing uses 4 bits");
     static_assert(NT <= 64 && NPART >= 1, "state too large for this kernel");
 };
-
-// part of sample x that goes to float4 number q of a row, component c4: the d values, then the count
-template <int D>
-__device__ __forceinline__ float row_part(const float (&x)[D], int q, int c4)
-{
-    const int j = 4 * q + c4;
-    return j < D ? x[j] : (j == D ? 1.0f : 0.0f);
-}
 
 // Nearest centroid of a lane's sample from its tagged scores tk and the two largest of them (largest = nearest;
 // tag = 15 - index in the low 4 mantissa bits): exact where the fp32 scores are closer than thr.  wsf: the copy of the
@@ -279,34 +270,44 @@ __device__ __forceinline__ int decide(const float (&tk)[K], float best, float se
     return arg;
 }
 
-// Sums `rows` accumulator rows of one float4 column (col[r], r < rows) in a fixed order and clears them.  Row r of
-// the visit is row r ^ (task mod ROWS) of the column, so that the lanes of one access hit different banks; with the
-// column at a multiple of ROWS * 16 bytes in LDS the address of a row is ONE exclusive-or away from the address of the
-// first (no add, mask and shift per row).
-typedef float lds_vec4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) lds_vec4 *lds_vec4_ptr;
-template <int ROWS>
-__device__ __forceinline__ float4 sum_and_clear(float4 *col, int task)
+// Row updates: the accumulator of a wave holds 32-bit fixed-point sums (fixed_point_sums.h), element-major - cell
+// (centroid c, element j, copy r) lies at ((c * 4 NQ + j) * RL + r) * 4 bytes, element D being the count -, and a sample
+// adds its D terms and a one for the count with D + 1 LDS atomics that return nothing.  The lanes of one such instruction
+// (same j, consecutive r) fall into consecutive banks; there is no read-modify-write chain through LDS and no exchange
+// of operands between lanes that share a copy, and because integer addition does not depend on the order, the sums
+// - and with them the whole run - are the same whatever order the lanes get their turn in.
+typedef __attribute__((address_space(3))) unsigned *lds_u32_ptr;
+typedef int lds_ivec4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) lds_ivec4 *lds_ivec4_ptr;
+__device__ __forceinline__ void lds_add_u32(unsigned addr, unsigned v)
 {
-    static_assert(ROWS % 2 == 0 && (ROWS & (ROWS - 1)) == 0, "rows are summed in two interleaved chains; the rotation is an exclusive-or");
-    unsigned first = (unsigned)(size_t)(lds_vec4_ptr)(lds_vec4 *)col + ((unsigned)(task & (ROWS - 1)) << 4);
-    // (the row addresses are formed here, at every call, from a value the compiler cannot see through: hoisted out of
-    // the step loop they would be ROWS more registers per lane, held across the streaming part)
+    (void)__hip_atomic_fetch_add((lds_u32_ptr)(size_t)addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+// Sums and clears the cells of elements 4q .. 4q+3 of one centroid over ROWS copies: `cells` is the LDS byte address of
+// copy 0 of element 4q (a multiple of ROWS * 4), elem_bytes the distance between elements.  Four copies are read at a
+// time; block rb of the visit is block rb ^ (task mod ROWS/4), so that the lanes of one access do not all hit the same
+// banks, and its address is ONE exclusive-or away from the first (no add, mask and shift per block).
+template <int ROWS>
+__device__ __forceinline__ void sum_and_clear_cells(unsigned cells, unsigned elem_bytes, int task, int (&s)[4])
+{
+    static_assert(ROWS % 4 == 0 && ((ROWS / 4) & (ROWS / 4 - 1)) == 0, "blocks of four copies, rotated by exclusive-or");
+    unsigned first = cells + ((unsigned)(task & (ROWS / 4 - 1)) << 4);
+    // (the addresses are formed here, at every call, from a value the compiler cannot see through: hoisted out of
+    // the step loop they would be registers held across the streaming part)
     asm volatile("" : "+v"(first));
-    const lds_vec4 zero = {0.f, 0.f, 0.f, 0.f};
-    lds_vec4 s0 = zero, s1 = zero;
+    const lds_ivec4 zero = {0, 0, 0, 0};
 #pragma unroll
-    for (int r = 0; r < ROWS; r += 2) {
-        lds_vec4_ptr p0 = (lds_vec4_ptr)(size_t)(first ^ (unsigned)(r << 4));
-        lds_vec4_ptr p1 = (lds_vec4_ptr)(size_t)(first ^ (unsigned)((r + 1) << 4));
-        const lds_vec4 v0 = *p0, v1 = *p1;
-        *p0 = zero;
-        *p1 = zero;
-        s0 = r == 0 ? v0 : s0 + v0;
-        s1 = r == 0 ? v1 : s1 + v1;
+    for (int c4 = 0; c4 < 4; ++c4) {
+        lds_ivec4 t = zero;
+#pragma unroll
+        for (int rb = 0; rb < ROWS / 4; ++rb) {
+            lds_ivec4_ptr q = (lds_ivec4_ptr)(size_t)((first ^ (unsigned)(rb << 4)) + (unsigned)c4 * elem_bytes);
+            const lds_ivec4 v = *q;
+            *q = zero;
+            t = rb == 0 ? v : t + v;
+        }
+        s[c4] = (t.x + t.y) + (t.z + t.w);
     }
-    const lds_vec4 t = s0 + s1;
-    return make_float4(t.x, t.y, t.z, t.w);
 }
 
 // The walk of a workgroup through its work, the same in every wave: segments of steps (in deterministic mode a
@@ -368,8 +369,8 @@ struct SmallWalk {
 // early fetch of the messages, gradient, merge (Eq. 4, Eq. 6 / Eq. 7), update (Alg. 5 line 8), send (Alg. 5 line 9).
 //
 // State layout in registers ("task layout"): lane l < NT = K*NQ holds the four elements (c, 4q .. 4q+3) of the state
-// with c = l / NQ, q = l % NQ (elements past d do not exist and stay 0); the same lane receives the total of float4
-// column (c, q) of the accumulator rows once per step.  Written to LDS as one float4 per lane this is the state with
+// with c = l / NQ, q = l % NQ (elements past d do not exist and stay 0); the same lane receives the totals of the
+// accumulator cells of these four elements once per step.  Written to LDS as one float4 per lane this is the state with
 // its rows padded to 4*NQ floats.
 //   NB     external buffers per worker = recipients per message (Eq. 3 / Eq. 6); NB = p.nb
 //   PARTS  partial messages (Sec. 4.4) compiled in; p.parts > 1 needs it
@@ -531,7 +532,7 @@ struct SmallKeeper {
         }
     }
 
-    // End of a step: S4 = total of this lane's float4 column of the gradient sums (the count of a centroid in
+    // End of a step: S4 = totals of this lane's four elements of the gradient sums (the count of a centroid in
     // component CI of float4 number CQ).  BAR: several waves hold the state and read the buffers, a workgroup barrier
     // separates their reads from the release of the buffers.  sender: this wave writes messages, state and counters.
     template <bool BAR>
@@ -742,10 +743,9 @@ struct SmallKeeper {
 };
 
 // Steps [t0, t1) of the workers blockIdx.x, blockIdx.x + gridDim.x, ..., with NW like waves per worker: wave v takes
-// the groups v, v+NW, ... of every mini-batch from the loads to the accumulator rows, and every wave holds the state.
-//   RS   lanes sharing an accumulator row: 1 = every lane has its own rows (64 per centroid and
-//        wave); 2 = lanes l and l+32 share a row, which halves the LDS per wave so that twice as many
-//        waves are resident.
+// the groups v, v+NW, ... of every mini-batch from the loads to the accumulator cells, and every wave holds the state.
+//   RS   lanes sharing a copy of the accumulator cells: 1 = every lane has its own (64 copies per wave); 2 = lanes l and
+//        l+32 share one, which halves the LDS per wave so that twice as many waves are resident.
 //   sync = 0: the launch contains nothing a worker has to wait for (silent or free-running mode,
 //             or the host ends every launch at a multiple of E); one workgroup per worker.
 //   sync = 1: the whole run is one launch of co-resident workgroups.  A workgroup takes its workers
@@ -796,23 +796,22 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 {
     using G = SmallGeo<K, D>;
     constexpr int NQ = G::NQ, RW = G::RW, NT = G::NT, NPART = G::NPART;
-    constexpr int RL = 64 / RS;                     // accumulator rows per centroid and wave
-    constexpr int RPP = RL / NPART;                 // rows one lane sums in the reduction
+    constexpr int RL = 64 / RS;                     // copies of an accumulator cell per wave (lanes r and r + RL share one)
+    constexpr int RPP = RL / NPART;                 // copies one lane sums in the reduction
     static_assert(NW == 1 || NW == 2, "one or two waves per worker");
-    static_assert(RS == 1 || (RS == 2 && NQ >= 2), "two lanes share a row only if it has two float4 or more");
+    static_assert(RS == 1 || RS == 2, "one copy per lane, or one per pair of lanes");
     static_assert(PF >= 2, "the ring needs the previous group's buffer");
-    static_assert(RL % NPART == 0 && RPP % 2 == 0, "state too large for this kernel");
+    static_assert(RL % NPART == 0 && RPP % 4 == 0, "state too large for this kernel");
 
-    // acc[wave][row][q][r]: float4 number q of the row that lane r (RS = 2: lanes r and r+32) keeps for
-    // centroid `row`; row K is scratch for masked lanes.  Consecutive lanes are 16 bytes apart.
-    __shared__ __align__(1024) float4 acc[NW][K + 1][NQ][RL];    // (alignment: see sum_and_clear)
+    // acc[wave][c][j][r]: copy r (lane r; RS = 2: lanes r and r + 32) of the fixed-point sum of element j of the samples
+    // of centroid c, j = D: their count, j > D: unused; row K is scratch for masked lanes
+    __shared__ __align__(1024) unsigned acc[NW][K + 1][4 * NQ][RL];      // (alignment: see sum_and_clear_cells)
     __shared__ float4 wst[NW][NT];                  // state, rows padded to RW floats; one copy per wave
     __shared__ float4 wdt[NW][NT];                  // row k: w_k - w_0 in elements < D, (h_k - h_0) + 1 in element D
-    __shared__ float4 part[2][NW][NPART][NT];       // per-wave totals, double-buffered by step parity
+    __shared__ int4 part[2][NW][NPART][NT];         // per-wave totals, double-buffered by step parity
 
     const int wave = NW == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
-    const bool lower = RS == 1 || lane < 32;        // the half of the wave that starts with float4 number 0
     const int b = p.b, W = p.W, E = p.E;
     const bool det = (p.mode == ASGD_MODE_DETERMINISTIC);
     // groups of 64 samples per mini-batch and wave, rounded up to a multiple of the ring depth (the
@@ -833,11 +832,27 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     // the budget of polls grows with the rounds the launch covers: a healthy run of the streaming workload spends up
     // to ~30 polls per round on the workgroup that waits most
     if (p.wait_polls <= 0 && p.E > 0) kp.budget += WAIT_PER_ROUND * (int)min((t1 - t0) / p.E + 1, (long long)(1 << 20));
-    // float4 number this lane works on in phase ph of a row update, as an offset in float4 units
-    int qoff[NQ];
+    for (int q = lane; q < (K + 1) * 4 * NQ * RL; q += 64) (&acc[wave][0][0][0])[q] = 0u;
+
+    // Fixed-point sums: the scale of every column (2^e with b * max|x_j| * 2^e < 2^30 and max|x_j| * 2^e < 2^22; 0 for a
+    // column of zeros), the inverse scales of this lane's four elements in the task layout (the count needs none),
+    // and the LDS byte address of this lane's copy of element 0 of centroid 0
+    constexpr unsigned ELEM_BYTES = RL * 4u, CENT_BYTES = 4u * NQ * ELEM_BYTES;
+    float scl[D], inv4[4];
 #pragma unroll
-    for (int ph = 0; ph < NQ; ++ph) qoff[ph] = (lower ? ph : (ph + 1) % NQ) * RL;
-    for (int q = lane; q < (K + 1) * NQ * RL; q += 64) (&acc[wave][0][0][0])[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c4 = 0; c4 < 4; ++c4) inv4[c4] = 1.0f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        int e = 0;
+        const bool okj = fx_scale_exponent(b, p.xabsmax[j], true, &e);
+        scl[j] = okj ? ldexpf(1.0f, e) : 0.0f;
+        const float iv = okj ? ldexpf(1.0f, -e) : 0.0f;
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4)
+            if (kp.has_task && 4 * kp.tq + c4 == j) inv4[c4] = iv;
+    }
+    const unsigned wave_cells = (unsigned)(size_t)(lds_u32_ptr)&acc[wave][0][0][0];
+    const unsigned lane_cell = wave_cells + (unsigned)(lane % RL) * 4u;
 
     int rechecks = 0;
     int parity = 0;
@@ -863,27 +878,6 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
             for (int j = 0; j < D; ++j) asm volatile("" : "+v"(xr[u][j]));
         }
     }
-
-    // one phase of a row update: add, write, (fence,) read for the next phase
-    auto row_phase = [&](const float(&xp)[D], int ph, float4 *prow, float4 &pr) {
-        float add[4];
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) {
-            const float lo = row_part<D>(xp, ph, c4);
-            if constexpr (RS == 1) {
-                add[c4] = lo;
-            } else {
-                const float hi = row_part<D>(xp, (ph + 1) % NQ, c4);
-                add[c4] = lower ? lo : hi;
-            }
-        }
-        pr.x += add[0]; pr.y += add[1]; pr.z += add[2]; pr.w += add[3];
-        prow[qoff[ph]] = pr;
-        if (ph + 1 < NQ) {
-            if constexpr (RS == 2) phase_fence();
-            pr = prow[qoff[ph + 1]];
-        }
-    };
 
     // A workgroup with one worker keeps its state in registers from segment to segment (every wave holds the same
     // values); one that takes several workers in turn stores and reloads it.
@@ -936,11 +930,6 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 int32_t *dump = p.dump ? p.dump + ((size_t)(wk.dump0 + wk.done + ls) * W + i) * b : nullptr;
                 const float tk0 = __uint_as_float(0x3F800000u | 15u);     // t_0 = 1 with the index of centroid 0
 
-                // pending row update of the group before the current one: row pointer (float4 number 0 of the
-                // row) and the float4 read for the coming phase.  At the start of a step: the scratch row.
-                float4 *prow = &acc[wave][K][0][lane % RL];
-                float4 pr = prow[qoff[0]];
-
                 int m0 = 0;
                 do {        // (ngw >= PF: at least one turn, which the compiler has to know for settle_fetched)
                     // Refills of this turn: slot 0 takes group m0 + PF - 1 of this mini-batch, slot u >= 1 group
@@ -955,36 +944,23 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                         const int up = (u + PF - 1) % PF;           // buffer of the previous group
                         const int m = m0 + u;
                         const float(&xc)[D] = xr[u];
-                        const float(&xp)[D] = xr[up];
 
                         // t_k with the centroid index in the low 4 mantissa bits (15 - k, so that the lower index
-                        // wins exact ties of positive values); between the chains, the row phases of the
-                        // previous group: add, write, (fence,) read for the next phase
+                        // wins exact ties of positive values)
                         float tk[K];
                         tk[0] = tk0;
                         // The chains advance together, in two sets (a wave issues an instruction that depends on the
                         // one before it at two thirds of the rate of independent ones, and four or more independent
                         // chains issue at the full rate; the scheduling barriers in score_chains keep the compiler from
-                        // putting the chains one after the other).  Row phases 0 and 1 of the previous group follow a
-                        // set each and the remaining ones the search for the two largest scores, so that the LDS read
-                        // issued at the end of a phase returns under other work instead of being waited for at once.
+                        // putting the chains one after the other).
                         constexpr int CA = K / 2, CB = K - 1 - CA;
                         score_chains<K, D, 1, CA>(xc, wv, tk);
                         __builtin_amdgcn_sched_barrier(0);
-                        row_phase(xp, 0, prow, pr);
-                        __builtin_amdgcn_sched_barrier(0);
                         score_chains<K, D, 1 + CA, CB>(xc, wv, tk);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if constexpr (NQ > 1) row_phase(xp, 1, prow, pr);
                         __builtin_amdgcn_sched_barrier(0);
                         float best, second;
                         top2<K>(tk, best, second);
                         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int ph = 2; ph < NQ; ++ph) {
-                            row_phase(xp, ph, prow, pr);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
                         // buffer `up` is free now: refill it with the group PF-1 turns ahead
                         {
                             const unsigned off = u == 0 ? own_off : turn_off + (unsigned)(NW * (u - 1)) * GROUP_BYTES;
@@ -997,35 +973,50 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                         const int arg = decide<K, D>(tk, best, second, xc, valid, thr, wsf, rechecks);
                         if (dump && valid) dump[n] = arg;
 
-                        // start this group's row update: read for phase 0
-                        if constexpr (RS == 2) phase_fence();
-                        prow = &acc[wave][valid ? arg : K][0][lane % RL];
-                        pr = prow[qoff[0]];
+                        // this group's row update: D fixed-point terms and a one for the count, added to the lane's
+                        // cells of the centroid (masked lanes: the scratch row)
+                        const unsigned cell = lane_cell + __umul24((unsigned)(valid ? arg : K), CENT_BYTES);
+#pragma unroll
+                        for (int j = 0; j < D; ++j) lds_add_u32(cell + (unsigned)j * ELEM_BYTES, fx_term_bits(xc[j], scl[j]));
+                        lds_add_u32(cell + (unsigned)D * ELEM_BYTES, 1u);
                     }
                     kp.settle_fetched();
                     m0 += PF;
                 } while (m0 < ngw);
-                // finish the last group of the mini-batch (buffer PF-1)
-#pragma unroll
-                for (int ph = 0; ph < NQ; ++ph) row_phase(xr[PF - 1], ph, prow, pr);
-                phase_fence();      // a wave sums its own rows
+                phase_fence();      // a wave sums its own cells: its atomics have to be done
 
-                // ---- sum the rows of every centroid in a fixed order, clear them ----
-                // lane = (part, task): task = one float4 column (centroid, float4 number); part = its share of the rows
+                // ---- sum the copies of every cell, clear them ----
+                // lane = (part, task): task = four elements of a centroid (centroid, float4 number); part = its share of
+                // the copies
                 {
                     const int task = lane % NT, prt = lane / NT;
-                    if (prt < NPART)
-                        part[parity][wave][prt][task] = sum_and_clear<RPP>(&acc[wave][task / NQ][task % NQ][prt * RPP], task);
+                    if (prt < NPART) {
+                        int si[4];
+                        sum_and_clear_cells<RPP>(wave_cells + (unsigned)(task / NQ) * CENT_BYTES +
+                                                     (unsigned)(4 * (task % NQ)) * ELEM_BYTES + (unsigned)(prt * RPP) * 4u,
+                                                 ELEM_BYTES, task, si);
+                        part[parity][wave][prt][task] = make_int4(si[0], si[1], si[2], si[3]);
+                    }
                 }
                 if constexpr (NW > 1) __syncthreads(); else phase_fence();
-                // totals of this lane's float4 column: waves, then parts, one fixed order
-                float S4[4] = {0.f, 0.f, 0.f, 0.f};
+                // Totals of this lane's four elements over waves and parts, as integers.  The count of the centroid
+                // (element D) times the rounding constant comes off the sums (modulo 2^32, like the additions), then
+                // the column's inverse scale.
+                int Si[4] = {0, 0, 0, 0};
                 if (kp.has_task) {
 #pragma unroll
                     for (int v = 0; v < NW * NPART; ++v) {
-                        const float4 sv = (&part[parity][0][0][0])[v * NT + lane];
-                        S4[0] += sv.x; S4[1] += sv.y; S4[2] += sv.z; S4[3] += sv.w;
+                        const int4 sv = (&part[parity][0][0][0])[v * NT + lane];
+                        Si[0] += sv.x; Si[1] += sv.y; Si[2] += sv.z; Si[3] += sv.w;
                     }
+                }
+                const int cnt_i = __float_as_int(lane_read(kp.bp_row + 4 * G::CQ, __int_as_float(Si[G::CI])));
+                float S4[4];
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4) {
+                    const bool is_count = kp.tq == G::CQ && c4 == G::CI;
+                    S4[c4] = is_count ? (float)cnt_i
+                                      : (kp.tv[c4] ? (float)fx_unbias((unsigned)Si[c4], (unsigned)cnt_i) * inv4[c4] : 0.0f);
                 }
                 parity ^= 1;
                 kp.template finish<(NW > 1)>(p, i, round, S4, merge_point, send_point, det, sync_now, wave == 0);
@@ -1133,15 +1124,15 @@ hipError_t launch_shape(const StepParams &p, long long t0, long long t1, hipStre
     return launch_variant<K, D, 2, NW, RS>(p, t0, t1, s, persistent);
 }
 
-// Steps [t0, t1) of a K x D state.  Shape of a worker: two waves sharing accumulator rows pairwise (default: 8 waves
-// per CU with one worker per 4 SIMD slots), one wave with shared rows (many workers: twice as many resident), or one
-// wave with private rows (ALL: built for the streaming workload's own shape only, the others take shared rows).
+// Steps [t0, t1) of a K x D state.  Shape of a worker: two waves whose lanes share accumulator cells pairwise (default: 8
+// waves per CU with one worker per 4 SIMD slots), one wave with shared cells (many workers: twice as many resident), or
+// one wave with private cells (ALL: built for the streaming workload's own shape only, the others take shared cells).
 // tune: bits 2-3 pick the shape, bits 0-1 limit the ring depth (1: 4, 2: 2); the value 3 in bits 0-1 is handled by
 // the caller (one launch per round).
 template <int K, int D, bool ALL>
 hipError_t launch_small_kd(const StepParams &p, long long t0, long long t1, hipStream_t s, bool persistent)
 {
-    int shape = (p.tune >> 2) & 3;          // 0 = by number of workers, 1 = 1 wave private rows, 2 = 1 wave shared rows, 3 = 2 waves
+    int shape = (p.tune >> 2) & 3;          // 0 = by number of workers, 1 = 1 wave private cells, 2 = 1 wave shared cells, 3 = 2 waves
     if (shape == 0) shape = p.W > 1024 ? 2 : 3;
     if (!ALL && shape == 1) shape = 2;
     const int nw = shape == 3 ? 2 : 1;
