@@ -114,6 +114,36 @@ def test_small_kernel_ragged(B, oracle):
         run_both(B, oracle, X, 10, 4, b, 0.05, 3, 11, kernel=2)
 
 
+@pytest.mark.parametrize("b", [1, 5, 200, 1000])
+@pytest.mark.parametrize("kernel,tune", [(2, 0), (2, 4), (2, 8), (1, 0)])
+def test_small_kernel_column_ranges(B, oracle, kernel, tune, b):
+    # The streaming kernel sums the gradient in fixed point with one power-of-two scale per column, taken from the
+    # column's largest magnitude: columns of very different size, a column of zeros, a column far from the origin and
+    # a column that is negative throughout each have to come out as exact as an ordinary one, whatever the mini-batch
+    # size (which bounds the scale from the other side).  Every column is checked on its own: in the norm of the whole
+    # state the small ones would not show.
+    X = make_data(4 * 3000, 10, 10, seed=17 + b)
+    X = X * np.array([1e-6, 1e-3, 1.0, 1.0, 1.0, 1.0, 1e2, 3e3, 0.0, 1.0], dtype=np.float32)
+    X[:, 4] += np.float32(1000.0)
+    X[:, 5] = -np.abs(X[:, 5]) - np.float32(2.0)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    steps = 11 if b > 5 else 60
+    # (initial centroids that no mini-batch of the run contains: a worker's default start, its own first k samples,
+    # makes the first mini-batches of b = 1 coincide with their centroids, G = 0 and Eq. 4 an exact tie, which the
+    # fixed-point sums decide by rounding - the oracle counts those as Parzen near-ties)
+    w0 = X[5000:5010].astype(np.float64)
+    g, o = run_both(B, oracle, X, 10, 4, b, 0.05, 3, steps, kernel=kernel, tune=tune, check_qe=False, w0=w0)
+    wg = np.asarray(g.get_state(), dtype=np.float64)
+    wo = np.asarray(o.w, dtype=np.float64)
+    assert np.all(wg[:, :, 8] == 0.0)
+    for j in range(10):
+        if j == 8:
+            continue
+        num = np.linalg.norm((wg - wo)[:, :, j].reshape(4, -1), axis=1)
+        den = np.linalg.norm(wo[:, :, j].reshape(4, -1), axis=1)
+        assert np.all(num <= TOL * den), (j, num / den)
+
+
 @pytest.mark.parametrize("k,d", [(4, 4), (8, 8), (8, 16), (16, 8), (16, 12)])
 @pytest.mark.parametrize("W,b,E,buffers,parts,tune", [
     (6, 200, 2, 1, 1, 0),        # two waves per worker
