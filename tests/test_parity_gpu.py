@@ -294,6 +294,34 @@ def test_matrix_core_kernel_fused_sums(B, oracle, k, d, W, b, E, steps, N, weigh
     assert np.array_equal(g.worker_counters(), again.worker_counters())
 
 
+@pytest.mark.parametrize("b", [7, 100, 600])
+@pytest.mark.parametrize("tune", [2, 32, 0])
+def test_matrix_core_kernel_column_ranges(B, oracle, tune, b):
+    # like test_small_kernel_column_ranges, for the variants of the matrix-core kernel with fixed-point gradient sums
+    # (2: second pass, 32: tile by tile) and the one that sums in fp32 (0, eight waves): columns of very different
+    # size, a zero column, a column far from the origin, a negative one; every column checked on its own
+    k, d, W = 40, 20, 4
+    X = make_data(W * 3000, d, k, seed=31 + b)
+    scale = np.ones(d, dtype=np.float32)
+    scale[[0, 1, 6, 7, 8, 13]] = [1e-6, 1e-3, 1e2, 3e3, 0.0, 1e-2]
+    X = X * scale
+    X[:, 4] += np.float32(1000.0)
+    X[:, 5] = -np.abs(X[:, 5]) - np.float32(2.0)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    w0 = X[5000:5000 + k].astype(np.float64)
+    g, o = run_both(B, oracle, X, k, W, b, 0.05, 3, 11 if b > 7 else 40, kernel=3, tune=tune, check_qe=False, w0=w0)
+    assert g.stats().kernel == 3
+    wg = np.asarray(g.get_state(), dtype=np.float64)
+    wo = np.asarray(o.w, dtype=np.float64)
+    assert np.all(wg[:, :, 8] == 0.0)
+    for j in range(d):
+        if j == 8:
+            continue
+        num = np.linalg.norm((wg - wo)[:, :, j].reshape(W, -1), axis=1)
+        den = np.linalg.norm(wo[:, :, j].reshape(W, -1), axis=1)
+        assert np.all(num <= TOL * den), (j, num / den)
+
+
 @pytest.mark.parametrize("k,d", [(12, 8), (5, 4), (20, 32)])
 def test_automatic_choice_prefers_the_matrix_core_kernel(B, oracle, k, d):
     # shapes the streaming kernel is not built for, with rows the matrix-core kernel can take (d % 4 = 0)
