@@ -1,5 +1,6 @@
-// Fixed-point gradient sums of the matrix-core kernel (Eq. 9: the sum of the samples assigned to a centroid), in one
-// place: the kernel and a host-only check (tests/host/check_fixed_point_sums.cpp, plain C++ compiler) use these.
+// Fixed-point gradient sums of the streaming and the matrix-core kernel (Eq. 9: the sum of the samples assigned to a
+// centroid), in one place: the kernels and a host-only check (tests/host/check_fixed_point_sums.cpp, plain C++
+// compiler) use these.
 //
 // A column j of the samples gets a power-of-two scale; a term x * scale is rounded to an integer and added to a 32-bit
 // cell with an integer atomic.  Integer addition is associative, so the sum does not depend on the order of the
