@@ -853,6 +853,11 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     }
     const unsigned wave_cells = (unsigned)(size_t)(lds_u32_ptr)&acc[wave][0][0][0];
     const unsigned lane_cell = wave_cells + (unsigned)(lane % RL) * 4u;
+    unsigned scratch_cell = lane_cell + (unsigned)K * CENT_BYTES;
+    // (opaque to the compiler, which would otherwise select between the two products and add lane_cell afterwards:
+    // three instructions per group instead of a multiply-add and a select)
+    asm volatile("" : "+v"(scratch_cell));
+    const int lane_room = b - wave * 64 - lane;     // group m of this wave holds a sample for this lane iff m NW 64 < lane_room
 
     int rechecks = 0;
     int parity = 0;
@@ -968,14 +973,14 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                                                     reinterpret_cast<const char *>(u == 0 ? xb : pbase) + min(off, max_off)));
                         }
 
-                        const int n = (wave + m * NW) * 64 + lane;
-                        const bool valid = n < b;
+                        // sample (wave + m NW) 64 + lane of the mini-batch exists: a scalar against a per-lane constant
+                        const bool valid = (m * NW) * 64 < lane_room;
                         const int arg = decide<K, D>(tk, best, second, xc, valid, thr, wsf, rechecks);
-                        if (dump && valid) dump[n] = arg;
+                        if (dump && valid) dump[(wave + m * NW) * 64 + lane] = arg;
 
                         // this group's row update: D fixed-point terms and a one for the count, added to the lane's
                         // cells of the centroid (masked lanes: the scratch row)
-                        const unsigned cell = lane_cell + __umul24((unsigned)(valid ? arg : K), CENT_BYTES);
+                        const unsigned cell = valid ? (__umul24((unsigned)arg, CENT_BYTES) + lane_cell) : scratch_cell;
 #pragma unroll
                         for (int j = 0; j < D; ++j) lds_add_u32(cell + (unsigned)j * ELEM_BYTES, fx_term_bits(xc[j], scl[j]));
                         lds_add_u32(cell + (unsigned)D * ELEM_BYTES, 1u);
