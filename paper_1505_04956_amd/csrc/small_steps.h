@@ -988,6 +988,9 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     kp.settle_fetched();
                     m0 += PF;
                 } while (m0 < ngw);
+                // the part of the step that does not stream is on the worker's critical path: it goes first on its SIMD
+                // until the next step sets the streaming priority again
+                __builtin_amdgcn_s_setprio(3);
                 phase_fence();      // a wave sums its own cells: its atomics have to be done
 
                 // ---- sum the copies of every cell, clear them ----
