@@ -802,17 +802,20 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             int *cell0 = fxsum + myc;
             const int nfull = b / R;                             // sweeps with R valid rows
             const int nsweep = (b + R - 1) / R;
+            // (the full sweeps are taken from the end of the mini-batch to its start: the rows that the assignment
+            // read last are the ones most likely to be in a cache still; integer sums do not depend on the order)
+            auto place = [&](int sw) { return sw < nfull ? nfull - 1 - sw : sw; };
             auto fetch = [&](float4(&v)[SU], int s0) {
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int sw = s0 + u;
+                    const int sw = place(s0 + u);
                     v[u] = xq[(sw * R + myr < b ? (unsigned)sw : 0u) * sweep4];
                 }
             };
             auto add = [&](auto guard, const float4(&v)[SU], int s0) {
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int n = (s0 + u) * R + myr;
+                    const int n = place(s0 + u) * R + myr;
                     if (!decltype(guard)::value || n < b) {
                         int *cell = cell0 + (int)idx[n] * DP8;
                         atomicAdd(cell, (int)fx_term_bits(v[u].x, s4.x));
