@@ -85,7 +85,7 @@ def test_config0_full(B, oracle, kernel):
     assert o.counters[:, 2].sum() > 0                          # merges really happened
 
 
-@pytest.mark.parametrize("tune", [1, 2, 4, 5, 6, 8, 9, 12])   # ring depths x worker shapes (waves, row sharing)
+@pytest.mark.parametrize("tune", [1, 2, 4, 5, 6, 8, 9, 12])   # ring depths x worker shapes (waves, sharing of accumulator cells)
 def test_small_kernel_variants(B, oracle, tune):
     X = make_data(8 * 4000, 10, 10, seed=5)
     run_both(B, oracle, X, 10, 8, 1000, 0.05, 2, 9, kernel=2, tune=tune)
@@ -384,7 +384,7 @@ def test_matrix_core_kernel_one_launch(B, oracle, tune):
     (2, 0, 10, 10, 6, 100, 2, 13, 2, True, 0.0),        # small-state kernel, two waves per worker, one launch
     (2, 0, 10, 10, 9, 500, 1, 12, 4, True, 0.3),
     (2, 0, 10, 10, 7, 130, 3, 14, 3, False, 0.0),
-    (2, 8, 10, 10, 6, 100, 2, 13, 2, True, 0.2),        # one wave per worker, shared rows
+    (2, 8, 10, 10, 6, 100, 2, 13, 2, True, 0.2),        # one wave per worker, shared accumulator cells
     (2, 3, 10, 10, 6, 256, 2, 13, 4, True, 0.0),        # one launch per round
     (1, 0, 7, 5, 5, 64, 1, 9, 4, True, 0.3),
     (1, 0, 12, 9, 6, 50, 3, 14, 3, False, 0.0),
@@ -410,7 +410,7 @@ def test_n_external_buffers(B, oracle, kernel, tune, k, d, W, b, E, steps, buffe
     (2, 0, 10, 10, 6, 100, 2, 13, 1, 2, True, 0.0),      # small-state kernel, two waves per worker, one launch
     (2, 0, 10, 10, 9, 500, 1, 12, 3, 10, True, 0.3),     # one row per message
     (2, 0, 10, 10, 7, 130, 3, 14, 2, 3, False, 0.0),
-    (2, 8, 10, 10, 6, 100, 2, 13, 4, 5, True, 0.2),      # one wave per worker, shared rows
+    (2, 8, 10, 10, 6, 100, 2, 13, 4, 5, True, 0.2),      # one wave per worker, shared accumulator cells
     (2, 3, 10, 10, 6, 256, 2, 13, 2, 4, True, 0.0),      # one launch per round
     (1, 0, 7, 5, 5, 64, 1, 9, 3, 7, True, 0.3),          # one row per message
     (1, 0, 12, 9, 6, 50, 3, 14, 2, 5, False, 0.0),
