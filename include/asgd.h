@@ -114,7 +114,7 @@ enum { ASGD_KERNEL_AUTO = 0, ASGD_KERNEL_GENERIC = 1, ASGD_KERNEL_SMALL = 2, ASG
 typedef struct asgd_stats {
     int64_t steps;            /* value of the step counter t */
     int64_t samples;          /* samples processed so far = t * W * b */
-    int64_t sent;             /* messages written, summed over workers (Alg. 5 line 9) */
+    int64_t sent;             /* messages written, summed over workers (Alg. 5, send) */
     int64_t received;         /* messages found in a buffer and tested with Eq. 4 */
     int64_t accepted;         /* of those, messages with delta = 1 ("good" messages, Sec. 5.4) */
     int64_t parzen_near_ties; /* tested messages with |lhs - rhs| / rhs < 1e-6 in Eq. 4 */
@@ -162,7 +162,7 @@ int asgd_set_state(asgd_ctx *ctx, int worker, const float *w_host);
 
 /* Set the step counter t (>= 0) when continuing an earlier run.  Exchange buffers are
    emptied: at a multiple of E the messages of the round just finished are in flight
-   (Alg. 5: sent in line 9 of one step, looked at in line 5 of the next), so a run resumed
+   (Alg. 5: sent at the end of one step, looked at in the merge of the next), so a run resumed
    there equals the uninterrupted one only if asgd_set_exchange() hands them over too. */
 int asgd_set_step(asgd_ctx *ctx, int64_t t);
 
@@ -194,8 +194,8 @@ int asgd_set_exchange(asgd_ctx *ctx, const float *values_host, const int32_t *ro
  * worker, mini-batch s of an epoch being rows [s*b, (s+1)*b) of the shard (the tail
  * H mod b is skipped).  A step = assignment s_i(w) (Sec. 5.1), gradient (Eq. 9 with
  * m' = b), merge of a buffered external state when t > 0 and t mod E == 0 (Eq. 4,
- * Eq. 7), update w <- w - eps * step (Alg. 5 line 8) and, when (t+1) mod E == 0, the
- * send of the new state to one other worker (Alg. 5 line 9).  Returns after the work
+ * Eq. 7), update w <- w - eps * step (Alg. 5, update) and, when (t+1) mod E == 0, the
+ * send of the new state to one other worker (Alg. 5, send).  Returns after the work
  * has finished on the device.  The result does not depend on how a run is cut into
  * calls (deterministic mode: bit for bit), the time does: where all workers fit the
  * device at once, a call is ONE kernel launch for every 1024 communication rounds it
@@ -217,7 +217,7 @@ int asgd_set_assign_dump(asgd_ctx *ctx, int32_t *assign_dev, size_t capacity);
 
 /*
  * Copy states to host memory.  worker >= 0: that worker's k*d floats (worker 0 is the
- * result Alg. 5 line 11 returns); worker = -1: all W states, W*k*d floats.
+ * result Alg. 5, return returns); worker = -1: all W states, W*k*d floats.
  * out_bytes must be at least the size copied.
  */
 int asgd_get_state(asgd_ctx *ctx, int worker, float *out_host, size_t out_bytes);

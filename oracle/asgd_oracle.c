@@ -18,8 +18,8 @@
  *   mini-batch gradient with 1/m', m' = b ................... Eq. 9, Alg. 4
  *   Parzen window delta(i,j) ................................ Eq. 4
  *   gated merge of one external state ....................... Eq. 7 (Eq. 5 with mini-batches)
- *   update w <- w - eps * merged step ....................... Alg. 5 line 8, Fig. 4 stage IV
- *   send of the new state to one other worker ............... Alg. 5 line 9, Fig. 2 stage I
+ *   update w <- w - eps * merged step ....................... Alg. 5, update, Fig. 4 stage IV
+ *   send of the new state to one other worker ............... Alg. 5, send, Fig. 2 stage I
  *   empty external buffer <=> zero norm ..................... Eq. 3 (lambda)
  *   merge of N external buffers, each gated on its own ...... Eq. 3 (no gate), Eq. 6 (gated)
  *   partial messages, partitioned along the cluster centres . Sec. 4.4 (data races and sparsity)
@@ -29,8 +29,8 @@
  * reason in the design notes of the repository):
  *   - sign: the step is a descent step on E(w), i.e. the gradient for centroid k is
  *     (1/b) * sum_{assigned i} (w_k - x_i), so that w - eps*gradient moves centroids
- *     towards their samples (Eq. 9 prints the opposite sign of Alg. 5 line 8);
- *   - the gradient is taken at the state the mini-batch started with (Alg. 4 line 5);
+ *     towards their samples (Eq. 9 prints the opposite sign of Alg. 5, update);
+ *   - the gradient is taken at the state the mini-batch started with (Alg. 4, gradient step);
  *   - mini-batch s of an epoch is rows [s*b, (s+1)*b) of the worker's shard, the
  *     shard tail H mod b is not visited, the order repeats every epoch;
  *   - a state is sent after every E-th mini-batch (E = 1 is Alg. 5 as printed,
@@ -271,7 +271,7 @@ static int worker_step(const float *M, int b, int k, int d, double eps, int lr_m
             ndelta += delta[n];
         }
         flags |= ndelta;
-        /* Eq. 6 (one buffer: Eq. 7; gate off: Eq. 3) with the mini-batch gradient, then Alg. 5 line 8. */
+        /* Eq. 6 (one buffer: Eq. 7; gate off: Eq. 3) with the mini-batch gradient, then Alg. 5, update. */
         for (size_t e = 0; e < kd; ++e) {
             double Gbar = G[e];
             if (ndelta > 0) {
@@ -316,7 +316,7 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
                       double *gap_out)
 {
     if (k < 1 || d < 1 || W < 1 || b < 1 || !(eps > 0.0) || E < 0) return -1;
-    const int64_t H = N / W;           /* Alg. 5 line 1 */
+    const int64_t H = N / W;           /* Alg. 5, partition of the data */
     const int64_t S = H / b;           /* full mini-batches per epoch */
     if (H < k || S < 1) return -1;
     if (lr_mode == 1 && E != 0) return -1;
@@ -368,7 +368,7 @@ int asgd_oracle_steps(const float *X, int64_t N, int k, int d, int W, int b, dou
             for (size_t q = 0; q < (size_t)nb * W; ++q) slot_stamp[q] = -1;
         }
         memcpy(w, wnew, (size_t)W * kd * sizeof(double));
-        if (E > 0 && W > 1 && (t + 1) % E == 0) {       /* Alg. 5 line 9 */
+        if (E > 0 && W > 1 && (t + 1) % E == 0) {       /* Alg. 5, send */
             const int64_t r = t / E;
             for (int i = 0; i < W; ++i) {
                 counters[i * 3 + 0] += 1;

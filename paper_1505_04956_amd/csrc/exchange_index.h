@@ -29,7 +29,7 @@ ASGD_HD inline uint64_t round_hash(uint64_t seed, int64_t r)
     return mix64(seed + 0x9E3779B97F4A7C15ULL * (uint64_t)(r + 1));
 }
 // Deterministic schedule: one cyclic shift per round and copy, shared by all senders, so that every
-// worker receives exactly one message per round in each of its buffers (Alg. 5 line 9 asks only for
+// worker receives exactly one message per round in each of its buffers (Alg. 5, send asks only for
 // "a random node other than i").  Copy n of a message (0 <= n < number of buffers < W) goes into the
 // recipient's buffer n; the shifts of one round differ, so a worker's senders differ.
 ASGD_HD inline int shift_deterministic(uint64_t seed, int64_t r, int W, int n = 0)

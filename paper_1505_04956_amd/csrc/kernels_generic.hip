@@ -149,7 +149,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         for (size_t e = tid; e < kd; e += GEN_THREADS) sp[e] = 0.0f;
         for (int c = tid; c < k; c += GEN_THREADS) cntp[c] = 0;
 
-        // ---- assignment under the state the step started with (Alg. 4 line 5) ----
+        // ---- assignment under the state the step started with (Alg. 4, gradient step) ----
         for (int n = tid; n < b; n += GEN_THREADS) {
             const float *xr = xb + (size_t)n * d;
             float best = INFINITY, second = INFINITY;
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
                 }
             }
         }
-        // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
+        // Eq. 6 (one buffer: Eq. 7) and Alg. 5, update
         const float inv = 1.0f / (float)(ndelta + 1);
         for (size_t e = tid; p.parts == 1 && e < kd; e += GEN_THREADS) {
             float step = sp[e];
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(GEN_THREADS) void generic_steps_kernel(StepParams p
         }
         __syncthreads();
 
-        // ---- send (Alg. 5 line 9) ----
+        // ---- send (Alg. 5, send) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
             const long long r = t / p.E;
             for (int n = 0; n < p.nb; ++n) {

@@ -1253,7 +1253,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             __syncthreads();                          // red_d is written again for the next buffer
         }
-        // ---- update: Eq. 6 (one buffer: Eq. 7), Alg. 5 line 8; new offsets h_c and max |w_c|^2 ----
+        // ---- update: Eq. 6 (one buffer: Eq. 7), Alg. 5, update; new offsets h_c and max |w_c|^2 ----
         {
             const int delta = delta_mask != 0;
             const int first = delta ? __builtin_ctz(delta_mask) : 0;
@@ -1315,7 +1315,7 @@ __global__ __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (sync && merge_point && tid == 0)
             __hip_atomic_store(p.consumed + i, (int)r_now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-        // ---- send (Alg. 5 line 9) ----
+        // ---- send (Alg. 5, send) ----
         if (p.E > 0 && p.W > 1 && ((t + 1) % p.E) == 0) {
             const long long r = t / p.E;
             for (int n = 0; n < p.nb; ++n) {

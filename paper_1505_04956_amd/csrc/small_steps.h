@@ -366,7 +366,7 @@ struct SmallWalk {
 };
 
 // What a wave that holds a worker's state does in a step besides streaming: the wave-uniform copies of the state, the
-// early fetch of the messages, gradient, merge (Eq. 4, Eq. 6 / Eq. 7), update (Alg. 5 line 8), send (Alg. 5 line 9).
+// early fetch of the messages, gradient, merge (Eq. 4, Eq. 6 / Eq. 7), update (Alg. 5, update), send (Alg. 5, send).
 //
 // State layout in registers ("task layout"): lane l < NT = K*NQ holds the four elements (c, 4q .. 4q+3) of the state
 // with c = l / NQ, q = l % NQ (elements past d do not exist and stay 0); the same lane receives the totals of the
@@ -703,7 +703,7 @@ struct SmallKeeper {
             }
         }
 
-        // Eq. 6 (one buffer: Eq. 7) and Alg. 5 line 8
+        // Eq. 6 (one buffer: Eq. 7) and Alg. 5, update
         {
             const bool half = (NB == 1) && !(PARTS && p.parts > 1);
             const float inv_n = half ? 0.5f : 1.0f / (float)(ndelta + 1);
@@ -715,7 +715,7 @@ struct SmallKeeper {
             }
         }
 
-        // ---- send (Alg. 5 line 9) ----
+        // ---- send (Alg. 5, send) ----
         if (send_point && sender) {
 #pragma unroll
             for (int n = 0; n < NB; ++n) {

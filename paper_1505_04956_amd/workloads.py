@@ -37,7 +37,7 @@ class Workload:
     schedule_seed: int = 1
 
     @property
-    def H(self) -> int:          # shard length, Alg. 5 line 1
+    def H(self) -> int:          # shard length, Alg. 5, partition of the data
         return self.N // self.W
 
     @property

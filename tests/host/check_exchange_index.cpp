@@ -42,7 +42,7 @@ int main(int argc, char **argv)
             std::fill(hits.begin(), hits.end(), 0);
             for (int i = 0; i < W; ++i)
                 for (int n = 0; n < nb; ++n) {
-                    // ---- sender side (Alg. 5 line 9) ----
+                    // ---- sender side (Alg. 5, send) ----
                     const int peer = free_mode ? peer_free(seed, r, i, W, n) : peer_deterministic(seed, r, i, W, n);
                     REQUIRE(peer >= 0 && peer < W && peer != i, "peer %d of worker %d round %lld copy %d", peer, i, r, n);
                     const size_t buf = exchange_buffer(spar, nb, n, W, peer);

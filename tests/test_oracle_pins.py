@@ -540,7 +540,7 @@ def test_peer_schedule(oracle):
                 p = [oracle.peer(seed, r, i, W) for i in range(W)]
                 assert p == [py_peer(seed, r, i, W) for i in range(W)]
                 assert sorted(p) == list(range(W))                 # everyone receives exactly once
-                assert all(p[i] != i for i in range(W))            # never to oneself (Alg. 5 line 9)
+                assert all(p[i] != i for i in range(W))            # never to oneself (Alg. 5, send)
     shifts = {oracle.peer(9, r, 0, 64) for r in range(200)}
     assert len(shifts) > 30                                        # rounds use different shifts
 
