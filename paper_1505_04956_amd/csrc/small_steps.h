@@ -17,7 +17,8 @@
 //     lane pair l, l+32 (RS = 2): a sample adds its d values, each scaled by its column's power of two and rounded
 //     to an integer, and a one for the count to the cells of its centroid with d + 1 LDS atomics that return
 //     nothing.  Lanes past the end of a mini-batch use a scratch centroid.  Once per step the copies of every cell
-//     are summed and cleared.
+//     are summed; the cells are never cleared, a step's sums are the totals now minus the totals a step ago,
+//     modulo 2^32.
 // The part of a step that does not stream (row sums, totals, update, the new wave-uniform copies) is
 // on every worker's critical path, once per mini-batch; it is written for few instructions: all step
 // bookkeeping is 32-bit and scalar, the state lives in registers in the layout the row sums come out
@@ -283,12 +284,12 @@ __device__ __forceinline__ void lds_add_u32(unsigned addr, unsigned v)
 {
     (void)__hip_atomic_fetch_add((lds_u32_ptr)(size_t)addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-// Sums and clears the cells of elements 4q .. 4q+3 of one centroid over ROWS copies: `cells` is the LDS byte address of
+// Sums the cells of elements 4q .. 4q+3 of one centroid over ROWS copies (they are not cleared, see the caller): `cells` is the LDS byte address of
 // copy 0 of element 4q (a multiple of ROWS * 4), elem_bytes the distance between elements.  Four copies are read at a
 // time; block rb of the visit is block rb ^ (task mod ROWS/4), so that the lanes of one access do not all hit the same
 // banks, and its address is ONE exclusive-or away from the first (no add, mask and shift per block).
 template <int ROWS>
-__device__ __forceinline__ void sum_and_clear_cells(unsigned cells, unsigned elem_bytes, int task, int (&s)[4])
+__device__ __forceinline__ void sum_cells(unsigned cells, unsigned elem_bytes, int task, int (&s)[4])
 {
     static_assert(ROWS % 4 == 0 && ((ROWS / 4) & (ROWS / 4 - 1)) == 0, "blocks of four copies, rotated by exclusive-or");
     unsigned first = cells + ((unsigned)(task & (ROWS / 4 - 1)) << 4);
@@ -303,7 +304,6 @@ __device__ __forceinline__ void sum_and_clear_cells(unsigned cells, unsigned ele
         for (int rb = 0; rb < ROWS / 4; ++rb) {
             lds_ivec4_ptr q = (lds_ivec4_ptr)(size_t)((first ^ (unsigned)(rb << 4)) + (unsigned)c4 * elem_bytes);
             const lds_ivec4 v = *q;
-            *q = zero;
             t = rb == 0 ? v : t + v;
         }
         s[c4] = (t.x + t.y) + (t.z + t.w);
@@ -805,7 +805,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
     // acc[wave][c][j][r]: copy r (lane r; RS = 2: lanes r and r + 32) of the fixed-point sum of element j of the samples
     // of centroid c, j = D: their count, j > D: unused; row K is scratch for masked lanes
-    __shared__ __align__(1024) unsigned acc[NW][K + 1][4 * NQ][RL];      // (alignment: see sum_and_clear_cells)
+    __shared__ __align__(1024) unsigned acc[NW][K + 1][4 * NQ][RL];      // (alignment: see sum_cells)
     __shared__ float4 wst[NW][NT];                  // state, rows padded to RW floats; one copy per wave
     __shared__ float4 wdt[NW][NT];                  // row k: w_k - w_0 in elements < D, (h_k - h_0) + 1 in element D
     __shared__ int4 part[2][NW][NPART][NT];         // per-wave totals, double-buffered by step parity
@@ -861,6 +861,11 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
     int rechecks = 0;
     int parity = 0;
+    // totals of this lane's four elements over all copies after the previous step: in registers, or, where a centroid
+    // has a padding element (d + 1 not a multiple of four), in the cells of that element, which start at zero like the rest
+    constexpr bool PAD_CELLS = (D + 1) % 4 != 0 && RL >= 4 * NQ;
+    int Si_before[4] = {0, 0, 0, 0};
+    const unsigned before_cell = wave_cells + (unsigned)kp.tc * CENT_BYTES + (unsigned)(4 * NQ - 1) * ELEM_BYTES + (unsigned)kp.tq * 16u;
     SmallWalk wk(p, t0, t1);
 
     // ring of sample buffers: buffer u holds this wave's group m with m % PF == u
@@ -993,14 +998,14 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 __builtin_amdgcn_s_setprio(3);
                 phase_fence();      // a wave sums its own cells: its atomics have to be done
 
-                // ---- sum the copies of every cell, clear them ----
+                // ---- sum the copies of every cell ----
                 // lane = (part, task): task = four elements of a centroid (centroid, float4 number); part = its share of
                 // the copies
                 {
                     const int task = lane % NT, prt = lane / NT;
                     if (prt < NPART) {
                         int si[4];
-                        sum_and_clear_cells<RPP>(wave_cells + (unsigned)(task / NQ) * CENT_BYTES +
+                        sum_cells<RPP>(wave_cells + (unsigned)(task / NQ) * CENT_BYTES +
                                                      (unsigned)(4 * (task % NQ)) * ELEM_BYTES + (unsigned)(prt * RPP) * 4u,
                                                  ELEM_BYTES, task, si);
                         part[parity][wave][prt][task] = make_int4(si[0], si[1], si[2], si[3]);
@@ -1016,6 +1021,27 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     for (int v = 0; v < NW * NPART; ++v) {
                         const int4 sv = (&part[parity][0][0][0])[v * NT + lane];
                         Si[0] += sv.x; Si[1] += sv.y; Si[2] += sv.z; Si[3] += sv.w;
+                    }
+                }
+                // the cells are never cleared: they run on, modulo 2^32, and a step's sums are the totals now minus the
+                // totals a step ago (exact, since a step's sums are below 2^30 in magnitude)
+                if constexpr (PAD_CELLS) {
+                    // (the totals a step ago wait in cells that no sample touches: copies 4q .. 4q+3 of the padding
+                    // element of the lane's centroid; every wave keeps its own, the values are the same)
+                    if (kp.has_task) {
+                        const lds_ivec4_ptr bq = (lds_ivec4_ptr)(size_t)before_cell;
+                        const lds_ivec4 bv = *bq;
+                        const lds_ivec4 nv = {Si[0], Si[1], Si[2], Si[3]};
+                        *bq = nv;
+                        Si[0] = (int)((unsigned)Si[0] - (unsigned)bv.x); Si[1] = (int)((unsigned)Si[1] - (unsigned)bv.y);
+                        Si[2] = (int)((unsigned)Si[2] - (unsigned)bv.z); Si[3] = (int)((unsigned)Si[3] - (unsigned)bv.w);
+                    }
+                } else {
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        const int now = Si[c4];
+                        Si[c4] = (int)((unsigned)now - (unsigned)Si_before[c4]);
+                        Si_before[c4] = now;
                     }
                 }
                 const int cnt_i = __float_as_int(lane_read(kp.bp_row + 4 * G::CQ, __int_as_float(Si[G::CI])));
