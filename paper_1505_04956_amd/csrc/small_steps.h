@@ -13,8 +13,8 @@
 //     of a network of three-input max/median instructions; when they are closer than a rigorous
 //     bound on the fp32 rounding error (packing included), the lane decides exactly in fp64, so the
 //     assignment is the exact-arithmetic nearest centroid of the fp32 state;
-//   - the gradient sums of Eq. 9 are kept in LDS as 32-bit fixed-point cells, one copy per lane (RS = 1) or per
-//     lane pair l, l+32 (RS = 2): a sample adds its d values, each scaled by its column's power of two and rounded
+//   - the gradient sums of Eq. 9 are kept in LDS as 32-bit fixed-point cells, one copy per lane (RS = 1) or sixteen
+//     copies per wave, one for the lanes l, l+16, l+32, l+48 (RS = 2): a sample adds its d values, each scaled by its column's power of two and rounded
 //     to an integer, and a one for the count to the cells of its centroid with d + 1 LDS atomics that return
 //     nothing.  Lanes past the end of a mini-batch use a scratch centroid.  Once per step the copies of every cell
 //     are summed; the cells are never cleared, a step's sums are the totals now minus the totals a step ago,
@@ -272,7 +272,8 @@ __device__ __forceinline__ int decide(const float (&tk)[K], float best, float se
 }
 
 // Row updates: the accumulator of a wave holds 32-bit fixed-point sums (fixed_point_sums.h), element-major - cell
-// (centroid c, element j, copy r) lies at ((c * 4 NQ + j) * RL + r) * 4 bytes, element D being the count -, and a sample
+// (centroid c, element j, copy r) lies at ((c * CE + j) * RL + r) * 4 bytes, element D being the count and CE = D + 1 or
+// D + 2, whichever is odd -, and a sample
 // adds its D terms and a one for the count with D + 1 LDS atomics that return nothing.  The lanes of one such instruction
 // (same j, consecutive r) fall into consecutive banks; there is no read-modify-write chain through LDS and no exchange
 // of operands between lanes that share a copy, and because integer addition does not depend on the order, the sums
@@ -744,8 +745,9 @@ struct SmallKeeper {
 
 // Steps [t0, t1) of the workers blockIdx.x, blockIdx.x + gridDim.x, ..., with NW like waves per worker: wave v takes
 // the groups v, v+NW, ... of every mini-batch from the loads to the accumulator cells, and every wave holds the state.
-//   RS   lanes sharing a copy of the accumulator cells: 1 = every lane has its own (64 copies per wave); 2 = lanes l and
-//        l+32 share one, which halves the LDS per wave so that twice as many waves are resident.
+//   RS   lanes sharing a copy of the accumulator cells: 1 = every lane has its own (64 copies per wave); 2 = sixteen
+//        copies per wave (32 for the shapes whose once-per-step sums need them), a quarter of the LDS and a quarter of the
+//        once-per-step sums; lanes that share a copy and hold samples of one centroid take turns in the LDS unit.
 //   sync = 0: the launch contains nothing a worker has to wait for (silent or free-running mode,
 //             or the host ends every launch at a multiple of E); one workgroup per worker.
 //   sync = 1: the whole run is one launch of co-resident workgroups.  A workgroup takes its workers
@@ -796,16 +798,25 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 {
     using G = SmallGeo<K, D>;
     constexpr int NQ = G::NQ, RW = G::RW, NT = G::NT, NPART = G::NPART;
-    constexpr int RL = 64 / RS;                     // copies of an accumulator cell per wave (lanes r and r + RL share one)
+    // copies of an accumulator cell per wave: one per lane, or sixteen (lanes r, r + 16, r + 32, r + 48 share one; 32 where
+    // the once-per-step sums need that many to give every lane of a task four)
+    constexpr int RL = RS == 1 ? 64 : (16 >= 4 * NPART ? 16 : 32);
+    // Elements per centroid in the accumulator: d sums and the count, one more if that makes the number odd - then the
+    // cells of neighbouring centroids start in different banks (with 16 copies: 48 banks on), and lanes that share a
+    // copy but hold samples of different centroids seldom collide.  The once-per-step sums read 4 NQ elements from a
+    // centroid's first, i.e. into the next centroid's cells, which is harmless: nothing is written there.
+    constexpr int CE = (D + 1) % 2 ? D + 1 : D + 2;
     constexpr int RPP = RL / NPART;                 // copies one lane sums in the reduction
     static_assert(NW == 1 || NW == 2, "one or two waves per worker");
-    static_assert(RS == 1 || RS == 2, "one copy per lane, or one per pair of lanes");
+    static_assert(RS == 1 || RS == 2, "one copy of the cells per lane, or shared copies");
     static_assert(PF >= 2, "the ring needs the previous group's buffer");
     static_assert(RL % NPART == 0 && RPP % 4 == 0, "state too large for this kernel");
 
-    // acc[wave][c][j][r]: copy r (lane r; RS = 2: lanes r and r + 32) of the fixed-point sum of element j of the samples
-    // of centroid c, j = D: their count, j > D: unused; row K is scratch for masked lanes
-    __shared__ __align__(1024) unsigned acc[NW][K + 1][4 * NQ][RL];      // (alignment: see sum_cells)
+    // acc[wave][c * CE + j][r]: copy r (lanes r, r + RL, ...) of the fixed-point sum of element j of the samples of
+    // centroid c, j = D: their count; centroid K is scratch for masked lanes; four elements of slack behind it for the
+    // reads of the once-per-step sums
+    __shared__ __align__(1024) unsigned acc[NW][(K + 1) * CE + 4][RL];      // (alignment: see sum_cells)
+    __shared__ int4 before[NW][NT];                 // totals of a task lane's four elements after the previous step
     __shared__ float4 wst[NW][NT];                  // state, rows padded to RW floats; one copy per wave
     __shared__ float4 wdt[NW][NT];                  // row k: w_k - w_0 in elements < D, (h_k - h_0) + 1 in element D
     __shared__ int4 part[2][NW][NPART][NT];         // per-wave totals, double-buffered by step parity
@@ -832,12 +843,13 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     // the budget of polls grows with the rounds the launch covers: a healthy run of the streaming workload spends up
     // to ~30 polls per round on the workgroup that waits most
     if (p.wait_polls <= 0 && p.E > 0) kp.budget += WAIT_PER_ROUND * (int)min((t1 - t0) / p.E + 1, (long long)(1 << 20));
-    for (int q = lane; q < (K + 1) * 4 * NQ * RL; q += 64) (&acc[wave][0][0][0])[q] = 0u;
+    for (int q = lane; q < ((K + 1) * CE + 4) * RL; q += 64) (&acc[wave][0][0])[q] = 0u;
+    if (lane < NT) before[wave][lane] = make_int4(0, 0, 0, 0);
 
     // Fixed-point sums: the scale of every column (2^e with b * max|x_j| * 2^e < 2^30 and max|x_j| * 2^e < 2^22; 0 for a
     // column of zeros), the inverse scales of this lane's four elements in the task layout (the count needs none),
     // and the LDS byte address of this lane's copy of element 0 of centroid 0
-    constexpr unsigned ELEM_BYTES = RL * 4u, CENT_BYTES = 4u * NQ * ELEM_BYTES;
+    constexpr unsigned ELEM_BYTES = RL * 4u, CENT_BYTES = (unsigned)CE * ELEM_BYTES;
     float scl[D], inv4[4];
 #pragma unroll
     for (int c4 = 0; c4 < 4; ++c4) inv4[c4] = 1.0f;
@@ -851,7 +863,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
         for (int c4 = 0; c4 < 4; ++c4)
             if (kp.has_task && 4 * kp.tq + c4 == j) inv4[c4] = iv;
     }
-    const unsigned wave_cells = (unsigned)(size_t)(lds_u32_ptr)&acc[wave][0][0][0];
+    const unsigned wave_cells = (unsigned)(size_t)(lds_u32_ptr)&acc[wave][0][0];
     const unsigned lane_cell = wave_cells + (unsigned)(lane % RL) * 4u;
     unsigned scratch_cell = lane_cell + (unsigned)K * CENT_BYTES;
     // (opaque to the compiler, which would otherwise select between the two products and add lane_cell afterwards:
@@ -861,11 +873,8 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
 
     int rechecks = 0;
     int parity = 0;
-    // totals of this lane's four elements over all copies after the previous step: in registers, or, where a centroid
-    // has a padding element (d + 1 not a multiple of four), in the cells of that element, which start at zero like the rest
-    constexpr bool PAD_CELLS = (D + 1) % 4 != 0 && RL >= 4 * NQ;
-    int Si_before[4] = {0, 0, 0, 0};
-    const unsigned before_cell = wave_cells + (unsigned)kp.tc * CENT_BYTES + (unsigned)(4 * NQ - 1) * ELEM_BYTES + (unsigned)kp.tq * 16u;
+    // LDS byte address of the totals of this lane's four elements over all copies after the previous step
+    const unsigned before_cell = (unsigned)(size_t)(lds_u32_ptr)(unsigned *)&before[wave][kp.has_task ? lane : 0];
     SmallWalk wk(p, t0, t1);
 
     // ring of sample buffers: buffer u holds this wave's group m with m % PF == u
@@ -1025,24 +1034,14 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                 }
                 // the cells are never cleared: they run on, modulo 2^32, and a step's sums are the totals now minus the
                 // totals a step ago (exact, since a step's sums are below 2^30 in magnitude)
-                if constexpr (PAD_CELLS) {
-                    // (the totals a step ago wait in cells that no sample touches: copies 4q .. 4q+3 of the padding
-                    // element of the lane's centroid; every wave keeps its own, the values are the same)
-                    if (kp.has_task) {
-                        const lds_ivec4_ptr bq = (lds_ivec4_ptr)(size_t)before_cell;
-                        const lds_ivec4 bv = *bq;
-                        const lds_ivec4 nv = {Si[0], Si[1], Si[2], Si[3]};
-                        *bq = nv;
-                        Si[0] = (int)((unsigned)Si[0] - (unsigned)bv.x); Si[1] = (int)((unsigned)Si[1] - (unsigned)bv.y);
-                        Si[2] = (int)((unsigned)Si[2] - (unsigned)bv.z); Si[3] = (int)((unsigned)Si[3] - (unsigned)bv.w);
-                    }
-                } else {
-#pragma unroll
-                    for (int c4 = 0; c4 < 4; ++c4) {
-                        const int now = Si[c4];
-                        Si[c4] = (int)((unsigned)now - (unsigned)Si_before[c4]);
-                        Si_before[c4] = now;
-                    }
+                // (every wave keeps its own copy of the totals a step ago, the values are the same)
+                if (kp.has_task) {
+                    const lds_ivec4_ptr bq = (lds_ivec4_ptr)(size_t)before_cell;
+                    const lds_ivec4 bv = *bq;
+                    const lds_ivec4 nv = {Si[0], Si[1], Si[2], Si[3]};
+                    *bq = nv;
+                    Si[0] = (int)((unsigned)Si[0] - (unsigned)bv.x); Si[1] = (int)((unsigned)Si[1] - (unsigned)bv.y);
+                    Si[2] = (int)((unsigned)Si[2] - (unsigned)bv.z); Si[3] = (int)((unsigned)Si[3] - (unsigned)bv.w);
                 }
                 const int cnt_i = __float_as_int(lane_read(kp.bp_row + 4 * G::CQ, __int_as_float(Si[G::CI])));
                 float S4[4];
@@ -1158,7 +1157,7 @@ hipError_t launch_shape(const StepParams &p, long long t0, long long t1, hipStre
     return launch_variant<K, D, 2, NW, RS>(p, t0, t1, s, persistent);
 }
 
-// Steps [t0, t1) of a K x D state.  Shape of a worker: two waves whose lanes share accumulator cells pairwise (default: 8
+// Steps [t0, t1) of a K x D state.  Shape of a worker: two waves with shared copies of the accumulator cells (default: 8
 // waves per CU with one worker per 4 SIMD slots), one wave with shared cells (many workers: twice as many resident), or
 // one wave with private cells (ALL: built for the streaming workload's own shape only, the others take shared cells).
 // tune: bits 2-3 pick the shape, bits 0-1 limit the ring depth (1: 4, 2: 2); the value 3 in bits 0-1 is handled by
