@@ -533,15 +533,14 @@ struct SmallKeeper {
         }
     }
 
-    // End of a step: S4 = totals of this lane's four elements of the gradient sums (the count of a centroid in
-    // component CI of float4 number CQ).  BAR: several waves hold the state and read the buffers, a workgroup barrier
+    // End of a step: S4 = totals of this lane's four elements of the gradient sums, cnt = the number of samples of the
+    // lane's centroid.  BAR: several waves hold the state and read the buffers, a workgroup barrier
     // separates their reads from the release of the buffers.  sender: this wave writes messages, state and counters.
     template <bool BAR>
-    __device__ __forceinline__ void finish(const StepParams &p, int i, int round, const float (&S4)[4], bool merge_point,
+    __device__ __forceinline__ void finish(const StepParams &p, int i, int round, const float (&S4)[4], float cnt, bool merge_point,
                                            bool send_point, bool det, int sync, bool sender)
     {
         const int W = p.W;
-        const float cnt = lane_read(bp_row + 4 * CQ, S4[CI]);
         float Gr[4], wesum[4];
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
@@ -852,7 +851,7 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
     constexpr unsigned ELEM_BYTES = RL * 4u, CENT_BYTES = (unsigned)CE * ELEM_BYTES;
     float scl[D], inv4[4];
 #pragma unroll
-    for (int c4 = 0; c4 < 4; ++c4) inv4[c4] = 1.0f;
+    for (int c4 = 0; c4 < 4; ++c4) inv4[c4] = 0.0f;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
         int e = 0;
@@ -1044,15 +1043,14 @@ void small_steps_kernel(StepParams p, long long t0, long long t1, int sync)
                     Si[2] = (int)((unsigned)Si[2] - (unsigned)bv.z); Si[3] = (int)((unsigned)Si[3] - (unsigned)bv.w);
                 }
                 const int cnt_i = __float_as_int(lane_read(kp.bp_row + 4 * G::CQ, __int_as_float(Si[G::CI])));
+                // (inv4 is zero where the lane has no column: no select for those)
                 float S4[4];
+                const unsigned bias_off = (unsigned)cnt_i * FX_BIAS;
 #pragma unroll
-                for (int c4 = 0; c4 < 4; ++c4) {
-                    const bool is_count = kp.tq == G::CQ && c4 == G::CI;
-                    S4[c4] = is_count ? (float)cnt_i
-                                      : (kp.tv[c4] ? (float)fx_unbias((unsigned)Si[c4], (unsigned)cnt_i) * inv4[c4] : 0.0f);
-                }
+                for (int c4 = 0; c4 < 4; ++c4) S4[c4] = (float)(int)((unsigned)Si[c4] - bias_off) * inv4[c4];
+                if (kp.tq == G::CQ) S4[G::CI] = (float)cnt_i;
                 parity ^= 1;
-                kp.template finish<(NW > 1)>(p, i, round, S4, merge_point, send_point, det, sync_now, wave == 0);
+                kp.template finish<(NW > 1)>(p, i, round, S4, (float)cnt_i, merge_point, send_point, det, sync_now, wave == 0);
 
                 // advance the clock
                 xb = xbn;
